@@ -1,0 +1,226 @@
+"""Pins for the oracle's selection functions (Eq. 1, Eq. 3, Eq. 4, stage-2 top-p).
+
+Each test ties a function to something other than itself: a closed form, an
+invariant, a library witness or brute force over all possibilities."""
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import d2cache_oracle as O
+from paper_2509_23094_amd import workloads as W
+
+
+# ------------------------------------------------------------------ Eq. 1
+def test_confidence_constant_logits_power_of_two():
+    for V in (2, 16, 1024):
+        s, x = O.confidence(np.full((3, V), 1.7))
+        assert np.all(x == 0)                       # tie -> lowest index
+        assert np.all(s == 1.0 / V)                 # exactly representable
+
+
+def test_confidence_one_hot_limit():
+    z = np.zeros((2, 50)); z[0, 17] = 80.0; z[1, 49] = 60.0
+    s, x = O.confidence(z)
+    assert list(x) == [17, 49]
+    assert abs(s[0] - 1.0) < 1e-30 + 49 * math.exp(-80.0) * 1.01
+    assert abs(s[1] - 1.0 / (1.0 + 49 * math.exp(-60.0))) < 1e-15
+
+
+def test_confidence_two_level_closed_form():
+    # a of the V logits equal t, the rest 0  =>  s = 1 / (a + (V-a) e^{-t})
+    V, a, t = 37, 5, 2.5
+    z = np.zeros((1, V)); z[0, [3, 8, 9, 20, 36]] = t
+    s, x = O.confidence(z)
+    assert x[0] == 3
+    assert abs(s[0] - 1.0 / (a + (V - a) * math.exp(-t))) < 1e-15
+
+
+def test_confidence_matches_library_softmax():
+    z = W.logits_rows(3, 7, 999).astype(np.float64)
+    s, x = O.confidence(z)
+    p = torch.softmax(torch.from_numpy(z), dim=-1)
+    ps, px = p.max(dim=-1)
+    np.testing.assert_array_equal(x, px.numpy())
+    np.testing.assert_allclose(s, ps.numpy(), rtol=1e-13)
+
+
+def test_confidence_shift_invariance_and_tie():
+    z = W.logits_rows(4, 5, 64).astype(np.float64)
+    z[:, 40] = z[:, 11] = z.max(axis=1) + 1.0       # two equal maxima: 11 must win
+    s1, x1 = O.confidence(z)
+    s2, x2 = O.confidence(z + 123.0)
+    assert np.all(x1 == 11) and np.all(x2 == 11)
+    np.testing.assert_allclose(s1, s2, rtol=1e-12)
+
+
+# ------------------------------------------------------------------ Eq. 3
+def test_density_poisson_closed_form():
+    # all tokens known except i, i far from both ends: the sum over all integer
+    # offsets of a Gaussian is sigma*sqrt(2 pi) (Poisson summation; the
+    # correction term is exp(-2 pi^2 sigma^2) ~ 0), minus the j = i term.
+    for sigma in (10.0, 4.0):
+        L = int(2 * 14 * sigma) + 1
+        i = L // 2
+        is_masked = np.zeros(L, bool); is_masked[i] = True
+        D = O.certainty_density(is_masked, sigma)
+        assert abs(D[i] - (sigma * math.sqrt(2 * math.pi) - 1.0)) < 1e-12
+    assert abs(O.certainty_density(is_masked, 4.0)[i] - 9.02651309852) < 1e-9
+    is_masked = np.zeros(401, bool); is_masked[200] = True
+    assert abs(O.certainty_density(is_masked, 10.0)[200] - 24.0662827463) < 1e-9
+
+
+def test_density_brute_force_loops():
+    sigma = 3.0
+    is_masked = W.random_mask(1, 40, 10, 0.4).astype(bool)
+    D = O.certainty_density(is_masked, sigma)
+    for i in range(40):
+        ref = 0.0
+        for j in range(40):
+            if not is_masked[j]:
+                ref += math.exp(-abs(i - j) ** 2 / (2 * sigma ** 2))
+        assert abs(D[i] - ref) < 1e-12
+
+
+def test_density_reversal_monotone_and_wide_sigma():
+    is_masked = W.random_mask(2, 64, 16, 0.3).astype(bool)
+    D = O.certainty_density(is_masked, 10.0)
+    Dr = O.certainty_density(is_masked[::-1].copy(), 10.0)
+    np.testing.assert_allclose(D, Dr[::-1], rtol=1e-14)
+    more_known = is_masked.copy(); more_known[np.flatnonzero(is_masked)[:5]] = False
+    assert np.all(O.certainty_density(more_known, 10.0) >= D - 1e-15)
+    # a very wide Gaussian counts the known tokens (Sec. 4.1: D converges across i)
+    wide = O.certainty_density(is_masked, 1e6)
+    np.testing.assert_allclose(wide, np.full(64, (~is_masked).sum()), rtol=1e-8)
+
+
+def test_density_single_known_token_is_the_kernel():
+    is_masked = np.ones(50, bool); is_masked[20] = False
+    D = O.certainty_density(is_masked, 10.0)
+    for i in (0, 19, 20, 33, 49):
+        assert abs(D[i] - math.exp(-(i - 20) ** 2 / 200.0)) < 1e-15
+
+
+# ------------------------------------------------------------------ Eq. 4
+def _rank_count_topk(score, cand, k):
+    out = []
+    for i in cand:
+        rank = 0
+        for j in cand:
+            if score[j] > score[i] or (score[j] == score[i] and j < i):
+                rank += 1
+        if rank < k:
+            out.append(i)
+    return sorted(out)
+
+
+def test_topk_takes_all_when_k_large_and_lowest_on_ties():
+    cand = np.array([3, 5, 9, 12, 20])
+    sc = np.zeros(32, np.float32)
+    assert list(O.top_k_select(sc, cand, 99)) == [3, 5, 9, 12, 20]
+    assert list(O.top_k_select(sc, cand, 2)) == [3, 5]
+    assert list(O.top_k_select(sc, cand, 0)) == []
+    assert list(O.top_k_select(sc, np.zeros(0, int), 4)) == []
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_topk_brute_force_rank_count(seed):
+    n = 50
+    sc = W.random_scores(seed, n)
+    sc[::7] = sc[3]                                  # plant exact ties
+    cand = np.flatnonzero(W.random_mask(seed, n, 5, 0.5))
+    for k in (1, 4, 17):
+        assert list(O.top_k_select(sc, cand, k)) == _rank_count_topk(sc, list(cand), k)
+
+
+# ------------------------------------------------------------------ stage 2
+def _brute_top_p(c32, cand, p32):
+    """All prefixes of the (c desc, index asc) order, exact rational arithmetic."""
+    order = sorted(cand, key=lambda j: (-float(c32[j]), j))
+    q = [int(math.floor(Fraction(float(c32[j])) * 2 ** 32)) for j in order]
+    total = sum(q)
+    thr = math.floor(float(np.float32(p32)) * float(total))
+    for r in range(1, len(order) + 1):
+        if sum(q[:r]) > thr:
+            return sorted(order[:r])
+    return sorted(order)
+
+
+def test_topp_equal_candidates():
+    c = np.ones(40, np.float32)
+    cand = np.arange(5, 35)
+    n = len(cand)
+    for p in (0.1, 0.25, 0.5, 0.9):
+        got = O.top_p_select(c, cand, p)
+        assert list(got) == list(cand[: int(math.floor(float(np.float32(p)) * n)) + 1])
+
+
+def test_topp_all_dominant_empty():
+    c = np.ones(20, np.float32)
+    cand = np.arange(20)
+    assert list(O.top_p_select(c, cand, 1.0)) == list(range(20))
+    assert list(O.top_p_select(c, cand, 1.5)) == list(range(20))
+    c2 = c.copy(); c2[13] = 100.0
+    assert list(O.top_p_select(c2, cand, 0.5)) == [13]
+    assert list(O.top_p_select(c2, np.zeros(0, int), 0.5)) == []
+    assert list(O.top_p_select(c, cand, 0.0)) == [0]          # prefix r >= 1, ties -> lowest
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_topp_brute_force_prefixes(seed):
+    L = 60
+    c = W.skewed_influence(seed, L) if seed % 2 else W.random_scores(seed, L) + np.float32(0.01)
+    c[5] = c[40] = c[41]                              # exact ties
+    cand = np.flatnonzero(W.random_mask(seed + 10, L, 8, 0.5) == 0)
+    for p in (0.05, 0.1, 0.5, 0.9, 0.999):
+        assert list(O.top_p_select(c, cand, p)) == _brute_top_p(c, list(cand), p)
+
+
+def test_topp_mass_property():
+    # the selected set's share exceeds p and dropping its smallest member does not
+    L = 200
+    c = W.skewed_influence(7, L)
+    cand = np.arange(L)
+    for p in (0.1, 0.6):
+        u = O.top_p_select(c, cand, p)
+        tot = float(c.astype(np.float64).sum())
+        share = float(c[u].astype(np.float64).sum()) / tot
+        assert share > p - 1e-6
+        assert share - float(c[u].min()) / tot <= p + 1e-6
+        assert c[u].min() >= np.delete(c, u).max()
+
+
+# ------------------------------------------------------------------ blocks, select
+def test_current_block():
+    m = np.zeros(100, bool); m[20:] = True
+    assert O.current_block(m, 20, 32) == (20, 52)
+    m[20:52] = False
+    assert O.current_block(m, 20, 32) == (52, 84)
+    m[52:84] = False
+    assert O.current_block(m, 20, 32) == (84, 100)            # ragged last block
+    m[:] = False
+    assert O.current_block(m, 20, 32) == (100, 100)
+    m[60] = True
+    assert O.current_block(m, 20, 80) == (20, 100)            # NAR: one block
+
+
+def test_select_contract():
+    L, P = 96, 32
+    is_masked = W.random_mask(5, L, P, 0.3).astype(bool)
+    conf = W.random_scores(5, L)
+    c = W.skewed_influence(5, L)
+    prm = O.Params(sigma=10.0, k=8, p=0.3, block_len=32, n_unmask=2)
+    sel = O.select(prm, is_masked, P, conf, c)
+    lo, hi = sel["block"]
+    assert all(lo <= i < hi and is_masked[i] for i in sel["mstar"])
+    assert set(sel["decode"]) <= set(sel["mstar"])             # I_t within M* when n_u <= k
+    assert all(not is_masked[j] for j in sel["u"])             # R4: known tokens only
+    assert list(sel["s_next"]) == sorted(set(sel["mstar"]) | set(sel["u"]))
+    # cand_mode 1: everything except M*
+    sel1 = O.select(O.Params(k=8, p=1.0, cand_mode=1), is_masked, P, conf, c)
+    assert list(sel1["s_next"]) == list(range(L))
+    # select-all switch: k >= |M|, p = 1, one block
+    sel2 = O.select(O.Params(k=L, p=1.0, block_len=L), is_masked, P, conf, c)
+    assert list(sel2["s_next"]) == list(range(L))
