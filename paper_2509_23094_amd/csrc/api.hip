@@ -1,0 +1,396 @@
+// C ABI of the d2Cache selective-refresh step (see include/d2c.h): argument
+// validation, workspace ownership and the order of kernel launches.  No
+// arithmetic of the method lives here.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/d2c.h"
+#include "internal.h"
+
+using namespace d2c;
+
+struct d2c_ctx {
+  d2c_dims dims{};
+  int device = 0;
+  // borrowed weights
+  const void* tok_emb = nullptr;
+  const float* final_norm = nullptr;
+  const void* lm_head = nullptr;
+  std::vector<const float*> attn_norm, bqkv, ffn_norm;
+  std::vector<const void*> wqkv, wo, w_gate_up, w_down;
+  // workspace (device)
+  std::vector<void*> allocs;
+  int64_t ws_bytes = 0;
+  float* hidden = nullptr;      // [max_seq, d]
+  void* a_norm = nullptr;       // T [max_seq, d]
+  void* q = nullptr;            // T [max_seq, d_q]
+  void* attn_o = nullptr;       // T [max_seq, d_q]
+  void* act = nullptr;          // T [max_seq, F]
+  float* lse = nullptr;         // [H, max_seq]
+  float* partial = nullptr;     // split partials of the current projection
+  size_t partial_floats = 0;
+  float* abar = nullptr;        // [max_seq, max_seq]
+  float* roll[2] = {nullptr, nullptr};
+  void* head_a = nullptr;       // T [head_rows, d]
+  float* logits = nullptr;      // [head_rows, vocab]
+  int head_rows = 0;
+  float* rope_cos = nullptr;    // [max_seq, head_dim/2]
+  float* rope_sin = nullptr;
+  int32_t* counts_host = nullptr;   // pinned
+  int counts_host_cap = 0;
+  std::string err;
+};
+
+namespace {
+
+std::string g_init_err;
+
+int fail(d2c_ctx* ctx, int code, const std::string& msg) {
+  if (ctx) ctx->err = msg; else g_init_err = msg;
+  return code;
+}
+
+#define D2C_HIP(ctx, expr)                                                                  \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess)                                                                   \
+      return fail(ctx, D2C_EHIP, std::string(#expr) + ": " + hipGetErrorString(e_));        \
+  } while (0)
+
+template <typename P>
+int ws_alloc(d2c_ctx* ctx, P** out, size_t bytes) {
+  void* p = nullptr;
+  if (bytes == 0) bytes = 256;
+  hipError_t e = hipMalloc(&p, bytes);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(ctx, D2C_ENOMEM, "hipMalloc of " + std::to_string(bytes) + " bytes failed: " + hipGetErrorString(e));
+  }
+  ctx->allocs.push_back(p);
+  ctx->ws_bytes += (int64_t)bytes;
+  *out = reinterpret_cast<P*>(p);
+  return D2C_OK;
+}
+
+size_t tsize(const d2c_ctx* c) { return dtype_size(c->dims.dtype); }
+int d_q(const d2c_ctx* c) { return c->dims.n_heads * c->dims.head_dim; }
+int d_kv(const d2c_ctx* c) { return c->dims.n_kv_heads * c->dims.head_dim; }
+
+// One projection on m rows: P = A W^T as split partials in the context's buffer.
+int project(d2c_ctx* c, const void* A, int lda, const void* W, int m, int N, int K, GemmPlan* plan_out,
+            size_t* stride_out, hipStream_t st, bool single_split = false, float* dst = nullptr) {
+  GemmPlan pl = plan_gemm(c->dims.dtype, m, N, K, single_split);
+  const size_t stride = (size_t)m * N;
+  float* P = dst ? dst : c->partial;
+  if (!dst && stride * pl.splits > c->partial_floats) return fail(c, D2C_ESHAPE, "projection partials exceed workspace");
+  D2C_HIP(c, launch_gemm(c->dims.dtype, pl, A, lda, W, K, P, N, stride, m, N, K, st));
+  *plan_out = pl;
+  *stride_out = stride;
+  return D2C_OK;
+}
+
+// One block on m compact rows.  a_ready: ctx->a_norm already holds RMSNorm(hidden) * attn_norm[layer].
+// next_gain: when non-null the last kernel also leaves RMSNorm(hidden) * next_gain in ctx->a_norm.
+int layer_impl(d2c_ctx* c, int layer, float* hidden, const int32_t* idx, int m, void* k_cache, void* v_cache, int L,
+               float* abar, const float* roll_in, float* roll_out, bool a_ready, const float* next_gain,
+               hipStream_t st) {
+  const d2c_dims& D = c->dims;
+  const int dt = D.dtype, d = D.d_model, dq = d_q(c), dkv = d_kv(c), F = D.d_ffn;
+  GemmPlan pl;
+  size_t stride;
+  int rc;
+  if (!a_ready)
+    D2C_HIP(c, launch_add_norm(dt, hidden, nullptr, 0, 0, d, m, d, c->attn_norm[layer], D.rms_eps, c->a_norm, st));
+  if ((rc = project(c, c->a_norm, d, c->wqkv[layer], m, dq + 2 * dkv, d, &pl, &stride, st)) != D2C_OK) return rc;
+  D2C_HIP(c, launch_qkv_rope_scatter(dt, c->partial, pl.splits, stride, dq + 2 * dkv,
+                                     c->bqkv.empty() ? nullptr : c->bqkv[layer], idx, m, D.n_heads, D.n_kv_heads,
+                                     D.head_dim, c->rope_cos, c->rope_sin, c->q, k_cache, v_cache, st));
+  D2C_HIP(c, launch_attention(dt, c->q, k_cache, v_cache, m, L, D.n_heads, D.n_kv_heads, D.head_dim, c->attn_o,
+                              c->lse, abar, st));
+  if (abar && roll_out) D2C_HIP(c, launch_rollout(abar, roll_in, roll_out, idx, m, L, layer == 0, st));
+  if ((rc = project(c, c->attn_o, dq, c->wo[layer], m, d, dq, &pl, &stride, st)) != D2C_OK) return rc;
+  D2C_HIP(c, launch_add_norm(dt, hidden, c->partial, pl.splits, stride, d, m, d, c->ffn_norm[layer], D.rms_eps,
+                             c->a_norm, st));
+  if ((rc = project(c, c->a_norm, d, c->w_gate_up[layer], m, 2 * F, d, &pl, &stride, st)) != D2C_OK) return rc;
+  D2C_HIP(c, launch_swiglu(dt, c->partial, pl.splits, stride, 2 * F, m, F, c->act, st));
+  if ((rc = project(c, c->act, F, c->w_down[layer], m, d, F, &pl, &stride, st)) != D2C_OK) return rc;
+  D2C_HIP(c, launch_add_norm(dt, hidden, c->partial, pl.splits, stride, d, m, d, next_gain, D.rms_eps,
+                             next_gain ? c->a_norm : nullptr, st));
+  return D2C_OK;
+}
+
+int check_idx_host(d2c_ctx* c, const int32_t* idx_host, int m, int L) {
+  if (m < 0 || L <= 0 || m > L) return fail(c, D2C_EINVAL, "need 0 <= m <= L");
+  if (L > c->dims.max_seq) return fail(c, D2C_ESHAPE, "L exceeds max_seq of the context");
+  if (m > 0 && !idx_host) return fail(c, D2C_EINVAL, "idx_host is null");
+  for (int r = 0; r < m; ++r) {
+    if (idx_host[r] < 0 || idx_host[r] >= L) return fail(c, D2C_EINVAL, "idx out of range");
+    if (r && idx_host[r] <= idx_host[r - 1]) return fail(c, D2C_EINVAL, "idx must be ascending and distinct");
+  }
+  return D2C_OK;
+}
+
+int check_params(d2c_ctx* c, const d2c_params* p) {
+  if (!p) return fail(c, D2C_EINVAL, "params is null");
+  if (!(p->sigma > 0.f) || p->k < 0 || p->block_len <= 0 || p->n_unmask < 0 || !(p->p >= 0.f) ||
+      (p->cand_mode != 0 && p->cand_mode != 1))
+    return fail(c, D2C_EINVAL, "bad selection parameters");
+  return D2C_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int d2c_init(const d2c_dims* dims, const d2c_weights* w, d2c_ctx** out) {
+  if (!dims || !w || !out) return fail(nullptr, D2C_EINVAL, "null argument");
+  const d2c_dims& D = *dims;
+  if (D.n_layers <= 0 || D.d_model <= 0 || D.n_heads <= 0 || D.n_kv_heads <= 0 || D.head_dim <= 0 || D.d_ffn <= 0 ||
+      D.vocab <= 0 || D.max_seq <= 0)
+    return fail(nullptr, D2C_EINVAL, "dimensions must be positive");
+  if (D.dtype != D2C_F32 && D.dtype != D2C_BF16) return fail(nullptr, D2C_EINVAL, "dtype must be D2C_F32 or D2C_BF16");
+  if (D.n_heads % D.n_kv_heads) return fail(nullptr, D2C_EINVAL, "n_heads must be a multiple of n_kv_heads");
+  if (D.head_dim % 2) return fail(nullptr, D2C_EINVAL, "head_dim must be even");
+  if (D.dtype == D2C_BF16 && D.head_dim != 64 && D.head_dim != 128)
+    return fail(nullptr, D2C_ESHAPE, "bf16 attention supports head_dim 64 or 128");
+  const int e = D.dtype == D2C_BF16 ? 8 : 4;
+  if (D.d_model % e || D.d_ffn % e || (D.n_heads * D.head_dim) % e)
+    return fail(nullptr, D2C_ESHAPE, "d_model, d_ffn and n_heads*head_dim must be multiples of 16 bytes of T");
+  if (D.max_seq > select_max_len()) return fail(nullptr, D2C_ESHAPE, "max_seq exceeds the selection kernel's limit");
+  if (D.mask_id < 0 || D.mask_id >= D.vocab) return fail(nullptr, D2C_EINVAL, "mask_id outside the vocabulary");
+  if (!w->tok_emb || !w->final_norm || !w->lm_head || !w->attn_norm || !w->wqkv || !w->wo || !w->ffn_norm ||
+      !w->w_gate_up || !w->w_down)
+    return fail(nullptr, D2C_EINVAL, "null weight pointer");
+  for (int l = 0; l < D.n_layers; ++l)
+    if (!w->attn_norm[l] || !w->wqkv[l] || !w->wo[l] || !w->ffn_norm[l] || !w->w_gate_up[l] || !w->w_down[l] ||
+        (w->bqkv && !w->bqkv[l]))
+      return fail(nullptr, D2C_EINVAL, "null per-layer weight pointer");
+
+  d2c_ctx* c = new (std::nothrow) d2c_ctx();
+  if (!c) return fail(nullptr, D2C_ENOMEM, "out of host memory");
+  c->dims = D;
+  c->tok_emb = w->tok_emb; c->final_norm = w->final_norm; c->lm_head = w->lm_head;
+  for (int l = 0; l < D.n_layers; ++l) {
+    c->attn_norm.push_back(w->attn_norm[l]); c->wqkv.push_back(w->wqkv[l]); c->wo.push_back(w->wo[l]);
+    c->ffn_norm.push_back(w->ffn_norm[l]); c->w_gate_up.push_back(w->w_gate_up[l]); c->w_down.push_back(w->w_down[l]);
+    if (w->bqkv) c->bqkv.push_back(w->bqkv[l]);
+  }
+  int rc = D2C_OK;
+  auto bail = [&](int code) { std::string m = c->err; d2c_destroy(c); g_init_err = m; return code; };
+  if (hipGetDevice(&c->device) != hipSuccess) return bail(fail(c, D2C_EHIP, "hipGetDevice failed"));
+
+  const size_t ts = tsize(c), Lm = (size_t)D.max_seq, d = (size_t)D.d_model, dq = (size_t)d_q(c), F = (size_t)D.d_ffn;
+  // largest split-partial footprint over every row count the context can see
+  const int shapes[4][2] = {{d_q(c) + 2 * d_kv(c), D.d_model}, {D.d_model, d_q(c)}, {2 * D.d_ffn, D.d_model},
+                            {D.d_model, D.d_ffn}};
+  size_t pf = 0;
+  for (int m = 1; m <= D.max_seq; ++m)
+    for (auto& s : shapes) {
+      // up to 128 rows leave room for the largest split count; beyond that the planner's choice is taken
+      GemmPlan pl = plan_gemm(D.dtype, m, s[0], s[1]);
+      pf = std::max(pf, (size_t)(m <= 128 ? 8 : pl.splits) * m * s[0]);
+    }
+  c->partial_floats = pf;
+  c->head_rows = (int)std::min<size_t>(Lm, 256);
+  if ((rc = ws_alloc(c, &c->hidden, Lm * d * 4)) || (rc = ws_alloc(c, &c->a_norm, Lm * d * ts)) ||
+      (rc = ws_alloc(c, &c->q, Lm * dq * ts)) || (rc = ws_alloc(c, &c->attn_o, Lm * dq * ts)) ||
+      (rc = ws_alloc(c, &c->act, Lm * F * ts)) || (rc = ws_alloc(c, &c->lse, (size_t)D.n_heads * Lm * 4)) ||
+      (rc = ws_alloc(c, &c->partial, pf * 4)) || (rc = ws_alloc(c, &c->abar, Lm * Lm * 4)) ||
+      (rc = ws_alloc(c, &c->roll[0], Lm * Lm * 4)) || (rc = ws_alloc(c, &c->roll[1], Lm * Lm * 4)) ||
+      (rc = ws_alloc(c, &c->head_a, (size_t)c->head_rows * d * ts)) ||
+      (rc = ws_alloc(c, &c->logits, (size_t)c->head_rows * D.vocab * 4)) ||
+      (rc = ws_alloc(c, &c->rope_cos, Lm * (D.head_dim / 2) * 4)) ||
+      (rc = ws_alloc(c, &c->rope_sin, Lm * (D.head_dim / 2) * 4)))
+    return bail(rc);
+  c->counts_host_cap = 64;
+  if (hipHostMalloc((void**)&c->counts_host, sizeof(int32_t) * D2C_N_COUNTS * c->counts_host_cap) != hipSuccess)
+    return bail(fail(c, D2C_ENOMEM, "hipHostMalloc failed"));
+  hipError_t e2 = launch_rope_table(c->rope_cos, c->rope_sin, D.max_seq, D.head_dim, D.rope_theta, nullptr);
+  if (e2 == hipSuccess) e2 = hipStreamSynchronize(nullptr);
+  if (e2 != hipSuccess) return bail(fail(c, D2C_EHIP, std::string("rope table: ") + hipGetErrorString(e2)));
+  *out = c;
+  return D2C_OK;
+}
+
+int d2c_destroy(d2c_ctx* c) {
+  if (!c) return D2C_OK;
+  for (void* p : c->allocs) (void)hipFree(p);
+  if (c->counts_host) (void)hipHostFree(c->counts_host);
+  delete c;
+  return D2C_OK;
+}
+
+const char* d2c_last_error(const d2c_ctx* c) { return c ? c->err.c_str() : g_init_err.c_str(); }
+
+int64_t d2c_workspace_bytes(const d2c_ctx* c) { return c ? c->ws_bytes : 0; }
+
+int d2c_set_tunable(const char* name, int32_t value) {
+  if (!name) return D2C_EINVAL;
+  Tunables& t = tunables();
+  if (!strcmp(name, "gemm_target_wgs")) t.gemm_target_wgs = value;
+  else if (!strcmp(name, "gemm_max_splits")) t.gemm_max_splits = std::max(1, std::min(8, (int)value));
+  else if (!strcmp(name, "gemm_nt_big_n")) t.gemm_nt_big_n = value;
+  else return D2C_EINVAL;
+  return D2C_OK;
+}
+
+int d2c_seq_reset(d2c_ctx* c, d2c_seq_state* s, void* stream) {
+  if (!c || !s) return D2C_EINVAL;
+  if (!s->tokens || !s->is_masked || !s->k_cache || !s->v_cache || !s->conf || !s->pred || !s->s_idx || !s->s_rows ||
+      !s->influence || !s->mstar || !s->u_set || !s->decode_idx || !s->counts)
+    return fail(c, D2C_EINVAL, "null buffer in sequence state");
+  if (s->L <= 0 || s->L > c->dims.max_seq) return fail(c, D2C_ESHAPE, "L outside (0, max_seq]");
+  if (s->prompt_len < 0 || s->prompt_len > s->L) return fail(c, D2C_EINVAL, "prompt_len outside [0, L]");
+  hipStream_t st = (hipStream_t)stream;
+  D2C_HIP(c, launch_seq_reset(s->is_masked, s->L, s->s_idx, s->s_rows, s->conf, s->pred, s->counts, st));
+  D2C_HIP(c, hipMemcpyAsync(c->counts_host, s->counts, sizeof(int32_t) * D2C_N_COUNTS, hipMemcpyDeviceToHost, st));
+  D2C_HIP(c, hipStreamSynchronize(st));
+  s->n_s = c->counts_host[D2C_CNT_S];
+  s->n_rows = c->counts_host[D2C_CNT_NEXT_ROWS];
+  s->n_masked = c->counts_host[D2C_CNT_MASKED];
+  s->step = 0;
+  return D2C_OK;
+}
+
+int d2c_select(d2c_ctx* c, const d2c_params* p, const float* logits, const int32_t* logit_pos, int32_t n_rows,
+               int32_t* tokens, uint8_t* is_masked, int32_t L, int32_t prompt_len, float* conf, int32_t* pred,
+               const float* influence, int32_t* mstar, int32_t* u_set, int32_t* decode_idx, int32_t* s_next,
+               int32_t* s_rows_next, int32_t* counts, float* score_out, void* stream) {
+  if (!c) return D2C_EINVAL;
+  int rc = check_params(c, p);
+  if (rc) return rc;
+  if (!tokens || !is_masked || !conf || !pred || !influence || !mstar || !u_set || !decode_idx || !s_next ||
+      !s_rows_next || !counts)
+    return fail(c, D2C_EINVAL, "null buffer");
+  if (n_rows < 0 || (n_rows > 0 && (!logits || !logit_pos))) return fail(c, D2C_EINVAL, "logits / logit_pos missing");
+  if (L <= 0 || L > c->dims.max_seq) return fail(c, D2C_ESHAPE, "L outside (0, max_seq]");
+  if (prompt_len < 0 || prompt_len > L) return fail(c, D2C_EINVAL, "prompt_len outside [0, L]");
+  hipStream_t st = (hipStream_t)stream;
+  D2C_HIP(c, launch_confidence(logits, logit_pos, nullptr, n_rows, c->dims.vocab, conf, pred, st));
+  SelectArgs a{p->sigma, p->k, p->p, p->block_len, p->n_unmask, p->cand_mode, tokens, is_masked, L, prompt_len,
+               conf, pred, influence, mstar, u_set, decode_idx, s_next, s_rows_next, counts, score_out};
+  D2C_HIP(c, launch_select(a, st));
+  return D2C_OK;
+}
+
+int d2c_refresh_layer(d2c_ctx* c, int32_t layer, float* hidden, const int32_t* idx, const int32_t* idx_host,
+                      int32_t m, void* k_cache, void* v_cache, int32_t L, float* attn_avg, float* rollout,
+                      void* stream) {
+  if (!c) return D2C_EINVAL;
+  if (layer < 0 || layer >= c->dims.n_layers) return fail(c, D2C_EINVAL, "layer out of range");
+  int rc = check_idx_host(c, idx_host, m, L);
+  if (rc) return rc;
+  if (m == 0) return D2C_OK;
+  if (!hidden || !idx || !k_cache || !v_cache) return fail(c, D2C_EINVAL, "null buffer");
+  if ((attn_avg == nullptr) != (rollout == nullptr))
+    return fail(c, D2C_EINVAL, "attn_avg and rollout must both be given or both be null");
+  hipStream_t st = (hipStream_t)stream;
+  rc = layer_impl(c, layer, hidden, idx, m, k_cache, v_cache, L, attn_avg, rollout, rollout ? c->roll[0] : nullptr,
+                  false, nullptr, st);
+  if (rc) return rc;
+  if (rollout) D2C_HIP(c, launch_copy_f32(rollout, c->roll[0], (size_t)m * L, st));
+  return D2C_OK;
+}
+
+int d2c_attention(d2c_ctx* c, const void* q, const int32_t* idx, int32_t m, const void* new_k, const void* new_v,
+                  void* k_cache, void* v_cache, int32_t L, void* out, float* attn_avg, void* stream) {
+  if (!c) return D2C_EINVAL;
+  if (m < 0 || L <= 0 || m > c->dims.max_seq) return fail(c, D2C_EINVAL, "bad m or L");
+  if (L > c->dims.max_seq) return fail(c, D2C_ESHAPE, "L exceeds max_seq of the context");
+  if (m == 0) return D2C_OK;
+  if (!q || !k_cache || !v_cache || !out) return fail(c, D2C_EINVAL, "null buffer");
+  if ((new_k == nullptr) != (new_v == nullptr)) return fail(c, D2C_EINVAL, "new_k and new_v go together");
+  if (new_k && !idx) return fail(c, D2C_EINVAL, "idx is null");
+  hipStream_t st = (hipStream_t)stream;
+  const d2c_dims& D = c->dims;
+  if (new_k) {
+    D2C_HIP(c, launch_scatter_rows(D.dtype, new_k, idx, m, d_kv(c), k_cache, st));
+    D2C_HIP(c, launch_scatter_rows(D.dtype, new_v, idx, m, d_kv(c), v_cache, st));
+  }
+  D2C_HIP(c, launch_attention(D.dtype, q, k_cache, v_cache, m, L, D.n_heads, D.n_kv_heads, D.head_dim, out, c->lse,
+                              attn_avg, st));
+  return D2C_OK;
+}
+
+int d2c_influence(d2c_ctx* c, const float* rollout, const int32_t* idx, int32_t m, int32_t L, float* influence,
+                  void* stream) {
+  if (!c) return D2C_EINVAL;
+  if (m < 0 || L <= 0 || m > L || !influence || (m > 0 && (!rollout || !idx))) return fail(c, D2C_EINVAL, "bad argument");
+  D2C_HIP(c, launch_influence(rollout, idx, m, L, influence, (hipStream_t)stream));
+  return D2C_OK;
+}
+
+int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch, void* stream) {
+  if (!c) return D2C_EINVAL;
+  int rc = check_params(c, p);
+  if (rc) return rc;
+  if (!seqs || batch <= 0 || batch > c->counts_host_cap) return fail(c, D2C_EINVAL, "bad batch");
+  const d2c_dims& D = c->dims;
+  for (int b = 0; b < batch; ++b) {
+    const d2c_seq_state& s = seqs[b];
+    if (!s.tokens || !s.is_masked || !s.k_cache || !s.v_cache || !s.conf || !s.pred || !s.s_idx || !s.s_rows ||
+        !s.influence || !s.mstar || !s.u_set || !s.decode_idx || !s.counts)
+      return fail(c, D2C_EINVAL, "null buffer in sequence state");
+    if (s.L <= 0 || s.L > D.max_seq) return fail(c, D2C_ESHAPE, "L outside (0, max_seq]");
+    if (s.n_s < 0 || s.n_s > s.L || s.n_rows < 0 || s.n_rows > s.n_s) return fail(c, D2C_EINVAL, "bad set sizes");
+  }
+  hipStream_t st = (hipStream_t)stream;
+  const int dt = D.dtype, d = D.d_model;
+  const size_t ts = tsize(c), cache_layer = (size_t)d_kv(c) * ts;
+  for (int b = 0; b < batch; ++b) {
+    d2c_seq_state& s = seqs[b];
+    int32_t* ch = c->counts_host + (size_t)b * D2C_N_COUNTS;
+    if (s.n_masked == 0) { ch[D2C_CNT_S] = -1; continue; }
+    const int m = s.n_s, L = s.L;
+    float* roll_final = nullptr;
+    if (m > 0) {
+      D2C_HIP(c, launch_embed_norm(dt, c->tok_emb, s.tokens, s.s_idx, m, d, c->attn_norm[0], D.rms_eps, c->hidden,
+                                   c->a_norm, st));
+      for (int l = 0; l < D.n_layers; ++l) {
+        char* kc = (char*)s.k_cache + (size_t)l * L * cache_layer;
+        char* vc = (char*)s.v_cache + (size_t)l * L * cache_layer;
+        rc = layer_impl(c, l, c->hidden, s.s_idx, m, kc, vc, L, c->abar, c->roll[l & 1], c->roll[(l + 1) & 1], true,
+                        l + 1 < D.n_layers ? c->attn_norm[l + 1] : nullptr, st);
+        if (rc) return rc;
+      }
+      roll_final = c->roll[D.n_layers & 1];
+      if (s.hidden_out)
+        D2C_HIP(c, hipMemcpyAsync(s.hidden_out, c->hidden, (size_t)m * d * 4, hipMemcpyDeviceToDevice, st));
+    }
+    D2C_HIP(c, launch_influence(roll_final, s.s_idx, m, L, s.influence, st));
+    // Eq. 1 on the rows of S_t that are still masked, head_rows rows at a time
+    for (int r0 = 0; r0 < s.n_rows; r0 += c->head_rows) {
+      const int nr = std::min(c->head_rows, s.n_rows - r0);
+      D2C_HIP(c, launch_gather_norm(dt, c->hidden, s.s_rows + r0, nr, d, c->final_norm, D.rms_eps, c->head_a, st));
+      GemmPlan pl;
+      size_t stride;
+      if ((rc = project(c, c->head_a, d, c->lm_head, nr, D.vocab, d, &pl, &stride, st, true, c->logits))) return rc;
+      D2C_HIP(c, launch_confidence(c->logits, s.s_rows + r0, s.s_idx, nr, D.vocab, s.conf, s.pred, st));
+      if (s.logits_out)
+        D2C_HIP(c, hipMemcpyAsync(s.logits_out + (size_t)r0 * D.vocab, c->logits, (size_t)nr * D.vocab * 4,
+                                  hipMemcpyDeviceToDevice, st));
+    }
+    SelectArgs a{p->sigma, p->k, p->p, p->block_len, p->n_unmask, p->cand_mode, s.tokens, s.is_masked, L,
+                 s.prompt_len, s.conf, s.pred, s.influence, s.mstar, s.u_set, s.decode_idx, s.s_idx, s.s_rows,
+                 s.counts, s.score};
+    D2C_HIP(c, launch_select(a, st));
+    D2C_HIP(c, hipMemcpyAsync(ch, s.counts, sizeof(int32_t) * D2C_N_COUNTS, hipMemcpyDeviceToHost, st));
+  }
+  D2C_HIP(c, hipStreamSynchronize(st));
+  for (int b = 0; b < batch; ++b) {
+    const int32_t* ch = c->counts_host + (size_t)b * D2C_N_COUNTS;
+    if (ch[D2C_CNT_S] < 0) continue;
+    seqs[b].n_s = ch[D2C_CNT_S];
+    seqs[b].n_rows = ch[D2C_CNT_NEXT_ROWS];
+    seqs[b].n_masked = ch[D2C_CNT_MASKED];
+    seqs[b].step += 1;
+  }
+  return D2C_OK;
+}
+
+}  // extern "C"

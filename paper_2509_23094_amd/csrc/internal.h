@@ -1,0 +1,88 @@
+// Host-side launch interface between the C ABI layer and the kernel files.
+// Every launcher checks its own shape assumptions and returns hipError_t.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace d2c {
+
+enum DType { kF32 = 0, kBF16 = 1 };
+
+inline size_t dtype_size(int dt) { return dt == kBF16 ? 2 : 4; }
+
+// Tunables (defaults chosen by measurement; d2c_set_tunable changes them).
+struct Tunables {
+  int gemm_target_wgs = 512;   // aim for at least this many workgroups per GEMM
+  int gemm_max_splits = 8;
+  int gemm_nt_big_n = 16384;   // N above this uses two column tiles per wave
+};
+Tunables& tunables();
+
+// ---- GEMM on a ragged handful of rows: P[s] = A[m,K] * W[N,K]^T over the k-range of split s
+struct GemmPlan {
+  int mt;        // 16-row tiles per workgroup (1..8)
+  int nt;        // 16-column tiles per wave (1 or 2)
+  int splits;    // k splits (partials to be summed by the consumer)
+  int k_per_split;
+  int row_chunks;
+};
+GemmPlan plan_gemm(int dtype, int m, int N, int K, bool single_split = false);
+// P must hold plan.splits * split_stride floats; split_stride >= m * ldp.
+hipError_t launch_gemm(int dtype, const GemmPlan& plan, const void* A, int lda, const void* W, int ldw,
+                       float* P, int ldp, size_t split_stride, int m, int N, int K, hipStream_t st);
+
+// ---- row-wise kernels
+// h[r,:] = emb[tokens[idx[r]],:];  a[r,:] = T(rmsnorm(h[r,:]) * gain)
+hipError_t launch_embed_norm(int dtype, const void* emb, const int32_t* tokens, const int32_t* idx, int m, int d,
+                             const float* gain, float eps, float* h, void* a, hipStream_t st);
+// h[r,:] += bias? + sum_s P[s][r,:] (n_splits may be 0);  if a: a[r,:] = T(rmsnorm(h[r,:]) * gain)
+hipError_t launch_add_norm(int dtype, float* h, const float* P, int n_splits, size_t split_stride, int ldp, int m,
+                           int d, const float* gain, float eps, void* a, hipStream_t st);
+// a[i,:] = T(rmsnorm(h[rows[i],:]) * gain)
+hipError_t launch_gather_norm(int dtype, const float* h, const int32_t* rows, int n_rows, int d, const float* gain,
+                              float eps, void* a, hipStream_t st);
+// split sums of the QKV projection (+bias), RoPE on q and k at positions idx[r];
+// q -> q_out[r,:], k -> k_cache[idx[r],:], v -> v_cache[idx[r],:]
+hipError_t launch_qkv_rope_scatter(int dtype, const float* P, int n_splits, size_t split_stride, int ldp,
+                                   const float* bias, const int32_t* idx, int m, int n_heads, int n_kv_heads,
+                                   int head_dim, const float* rope_cos, const float* rope_sin, void* q_out,
+                                   void* k_cache, void* v_cache, hipStream_t st);
+// act[r,f] = T(silu(g) * u), g/u = split sums of columns f and F+f
+hipError_t launch_swiglu(int dtype, const float* P, int n_splits, size_t split_stride, int ldp, int m, int F,
+                         void* act, hipStream_t st);
+// cache[idx[r],:] = rows[r,:]
+hipError_t launch_scatter_rows(int dtype, const void* rows, const int32_t* idx, int m, int width, void* cache,
+                               hipStream_t st);
+hipError_t launch_copy_f32(float* dst, const float* src, size_t n, hipStream_t st);
+// cos/sin table [max_pos, head_dim/2], angles evaluated in fp64
+hipError_t launch_rope_table(float* cos_t, float* sin_t, int max_pos, int head_dim, float theta, hipStream_t st);
+
+// ---- attention of m query rows against all L cached keys, no mask
+// out: T [m, H*dh]; lse: float [H, m] workspace; attn_avg: float [m, L] or null
+hipError_t launch_attention(int dtype, const void* q, const void* k_cache, const void* v_cache, int m, int L,
+                            int n_heads, int n_kv_heads, int head_dim, void* out, float* lse, float* attn_avg,
+                            hipStream_t st);
+
+// ---- rollout on the compact block: c_out = (A[:,S] c_in + A[:,notS] + c_in) / 2; first: c_in = one-hot rows
+hipError_t launch_rollout(const float* attn_avg, const float* c_in, float* c_out, const int32_t* idx, int m, int L,
+                          bool first, hipStream_t st);
+hipError_t launch_influence(const float* c_block, const int32_t* idx, int m, int L, float* influence,
+                            hipStream_t st);
+
+// ---- selection
+// Eq. 1 per logits row; the row's position is via ? via[pos[row]] : pos[row]
+hipError_t launch_confidence(const float* logits, const int32_t* pos, const int32_t* via, int n_rows, int vocab,
+                             float* conf, int32_t* pred, hipStream_t st);
+struct SelectArgs {
+  float sigma; int k; float p; int block_len; int n_unmask; int cand_mode;
+  int32_t* tokens; uint8_t* is_masked; int L; int prompt_len;
+  const float* conf; const int32_t* pred; const float* influence;
+  int32_t *mstar, *u_set, *decode_idx, *s_next, *s_rows_next, *counts;
+  float* score_out;   // nullable: D(i) * s^i of the stage-1 candidates, 0 elsewhere
+};
+int select_max_len();
+hipError_t launch_select(const SelectArgs& a, hipStream_t st);
+hipError_t launch_seq_reset(const uint8_t* is_masked, int L, int32_t* s_idx, int32_t* s_rows, float* conf,
+                            int32_t* pred, int32_t* counts, hipStream_t st);
+
+}  // namespace d2c

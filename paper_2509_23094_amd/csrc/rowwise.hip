@@ -1,0 +1,265 @@
+// Row-wise kernels around the projections of one block on the selected rows
+// (Eq. 5 of the d2Cache paper): embedding gather, residual add + RMSNorm,
+// RoPE + K/V cache update ("updates their KV states", Sec. 4 overview), SwiGLU.
+// All of them are HBM/L2-bound copies with a little arithmetic: one workgroup
+// per row, 16-byte coalesced accesses where the layout allows.
+#include "common.cuh"
+#include "internal.h"
+
+namespace d2c {
+namespace {
+
+constexpr int kThreads = 256;
+
+// Sum over the workgroup, same value in every thread, fixed order.
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  __syncthreads();
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  float t = 0.f;
+  for (int w = 0; w < (int)(blockDim.x >> 6); ++w) t += red[w];
+  return t;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void embed_norm_kernel(const T* __restrict__ emb,
+                                                              const int32_t* __restrict__ tokens,
+                                                              const int32_t* __restrict__ idx, int d,
+                                                              const float* __restrict__ gain, float eps,
+                                                              float* __restrict__ h, T* __restrict__ a) {
+  __shared__ float red[kThreads / 64];
+  const int r = blockIdx.x;
+  const T* src = emb + (size_t)tokens[idx[r]] * d;
+  float* hr = h + (size_t)r * d;
+  float ss = 0.f;
+  for (int c = threadIdx.x; c < d; c += kThreads) {
+    float v = to_f32(src[c]);
+    hr[c] = v;
+    ss += v * v;
+  }
+  const float inv = 1.0f / sqrtf(block_sum(ss, red) / (float)d + eps);
+  T* ar = a + (size_t)r * d;
+  for (int c = threadIdx.x; c < d; c += kThreads) ar[c] = from_f32<T>(hr[c] * inv * gain[c]);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void add_norm_kernel(float* __restrict__ h, const float* __restrict__ P,
+                                                            int n_splits, size_t split_stride, int ldp, int d,
+                                                            const float* __restrict__ gain, float eps,
+                                                            T* __restrict__ a) {
+  __shared__ float red[kThreads / 64];
+  const int r = blockIdx.x;
+  float* hr = h + (size_t)r * d;
+  float ss = 0.f;
+  for (int c = threadIdx.x; c < d; c += kThreads) {
+    float v = hr[c];
+    float add = 0.f;
+    for (int s = 0; s < n_splits; ++s) add += P[(size_t)s * split_stride + (size_t)r * ldp + c];
+    v += add;
+    hr[c] = v;
+    ss += v * v;
+  }
+  if (a == nullptr) return;
+  const float inv = 1.0f / sqrtf(block_sum(ss, red) / (float)d + eps);
+  T* ar = a + (size_t)r * d;
+  for (int c = threadIdx.x; c < d; c += kThreads) ar[c] = from_f32<T>(hr[c] * inv * gain[c]);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void gather_norm_kernel(const float* __restrict__ h,
+                                                               const int32_t* __restrict__ rows, int d,
+                                                               const float* __restrict__ gain, float eps,
+                                                               T* __restrict__ a) {
+  __shared__ float red[kThreads / 64];
+  const float* hr = h + (size_t)rows[blockIdx.x] * d;
+  float ss = 0.f;
+  for (int c = threadIdx.x; c < d; c += kThreads) {
+    float v = hr[c];
+    ss += v * v;
+  }
+  const float inv = 1.0f / sqrtf(block_sum(ss, red) / (float)d + eps);
+  T* ar = a + (size_t)blockIdx.x * d;
+  for (int c = threadIdx.x; c < d; c += kThreads) ar[c] = from_f32<T>(hr[c] * inv * gain[c]);
+}
+
+// One workgroup per selected row.  Columns of the fused projection: n_heads
+// query heads, then n_kv_heads key heads, then n_kv_heads value heads.
+// Rotate-half RoPE pairs element i with i + head_dim/2 inside a head.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void qkv_rope_scatter_kernel(
+    const float* __restrict__ P, int n_splits, size_t split_stride, int ldp, const float* __restrict__ bias,
+    const int32_t* __restrict__ idx, int n_heads, int n_kv_heads, int head_dim, const float* __restrict__ rope_cos,
+    const float* __restrict__ rope_sin, T* __restrict__ q_out, T* __restrict__ k_cache, T* __restrict__ v_cache) {
+  const int r = blockIdx.x;
+  const int pos = idx[r];
+  const int half = head_dim >> 1;
+  const int dq = n_heads * head_dim, dkv = n_kv_heads * head_dim;
+  const float* pr = P + (size_t)r * ldp;
+  auto col = [&](int c) {
+    float v = bias ? bias[c] : 0.f;
+    for (int s = 0; s < n_splits; ++s) v += pr[(size_t)s * split_stride + c];
+    return v;
+  };
+  const float* cs = rope_cos + (size_t)pos * half;
+  const float* sn = rope_sin + (size_t)pos * half;
+  // rotated pairs of q and k
+  const int n_pairs = (n_heads + n_kv_heads) * half;
+  for (int t = threadIdx.x; t < n_pairs; t += kThreads) {
+    const int head = t / half, i = t - head * half;
+    const int c1 = head * head_dim + i, c2 = c1 + half;      // columns in the fused projection
+    const float x1 = col(c1), x2 = col(c2);
+    const float c = cs[i], s = sn[i];
+    const float o1 = x1 * c - x2 * s, o2 = x2 * c + x1 * s;
+    if (head < n_heads) {
+      q_out[(size_t)r * dq + c1] = from_f32<T>(o1);
+      q_out[(size_t)r * dq + c2] = from_f32<T>(o2);
+    } else {
+      k_cache[(size_t)pos * dkv + (c1 - dq)] = from_f32<T>(o1);
+      k_cache[(size_t)pos * dkv + (c2 - dq)] = from_f32<T>(o2);
+    }
+  }
+  for (int c = threadIdx.x; c < dkv; c += kThreads)
+    v_cache[(size_t)pos * dkv + c] = from_f32<T>(col(dq + dkv + c));
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void swiglu_kernel(const float* __restrict__ P, int n_splits,
+                                                          size_t split_stride, int ldp, int F, T* __restrict__ act) {
+  const int r = blockIdx.y;
+  const int f = blockIdx.x * kThreads + threadIdx.x;
+  if (f >= F) return;
+  float g = 0.f, u = 0.f;
+  for (int s = 0; s < n_splits; ++s) {
+    const float* pr = P + (size_t)s * split_stride + (size_t)r * ldp;
+    g += pr[f];
+    u += pr[F + f];
+  }
+  act[(size_t)r * F + f] = from_f32<T>(g / (1.0f + expf(-g)) * u);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void scatter_rows_kernel(const T* __restrict__ rows,
+                                                                const int32_t* __restrict__ idx, int width,
+                                                                T* __restrict__ cache) {
+  const int r = blockIdx.x;
+  const T* src = rows + (size_t)r * width;
+  T* dst = cache + (size_t)idx[r] * width;
+  for (int c = threadIdx.x; c < width; c += kThreads) dst[c] = src[c];
+}
+
+__global__ void copy_f32_kernel(float* __restrict__ dst, const float* __restrict__ src, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) dst[i] = src[i];
+}
+
+// Angles in fp64 so that the table is the correctly rounded cos/sin of
+// pos * theta^(-2i/head_dim) at every position the cache can hold.
+__global__ void rope_table_kernel(float* __restrict__ cos_t, float* __restrict__ sin_t, int max_pos, int half,
+                                  double theta) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= max_pos * half) return;
+  const int pos = t / half, i = t - pos * half;
+  const double ang = (double)pos * pow(theta, -(double)i / (double)half);
+  cos_t[t] = (float)cos(ang);
+  sin_t[t] = (float)sin(ang);
+}
+
+}  // namespace
+
+#define D2C_DISPATCH(dtype, EXPR_BF16, EXPR_F32) \
+  do {                                           \
+    if ((dtype) == kBF16) { EXPR_BF16; } else { EXPR_F32; } \
+  } while (0)
+
+hipError_t launch_embed_norm(int dtype, const void* emb, const int32_t* tokens, const int32_t* idx, int m, int d,
+                             const float* gain, float eps, float* h, void* a, hipStream_t st) {
+  if (m <= 0) return hipSuccess;
+  D2C_DISPATCH(dtype,
+               hipLaunchKernelGGL(embed_norm_kernel<bf16>, dim3(m), dim3(kThreads), 0, st, (const bf16*)emb, tokens,
+                                  idx, d, gain, eps, h, (bf16*)a),
+               hipLaunchKernelGGL(embed_norm_kernel<float>, dim3(m), dim3(kThreads), 0, st, (const float*)emb, tokens,
+                                  idx, d, gain, eps, h, (float*)a));
+  return hipGetLastError();
+}
+
+hipError_t launch_add_norm(int dtype, float* h, const float* P, int n_splits, size_t split_stride, int ldp, int m,
+                           int d, const float* gain, float eps, void* a, hipStream_t st) {
+  if (m <= 0) return hipSuccess;
+  D2C_DISPATCH(dtype,
+               hipLaunchKernelGGL(add_norm_kernel<bf16>, dim3(m), dim3(kThreads), 0, st, h, P, n_splits, split_stride,
+                                  ldp, d, gain, eps, (bf16*)a),
+               hipLaunchKernelGGL(add_norm_kernel<float>, dim3(m), dim3(kThreads), 0, st, h, P, n_splits,
+                                  split_stride, ldp, d, gain, eps, (float*)a));
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_norm(int dtype, const float* h, const int32_t* rows, int n_rows, int d, const float* gain,
+                              float eps, void* a, hipStream_t st) {
+  if (n_rows <= 0) return hipSuccess;
+  D2C_DISPATCH(dtype,
+               hipLaunchKernelGGL(gather_norm_kernel<bf16>, dim3(n_rows), dim3(kThreads), 0, st, h, rows, d, gain,
+                                  eps, (bf16*)a),
+               hipLaunchKernelGGL(gather_norm_kernel<float>, dim3(n_rows), dim3(kThreads), 0, st, h, rows, d, gain,
+                                  eps, (float*)a));
+  return hipGetLastError();
+}
+
+hipError_t launch_qkv_rope_scatter(int dtype, const float* P, int n_splits, size_t split_stride, int ldp,
+                                   const float* bias, const int32_t* idx, int m, int n_heads, int n_kv_heads,
+                                   int head_dim, const float* rope_cos, const float* rope_sin, void* q_out,
+                                   void* k_cache, void* v_cache, hipStream_t st) {
+  if (m <= 0) return hipSuccess;
+  if (head_dim % 2) return hipErrorInvalidValue;
+  D2C_DISPATCH(dtype,
+               hipLaunchKernelGGL(qkv_rope_scatter_kernel<bf16>, dim3(m), dim3(kThreads), 0, st, P, n_splits,
+                                  split_stride, ldp, bias, idx, n_heads, n_kv_heads, head_dim, rope_cos, rope_sin,
+                                  (bf16*)q_out, (bf16*)k_cache, (bf16*)v_cache),
+               hipLaunchKernelGGL(qkv_rope_scatter_kernel<float>, dim3(m), dim3(kThreads), 0, st, P, n_splits,
+                                  split_stride, ldp, bias, idx, n_heads, n_kv_heads, head_dim, rope_cos, rope_sin,
+                                  (float*)q_out, (float*)k_cache, (float*)v_cache));
+  return hipGetLastError();
+}
+
+hipError_t launch_swiglu(int dtype, const float* P, int n_splits, size_t split_stride, int ldp, int m, int F,
+                         void* act, hipStream_t st) {
+  if (m <= 0) return hipSuccess;
+  dim3 grid((F + kThreads - 1) / kThreads, m);
+  D2C_DISPATCH(dtype,
+               hipLaunchKernelGGL(swiglu_kernel<bf16>, grid, dim3(kThreads), 0, st, P, n_splits, split_stride, ldp, F,
+                                  (bf16*)act),
+               hipLaunchKernelGGL(swiglu_kernel<float>, grid, dim3(kThreads), 0, st, P, n_splits, split_stride, ldp,
+                                  F, (float*)act));
+  return hipGetLastError();
+}
+
+hipError_t launch_scatter_rows(int dtype, const void* rows, const int32_t* idx, int m, int width, void* cache,
+                               hipStream_t st) {
+  if (m <= 0) return hipSuccess;
+  D2C_DISPATCH(dtype,
+               hipLaunchKernelGGL(scatter_rows_kernel<bf16>, dim3(m), dim3(kThreads), 0, st, (const bf16*)rows, idx,
+                                  width, (bf16*)cache),
+               hipLaunchKernelGGL(scatter_rows_kernel<float>, dim3(m), dim3(kThreads), 0, st, (const float*)rows, idx,
+                                  width, (float*)cache));
+  return hipGetLastError();
+}
+
+hipError_t launch_copy_f32(float* dst, const float* src, size_t n, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  const int blocks = (int)((n + 1023) / 1024 < 2048 ? (n + 1023) / 1024 : 2048);
+  hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks), dim3(256), 0, st, dst, src, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_table(float* cos_t, float* sin_t, int max_pos, int head_dim, float theta, hipStream_t st) {
+  const int half = head_dim / 2;
+  const int n = max_pos * half;
+  if (n <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, st, cos_t, sin_t, max_pos, half,
+                     (double)theta);
+  return hipGetLastError();
+}
+
+}  // namespace d2c

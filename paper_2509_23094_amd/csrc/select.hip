@@ -1,0 +1,438 @@
+// Selection side of the d2Cache step: Eq. 1 (prediction and confidence over the
+// vocabulary), Eq. 3-4 (certainty density, stage-1 top-k), unmasking (Eq. 2),
+// the rollout update on the compact |S| x L block (Eq. 6-8), influence scores
+// (Eq. 9) and the stage-2 cumulative-mass selection (Sec. 4.2, last paragraph).
+//
+// Everything that decides an index is integer-exact and order-independent:
+// top-k ranks 64-bit keys (float bits of the non-negative score, then lower
+// index first); top-p sorts such keys with a bitonic network in LDS and scans
+// fixed-point masses floor(c * 2^32) in uint64.  Ties always go to the lowest index.
+#include "common.cuh"
+#include "internal.h"
+
+namespace d2c {
+namespace {
+
+// ------------------------------------------------------------------ Eq. 1
+constexpr int kConfThreads = 1024;
+
+__global__ __launch_bounds__(kConfThreads) void confidence_kernel(const float* __restrict__ logits,
+                                                                  const int32_t* __restrict__ pos,
+                                                                  const int32_t* __restrict__ via, int vocab,
+                                                                  float* __restrict__ conf,
+                                                                  int32_t* __restrict__ pred) {
+  __shared__ float s_val[kConfThreads / 64];
+  __shared__ int s_idx[kConfThreads / 64];
+  __shared__ float s_sum[kConfThreads / 64];
+  const float* row = logits + (size_t)blockIdx.x * vocab;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  // arg-max, ties to the lowest index: a thread scans its indices in ascending order
+  float best = -INFINITY;
+  int bidx = 0x7fffffff;
+  for (int v = tid; v < vocab; v += kConfThreads) {
+    const float x = row[v];
+    if (x > best || (x == best && v < bidx)) { best = x; bidx = v; }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ob = __shfl_xor(best, o, kWave);
+    const int oi = __shfl_xor(bidx, o, kWave);
+    if (ob > best || (ob == best && oi < bidx)) { best = ob; bidx = oi; }
+  }
+  if (lane == 0) { s_val[wave] = best; s_idx[wave] = bidx; }
+  __syncthreads();
+  best = s_val[0]; bidx = s_idx[0];
+  for (int w = 1; w < kConfThreads / 64; ++w) {
+    const float ob = s_val[w];
+    const int oi = s_idx[w];
+    if (ob > best || (ob == best && oi < bidx)) { best = ob; bidx = oi; }
+  }
+  // s = p(x-hat) = 1 / sum_v exp(x_v - max)
+  float sum = 0.f;
+  for (int v = tid; v < vocab; v += kConfThreads) sum += expf(row[v] - best);
+  sum = wave_sum(sum);
+  if (lane == 0) s_sum[wave] = sum;
+  __syncthreads();
+  if (tid == 0) {
+    float t = 0.f;
+    for (int w = 0; w < kConfThreads / 64; ++w) t += s_sum[w];
+    const int p = via ? via[pos[blockIdx.x]] : pos[blockIdx.x];    // row -> position, directly or through S
+    conf[p] = 1.0f / t;
+    pred[p] = bidx;
+  }
+}
+
+// ------------------------------------------------------------------ Eq. 6-8 on the compact block
+// c_out[i, c] = ( sum_r A[i, S_r] c_in[r, c] + A[i, c] [c not in S] + c_in[i, c] ) / 2
+// Rows outside S stay one-hot under Eq. 6-7, so only these m rows ever change.
+constexpr int kRollThreads = 256;
+constexpr int kRollRows = 16;
+constexpr int kRollChunk = 128;
+
+__global__ __launch_bounds__(kRollThreads) void rollout_kernel(const float* __restrict__ A,
+                                                               const float* __restrict__ c_in,
+                                                               float* __restrict__ c_out,
+                                                               const int32_t* __restrict__ idx, int m, int L,
+                                                               int first) {
+  __shared__ float a_sel[kRollRows][kRollChunk + 1];
+  const int col = blockIdx.x * kRollThreads + threadIdx.x;
+  const int i0 = blockIdx.y * kRollRows;
+  const bool live = col < L;
+  const int self = live ? find_sorted(idx, m, col) : -1;     // row of S that sits at this column, or -1
+  float acc[kRollRows];
+#pragma unroll
+  for (int ii = 0; ii < kRollRows; ++ii) acc[ii] = 0.f;
+
+  if (first) {
+    // C^(0) = I: sum_r A[i,S_r] [c == S_r] + A[i,c][c not in S] = A[i,c];  c_in[i,c] = [c == S_i]
+    if (live)
+      for (int ii = 0; ii < kRollRows && i0 + ii < m; ++ii)
+        c_out[(size_t)(i0 + ii) * L + col] = 0.5f * (A[(size_t)(i0 + ii) * L + col] + (self == i0 + ii ? 1.f : 0.f));
+    return;
+  }
+  for (int rc = 0; rc < m; rc += kRollChunk) {
+    __syncthreads();
+    for (int e = threadIdx.x; e < kRollRows * kRollChunk; e += kRollThreads) {
+      const int ii = e / kRollChunk, rr = e - ii * kRollChunk;
+      float v = 0.f;
+      if (i0 + ii < m && rc + rr < m) v = A[(size_t)(i0 + ii) * L + idx[rc + rr]];
+      a_sel[ii][rr] = v;
+    }
+    __syncthreads();
+    if (live) {
+      const int n = min(kRollChunk, m - rc);
+      for (int rr = 0; rr < n; ++rr) {
+        const float cv = c_in[(size_t)(rc + rr) * L + col];
+#pragma unroll
+        for (int ii = 0; ii < kRollRows; ++ii) acc[ii] = fmaf(a_sel[ii][rr], cv, acc[ii]);
+      }
+    }
+  }
+  if (!live) return;
+#pragma unroll
+  for (int ii = 0; ii < kRollRows; ++ii) {
+    const int i = i0 + ii;
+    if (i >= m) break;
+    const float direct = self < 0 ? A[(size_t)i * L + col] : 0.f;
+    c_out[(size_t)i * L + col] = 0.5f * (acc[ii] + direct + c_in[(size_t)i * L + col]);
+  }
+}
+
+// Eq. 9 on the compact block: c_j = [j not in S] + sum_i C_S[i, j]
+__global__ void influence_kernel(const float* __restrict__ c_block, const int32_t* __restrict__ idx, int m, int L,
+                                 float* __restrict__ influence) {
+  const int col = blockIdx.x * blockDim.x + threadIdx.x;
+  if (col >= L) return;
+  float s = find_sorted(idx, m, col) < 0 ? 1.f : 0.f;
+  for (int i = 0; i < m; ++i) s += c_block[(size_t)i * L + col];
+  influence[col] = s;
+}
+
+// ------------------------------------------------------------------ two-stage selection, one workgroup
+constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kSelMaxL = 4096;
+
+struct SelShared {
+  int wcnt[kSelWaves];
+  int scalar[8];
+  unsigned long long total;
+};
+
+// Ordered compaction of {i in [0,n) : pred(i)} into out (ascending); returns the count (uniform).
+template <typename Pred, typename Emit>
+__device__ int block_compact(int n, Pred pred, Emit emit, SelShared* sh) {
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  int base = 0;
+  for (int start = 0; start < n; start += kSelThreads) {
+    const int i = start + tid;
+    const bool f = i < n && pred(i);
+    const unsigned long long ballot = __ballot(f);
+    const int before = __popcll(ballot & ((1ull << lane) - 1ull));
+    __syncthreads();
+    if (lane == 0) sh->wcnt[wave] = __popcll(ballot);
+    __syncthreads();
+    int off = 0, total = 0;
+    for (int w = 0; w < kSelWaves; ++w) {
+      const int c = sh->wcnt[w];
+      if (w < wave) off += c;
+      total += c;
+    }
+    if (f) emit(base + off + before, i);
+    base += total;
+  }
+  __syncthreads();
+  return base;
+}
+
+__device__ __forceinline__ unsigned long long make_key(float score, int index) {
+  return ((unsigned long long)__float_as_uint(score) << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)index);
+}
+__device__ __forceinline__ int key_index(unsigned long long key) { return (int)(0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull)); }
+__device__ __forceinline__ unsigned long long key_mass(unsigned long long key) {
+  // floor(c * 2^32): the scaling is exact in float, the conversion truncates a non-negative value
+  return (unsigned long long)(__uint_as_float((unsigned)(key >> 32)) * 4294967296.0f);
+}
+
+__global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a, int NP) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int L = a.L;
+  unsigned long long* keys = reinterpret_cast<unsigned long long*>(smem);            // [NP]
+  unsigned long long* keys1 = keys + NP;                                             // [L]
+  unsigned long long* scan_a = keys1 + L;                                            // [kSelThreads]
+  unsigned long long* scan_b = scan_a + kSelThreads;                                 // [kSelThreads]
+  SelShared* sh = reinterpret_cast<SelShared*>(scan_b + kSelThreads);                // 8-byte aligned
+  float* phi = reinterpret_cast<float*>(sh + 1);                                     // [L]
+  int* cand = reinterpret_cast<int*>(phi + L);                                       // [L]
+  int* slist = cand + L;                                                             // [L]
+  unsigned char* msk = reinterpret_cast<unsigned char*>(slist + L);                  // [L]
+  unsigned char* sel = msk + L;                                                      // [L]
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+
+  // ---- phase 0: mask flags, first masked position, |M_t|
+  if (tid == 0) { sh->scalar[0] = 0x7fffffff; sh->scalar[1] = 0; sh->scalar[2] = 0x7fffffff; sh->total = 0ull; }
+  __syncthreads();
+  {
+    int first = 0x7fffffff, cnt = 0;
+    for (int j = tid; j < L; j += kSelThreads) {
+      const unsigned char f = a.is_masked[j] ? 1 : 0;
+      msk[j] = f;
+      sel[j] = 0;
+      if (f) { cnt++; first = min(first, j); }
+    }
+    if (first != 0x7fffffff) atomicMin(&sh->scalar[0], first);
+    if (cnt) atomicAdd(&sh->scalar[1], cnt);
+  }
+  __syncthreads();
+  const int first_masked = sh->scalar[0];
+  const int n_masked = sh->scalar[1];
+  int lo = L, hi = L;
+  if (n_masked > 0) {
+    const int b = (first_masked - a.prompt_len) / a.block_len;
+    lo = a.prompt_len + b * a.block_len;
+    hi = min(L, lo + a.block_len);
+  }
+
+  // ---- phase 1: Eq. 3 on the masked tokens of the current block, score = D(i) * s^i
+  const float inv2s2 = 1.0f / (2.0f * a.sigma * a.sigma);
+  for (int d = tid; d < L; d += kSelThreads) {
+    phi[d] = expf(-((float)d * (float)d) * inv2s2);
+    if (a.score_out) a.score_out[d] = 0.f;
+  }
+  const int n1 = block_compact(hi - lo, [&](int t) { return msk[lo + t] != 0; },
+                               [&](int slot, int t) { cand[slot] = lo + t; }, sh);
+  for (int c = wave; c < n1; c += kSelWaves) {
+    const int i = cand[c];
+    float dsum = 0.f;
+    for (int j = lane; j < L; j += kWave)
+      if (!msk[j]) dsum += phi[abs(i - j)];
+    dsum = wave_sum(dsum);
+    if (lane == 0) {
+      const float score = dsum * a.conf[i];
+      keys1[c] = make_key(score, i);
+      if (a.score_out) a.score_out[i] = score;
+    }
+  }
+  __syncthreads();
+
+  // ---- phase 2: Eq. 4 (top-k) and the decode set (top-n_unmask) by rank counting
+  for (int c = tid; c < n1; c += kSelThreads) {
+    const unsigned long long mine = keys1[c];
+    int rank = 0;
+    for (int o = 0; o < n1; ++o) rank += keys1[o] > mine ? 1 : 0;
+    unsigned char f = 0;
+    if (rank < a.k) f |= 1;
+    if (rank < a.n_unmask) f |= 4;
+    sel[cand[c]] = f;
+  }
+  __syncthreads();
+  const int n_mstar = block_compact(n1, [&](int c) { return (sel[cand[c]] & 1) != 0; },
+                                    [&](int slot, int c) { a.mstar[slot] = cand[c]; }, sh);
+  const int n_dec = block_compact(n1, [&](int c) { return (sel[cand[c]] & 4) != 0; },
+                                  [&](int slot, int c) { a.decode_idx[slot] = cand[c]; }, sh);
+
+  // ---- phase 3: stage-2 keys (influence bits, lower index first); non-candidates sort last as key 0
+  {
+    unsigned long long part = 0ull;
+    for (int j = tid; j < NP; j += kSelThreads) {
+      unsigned long long key = 0ull;
+      if (j < L) {
+        const bool is_cand = a.cand_mode == 0 ? (msk[j] == 0) : ((sel[j] & 1) == 0);
+        if (is_cand) {
+          key = make_key(a.influence[j], j);
+          part += key_mass(key);
+        }
+      }
+      keys[j] = key;
+    }
+    if (part) atomicAdd(&sh->total, part);      // integer sum: order does not matter
+  }
+  __syncthreads();
+  const int n2 = block_compact(L, [&](int j) { return keys[j] != 0ull; }, [&](int, int) {}, sh);
+  const unsigned long long total = sh->total;
+
+  // bitonic network, descending
+  for (int k = 2; k <= NP; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int t = tid; t < (NP >> 1); t += kSelThreads) {
+        const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+        const int ixj = i | j;
+        const unsigned long long x = keys[i], y = keys[ixj];
+        const bool up = (i & k) == 0;
+        if (up ? (x < y) : (x > y)) { keys[i] = y; keys[ixj] = x; }
+      }
+      __syncthreads();
+    }
+  }
+
+  // ---- phase 4: smallest prefix whose mass exceeds floor(p * total)
+  int take = n2;
+  if (n2 > 0 && a.p < 1.0f) {
+    const unsigned long long thr = (unsigned long long)floor((double)a.p * __ull2double_rn(total));
+    const int per = (NP + kSelThreads - 1) / kSelThreads;
+    const int begin = tid * per;
+    unsigned long long local = 0ull;
+    for (int e = 0; e < per; ++e) {
+      const int rnk = begin + e;
+      if (rnk < n2) local += key_mass(keys[rnk]);
+    }
+    scan_a[tid] = local;
+    __syncthreads();
+    unsigned long long* src = scan_a;
+    unsigned long long* dst = scan_b;
+    for (int o = 1; o < kSelThreads; o <<= 1) {            // inclusive Hillis-Steele scan
+      dst[tid] = src[tid] + (tid >= o ? src[tid - o] : 0ull);
+      __syncthreads();
+      unsigned long long* t = src; src = dst; dst = t;
+    }
+    unsigned long long run = src[tid] - local;             // exclusive prefix of this thread's chunk
+    int found = 0x7fffffff;
+    for (int e = 0; e < per; ++e) {
+      const int rnk = begin + e;
+      if (rnk < n2) {
+        run += key_mass(keys[rnk]);
+        if (run > thr && found == 0x7fffffff) found = rnk;
+      }
+    }
+    if (found != 0x7fffffff) atomicMin(&sh->scalar[2], found);
+    __syncthreads();
+    if (sh->scalar[2] != 0x7fffffff) take = sh->scalar[2] + 1;
+  }
+  for (int rnk = tid; rnk < take; rnk += kSelThreads) sel[key_index(keys[rnk])] |= 2;
+  __syncthreads();
+
+  // ---- phase 5: unmask (Eq. 2), emit U, S_{t+1} = M* u U and its still-masked rows
+  for (int c = tid; c < n1; c += kSelThreads) {
+    const int i = cand[c];
+    if (sel[i] & 4) {
+      a.tokens[i] = a.pred[i];
+      a.is_masked[i] = 0;
+      msk[i] = 0;
+    }
+  }
+  const int n_u = block_compact(L, [&](int j) { return (sel[j] & 2) != 0; },
+                                [&](int slot, int j) { a.u_set[slot] = j; }, sh);
+  const int n_s = block_compact(L, [&](int j) { return (sel[j] & 3) != 0; },
+                                [&](int slot, int j) { a.s_next[slot] = j; slist[slot] = j; }, sh);
+  const int n_rows = block_compact(n_s, [&](int rr) { return msk[slist[rr]] != 0; },
+                                   [&](int slot, int rr) { a.s_rows_next[slot] = rr; }, sh);
+  if (tid == 0) {
+    a.counts[0] = n_mstar;
+    a.counts[1] = n_u;
+    a.counts[2] = n_s;
+    a.counts[3] = n_dec;
+    a.counts[4] = n_rows;
+    a.counts[5] = n_masked - n_dec;
+    a.counts[6] = lo;
+    a.counts[7] = hi;
+  }
+}
+
+size_t select_smem_bytes(int L, int NP) {
+  return (size_t)NP * 8 + (size_t)L * 8 + 2 * (size_t)kSelThreads * 8 + (size_t)L * 12 + sizeof(SelShared) +
+         2 * (size_t)L + 64;
+}
+
+// Step-0 state: S_0 = all rows, s_rows = masked rows, conf = 0, pred = 0.
+__global__ __launch_bounds__(kSelThreads) void seq_reset_kernel(const uint8_t* __restrict__ is_masked, int L,
+                                                                int32_t* __restrict__ s_idx,
+                                                                int32_t* __restrict__ s_rows,
+                                                                float* __restrict__ conf, int32_t* __restrict__ pred,
+                                                                int32_t* __restrict__ counts) {
+  __shared__ SelShared sh;
+  for (int j = threadIdx.x; j < L; j += kSelThreads) {
+    s_idx[j] = j;
+    conf[j] = 0.f;
+    pred[j] = 0;
+  }
+  const int n = block_compact(L, [&](int j) { return is_masked[j] != 0; },
+                              [&](int slot, int j) { s_rows[slot] = j; }, &sh);
+  if (threadIdx.x == 0) {
+    for (int c = 0; c < 8; ++c) counts[c] = 0;
+    counts[2] = L;
+    counts[4] = n;
+    counts[5] = n;
+  }
+}
+
+}  // namespace
+
+int select_max_len() { return kSelMaxL; }
+
+hipError_t launch_confidence(const float* logits, const int32_t* pos, const int32_t* via, int n_rows, int vocab,
+                             float* conf, int32_t* pred, hipStream_t st) {
+  if (n_rows <= 0) return hipSuccess;
+  if (vocab <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(confidence_kernel, dim3(n_rows), dim3(kConfThreads), 0, st, logits, pos, via, vocab, conf,
+                     pred);
+  return hipGetLastError();
+}
+
+hipError_t launch_rollout(const float* attn_avg, const float* c_in, float* c_out, const int32_t* idx, int m, int L,
+                          bool first, hipStream_t st) {
+  if (m <= 0) return hipSuccess;
+  dim3 grid((L + kRollThreads - 1) / kRollThreads, (m + kRollRows - 1) / kRollRows);
+  hipLaunchKernelGGL(rollout_kernel, grid, dim3(kRollThreads), 0, st, attn_avg, c_in, c_out, idx, m, L,
+                     first ? 1 : 0);
+  return hipGetLastError();
+}
+
+hipError_t launch_influence(const float* c_block, const int32_t* idx, int m, int L, float* influence,
+                            hipStream_t st) {
+  if (L <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(influence_kernel, dim3((L + 255) / 256), dim3(256), 0, st, c_block, idx, m, L, influence);
+  return hipGetLastError();
+}
+
+hipError_t launch_select(const SelectArgs& a, hipStream_t st) {
+  if (a.L <= 0 || a.L > kSelMaxL || a.block_len <= 0 || a.prompt_len < 0 || a.prompt_len > a.L)
+    return hipErrorInvalidValue;
+  int NP = 2;
+  while (NP < a.L) NP <<= 1;
+  const size_t smem = select_smem_bytes(a.L, NP);
+  static int lds_limit = 0;
+  if (lds_limit == 0) {
+    int dev = 0, optin = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&optin, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, optin);
+    if (e != hipSuccess) return e;
+    lds_limit = optin;
+  }
+  if (smem > (size_t)lds_limit) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(select_kernel, dim3(1), dim3(kSelThreads), smem, st, a, NP);
+  return hipGetLastError();
+}
+
+hipError_t launch_seq_reset(const uint8_t* is_masked, int L, int32_t* s_idx, int32_t* s_rows, float* conf,
+                            int32_t* pred, int32_t* counts, hipStream_t st) {
+  if (L <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(seq_reset_kernel, dim3(1), dim3(kSelThreads), 0, st, is_masked, L, s_idx, s_rows, conf, pred,
+                     counts);
+  return hipGetLastError();
+}
+
+}  // namespace d2c

@@ -1,0 +1,241 @@
+"""GPU parity of d2c_step (the whole denoising step) against the CPU oracle.
+
+Teacher-forced runs feed both sides the same S_t, tokens and cached confidences
+at every step, compare every float output within the dtype's tolerance, and check
+the index sets bit-exactly on the GPU's own score arrays; free-running runs compare
+the sets directly for as long as the oracle's decision margins are wide."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import d2cache_oracle as O
+from paper_2509_23094_amd import workloads as W
+
+from gpu_util import TOL, host, oracle_dims, oracle_params, rel_l2, say, topk_margin, topp_margin
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2509_23094_amd import binding
+    return binding
+
+
+def _gpu_params(B, prm: O.Params):
+    return B.make_params(prm.sigma, prm.k, prm.p, prm.block_len, prm.n_unmask, prm.cand_mode)
+
+
+def _sets(B, seq):
+    cnt = seq.counts.cpu().numpy()
+    return {
+        "mstar": seq.mstar.cpu().numpy()[: cnt[B.CNT_MSTAR]],
+        "u": seq.u_set.cpu().numpy()[: cnt[B.CNT_U]],
+        "decode": seq.decode_idx.cpu().numpy()[: cnt[B.CNT_DECODE]],
+        "s_next": seq.s_idx.cpu().numpy()[: cnt[B.CNT_S]],
+        "rows_next": seq.s_rows.cpu().numpy()[: cnt[B.CNT_NEXT_ROWS]],
+        "block": (int(cnt[B.CNT_BLOCK_LO]), int(cnt[B.CNT_BLOCK_HI])),
+    }
+
+
+def _force(seq, st: O.SeqState):
+    """Put the oracle's state (tokens, mask, cached Eq. 1 values, S_{t+1}) into the GPU sequence."""
+    seq.tokens.copy_(torch.from_numpy(st.y.astype(np.int32)))
+    seq.is_masked.copy_(torch.from_numpy(st.is_masked.astype(np.uint8)))
+    seq.conf.copy_(torch.from_numpy(st.conf))
+    seq.pred.copy_(torch.from_numpy(st.pred))
+    S = st.S.astype(np.int32)
+    seq.set_selection(S, np.flatnonzero(st.is_masked[S]).astype(np.int32))
+    seq.c.n_masked = int(st.is_masked.sum())
+
+
+def _teacher_forced(B, dims, mdl, su, prm, n_steps, seed=0, check_free_run=True):
+    od = oracle_dims(dims, len(mdl["layers"]))
+    tol = TOL[dims.dtype]
+    L = su.seq_len
+    ctx = B.Context(dims, mdl, L)
+    y0, m0 = W.initial_sequence(dims, su, seed)
+    st = O.new_state(od, y0, m0, su.prompt_len)
+    seq = B.Sequence_(ctx, y0, m0, su.prompt_len, trace=True, max_trace_rows=su.gen_len)
+    gp = _gpu_params(B, prm)
+    assert (seq.n_s, seq.n_rows, seq.n_masked) == (L, su.gen_len, su.gen_len)
+    free_running = check_free_run
+    for t in range(n_steps):
+        if not st.is_masked.any():
+            break
+        say(f"d2c_step teacher-forced t={t} m={len(st.S)} dtype={dims.dtype} d={dims.d_model} L={L}")
+        masked_before = st.is_masked.copy()
+        O.d2cache_step(od, mdl, prm, st)
+        ctx.d2c_step(gp, [seq])
+        tr = st.trace
+        S, m = tr["S"], len(tr["S"])
+        rows = tr["logit_rows"]
+        # --- floats
+        assert rel_l2(host(seq.hidden_out)[:m], tr["hidden"]) < tol, f"hidden t={t}"
+        if len(rows):
+            assert rel_l2(host(seq.logits_out)[: len(rows)], tr["logits"]) < tol, f"logits t={t}"
+        assert rel_l2(host(seq.k_cache), st.k_cache) < tol and rel_l2(host(seq.v_cache), st.v_cache) < tol, f"kv t={t}"
+        infl = host(seq.influence)
+        assert rel_l2(infl, tr["c"]) < tol and np.max(np.abs(infl - tr["c"])) < tol * max(1.0, tr["c"].max()), f"c t={t}"
+        conf_g, pred_g = host(seq.conf), seq.pred.cpu().numpy()
+        if len(rows):
+            np.testing.assert_allclose(conf_g[rows], st.conf[rows], rtol=max(tol, 1e-5) * 5, err_msg=f"conf t={t}")
+            lg = tr["logits"]
+            picked = lg[np.arange(len(rows)), pred_g[rows]]
+            assert np.all(lg.max(axis=1) - picked <= 4 * tol * np.abs(lg).max() + 1e-12), f"pred t={t}"
+            if dims.dtype == "f32":
+                np.testing.assert_array_equal(pred_g[rows], st.pred[rows])
+        g = _sets(B, seq)
+        assert g["block"] == tr["block"]
+        score_g = host(seq.score)
+        cand1 = np.array([i for i in range(*tr["block"]) if masked_before[i]], np.int64)
+        if len(cand1):
+            np.testing.assert_allclose(score_g[cand1], tr["score"][cand1], rtol=max(tol, 1e-5) * 5)
+        # --- index sets, integer-exact on the GPU's own float arrays
+        np.testing.assert_array_equal(g["mstar"], O.top_k_select(score_g, cand1, prm.k))
+        np.testing.assert_array_equal(g["decode"], O.top_k_select(score_g, cand1, prm.n_unmask))
+        cand2 = np.flatnonzero(~masked_before)
+        np.testing.assert_array_equal(g["u"], O.top_p_select(infl, cand2, prm.p))
+        np.testing.assert_array_equal(g["s_next"], np.union1d(g["mstar"], g["u"]))
+        # --- the same sets against the oracle's, while its margins are wide
+        if free_running:
+            safe = (topk_margin(tr["score"], cand1, prm.k) > 50 * tol and
+                    topk_margin(tr["score"], cand1, prm.n_unmask) > 50 * tol and
+                    topp_margin(tr["c"], cand2, prm.p) > 50 * tol)
+            if safe:
+                np.testing.assert_array_equal(g["mstar"], tr["mstar"])
+                np.testing.assert_array_equal(g["decode"], tr["decode"])
+                np.testing.assert_array_equal(g["u"], tr["u"])
+        _force(seq, st)
+    ctx.close()
+
+
+def test_step_c1_teacher_forced_all_steps(B):
+    """The small fp32 model: every one of its 64 steps."""
+    wd, su = W.DIMS["C1"], W.SETUP["C1"]
+    mdl = W.model_weights(wd, 0)
+    _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=su.gen_len)
+
+
+def test_step_c1_free_running(B):
+    """No forcing: the GPU decodes the whole response on its own; sets and tokens must match the oracle's
+    as long as the oracle's own decisions are not near-ties."""
+    wd, su = W.DIMS["C1"], W.SETUP["C1"]
+    mdl = W.model_weights(wd, 0)
+    od, prm = oracle_dims(wd), oracle_params(su)
+    ctx = B.Context(wd, mdl, su.seq_len)
+    y0, m0 = W.initial_sequence(wd, su, 0)
+    st = O.new_state(od, y0, m0, su.prompt_len)
+    seq = B.Sequence_(ctx, y0, m0, su.prompt_len, trace=True, max_trace_rows=su.gen_len)
+    gp = _gpu_params(B, prm)
+    compared = 0
+    for t in range(su.gen_len):
+        say(f"d2c_step free-running t={t}")
+        masked_before = st.is_masked.copy()
+        O.d2cache_step(od, mdl, prm, st)
+        ctx.d2c_step(gp, [seq])
+        tr = st.trace
+        cand1 = np.array([i for i in range(*tr["block"]) if masked_before[i]], np.int64)
+        cand2 = np.flatnonzero(~masked_before)
+        lg = np.sort(tr["logits"], axis=1) if len(tr["logit_rows"]) else np.zeros((0, 2))
+        safe = (topk_margin(tr["score"], cand1, prm.k) > 1e-4 and topk_margin(tr["score"], cand1, prm.n_unmask) > 1e-4
+                and topp_margin(tr["c"], cand2, prm.p) > 1e-4 and
+                (len(lg) == 0 or np.min(lg[:, -1] - lg[:, -2]) > 1e-4 * np.abs(lg).max()))
+        if not safe:
+            break
+        g = _sets(B, seq)
+        np.testing.assert_array_equal(g["s_next"], st.S)
+        np.testing.assert_array_equal(g["decode"], tr["decode"])
+        np.testing.assert_array_equal(seq.tokens.cpu().numpy(), st.y)
+        np.testing.assert_array_equal(seq.is_masked.cpu().numpy().astype(bool), st.is_masked)
+        compared += 1
+    assert compared >= 8, "the oracle's margins were too narrow to compare even a few steps"
+    if compared == su.gen_len:
+        assert seq.n_masked == 0
+    ctx.close()
+
+
+def test_step_select_all_equals_full_recomputation(B):
+    """k >= |M|, p = 1, one block: d2c_step must reproduce the oracle's separate full forward every step."""
+    wd = W.with_layers(W.DIMS["C1"], 2)
+    su = W.DecodeSetup(24, 16, 16, 1, k=10 ** 6, p=1.0)
+    mdl = W.model_weights(wd, 5)
+    od = oracle_dims(wd)
+    ctx = B.Context(wd, mdl, su.seq_len)
+    y0, m0 = W.initial_sequence(wd, su, 1)
+    seq = B.Sequence_(ctx, y0, m0, su.prompt_len, trace=True)
+    gp = B.make_params(10.0, su.seq_len, 1.0, su.gen_len, 1, 0)
+    for t in range(su.gen_len):
+        say(f"select-all step t={t}")
+        y_in = seq.tokens.cpu().numpy()
+        masked = seq.is_masked.cpu().numpy().astype(bool)
+        assert seq.n_s == su.seq_len
+        ctx.d2c_step(gp, [seq])
+        full = O.full_forward(od, mdl, y_in)
+        assert rel_l2(host(seq.hidden_out), full["hidden"]) < 1e-5
+        assert rel_l2(host(seq.k_cache), full["k"]) < 1e-5 and rel_l2(host(seq.v_cache), full["v"]) < 1e-5
+        rows = np.flatnonzero(masked)
+        assert rel_l2(host(seq.logits_out)[: len(rows)], full["logits"][rows]) < 1e-5
+    assert seq.n_masked == 0
+    ctx.close()
+
+
+def test_step_select_none_leaves_cache_unchanged(B):
+    wd = W.with_layers(W.DIMS["C1"], 2)
+    su = W.DecodeSetup(16, 16, 8, 1, k=4, p=0.5)
+    mdl = W.model_weights(wd, 6)
+    ctx = B.Context(wd, mdl, su.seq_len)
+    y0, m0 = W.initial_sequence(wd, su, 2)
+    seq = B.Sequence_(ctx, y0, m0, su.prompt_len, trace=True)
+    gp = B.make_params(10.0, su.k, su.p, su.block_len, 1, 0)
+    say("select-none: step 0")
+    ctx.d2c_step(gp, [seq])
+    snap = [t.clone() for t in (seq.k_cache, seq.v_cache, seq.conf, seq.pred)]
+    seq.set_selection(np.zeros(0, np.int32), np.zeros(0, np.int32))
+    say("select-none: empty S")
+    ctx.d2c_step(gp, [seq])
+    for a, b in zip(snap, (seq.k_cache, seq.v_cache, seq.conf, seq.pred)):
+        assert torch.equal(a, b)
+    np.testing.assert_array_equal(host(seq.influence), np.ones(su.seq_len, np.float32))     # S = {} => c = 1
+    ctx.close()
+
+
+def test_step_bf16_small_teacher_forced(B):
+    """A narrow bf16 model (GQA, head_dim 64), 24 steps, two blocks."""
+    wd = W.ModelDims(3, 512, 8, 2, 64, 1408, 2048, dtype="bf16")
+    su = W.DecodeSetup(40, 24, 12, 1, k=6, p=0.3)
+    mdl = W.model_weights(wd, 3)
+    _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=24)
+
+
+def test_step_batch_of_ragged_sequences(B):
+    """Two independent sequences of different length in one d2c_step call equal two separate calls."""
+    wd = W.ModelDims(2, 256, 4, 4, 64, 688, 512, dtype="bf16")
+    mdl = W.model_weights(wd, 4)
+    ctx = B.Context(wd, mdl, 96)
+    sus = [W.DecodeSetup(32, 32, 16, 2, k=8, p=0.2), W.DecodeSetup(64, 32, 32, 2, k=8, p=0.2)]
+    gp = B.make_params(10.0, 8, 0.2, 16, 2, 0)
+    pairs = []
+    for b, su in enumerate(sus):
+        y0, m0 = W.initial_sequence(wd, su, 7, seq=b)
+        pairs.append((B.Sequence_(ctx, y0, m0, su.prompt_len), B.Sequence_(ctx, y0, m0, su.prompt_len)))
+    for t in range(6):
+        say(f"batched d2c_step t={t}")
+        ctx.d2c_step(gp, [p[0] for p in pairs])
+        for p in pairs:
+            ctx.d2c_step(gp, [p[1]])
+        for a, b in pairs:
+            assert (a.n_s, a.n_rows, a.n_masked) == (b.n_s, b.n_rows, b.n_masked)
+            assert a.n_masked == a.L - a.prompt_len - 2 * (t + 1)
+            for name in ("tokens", "is_masked", "k_cache", "v_cache", "conf", "pred", "influence"):
+                assert torch.equal(getattr(a, name), getattr(b, name)), name
+            assert torch.equal(a.s_idx[: a.n_s], b.s_idx[: b.n_s])
+    ctx.close()
+
+
+def test_step_llada_shape_reduced_depth(B):
+    """LLaDA-8B geometry at full width and full vocabulary, 2 of the 32 layers: step 0 (all 512 rows)
+    and two d2Cache steps, teacher-forced."""
+    wd, su = W.with_layers(W.DIMS["C3"], 2), W.SETUP["C3"]
+    mdl = W.model_weights(wd, 0)
+    _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=3)
