@@ -184,6 +184,13 @@ int d2c_attention(d2c_ctx* ctx, const void* q, const int32_t* idx, int32_t m,
                   const void* new_k, const void* new_v, void* k_cache, void* v_cache,
                   int32_t L, void* out, float* attn_avg, void* stream);
 
+/* The projection kernel on its own: out[m, N] (float) = a[m, K] * w[N, K]^T with a and w
+ * of storage type T and fp32 accumulation -- the ragged-row, weight-streaming GEMM
+ * every projection of the partial forward (Eq. 5) runs through.  K and the row
+ * pitches must be multiples of 16 bytes of T; m <= max_seq. */
+int d2c_linear(d2c_ctx* ctx, const void* a, const void* w, int32_t m, int32_t N, int32_t K,
+               float* out, void* stream);
+
 /* c_j = [j not in S] + sum_i C_S[i, j] (Eq. 9 on the compact block). */
 int d2c_influence(d2c_ctx* ctx, const float* rollout, const int32_t* idx, int32_t m,
                   int32_t L, float* influence, void* stream);

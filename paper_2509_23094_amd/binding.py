@@ -52,7 +52,7 @@ class d2c_seq_state(C.Structure):
 
 
 EXPORTS = ["d2c_init", "d2c_destroy", "d2c_last_error", "d2c_seq_reset", "d2c_select", "d2c_refresh_layer",
-           "d2c_attention", "d2c_influence", "d2c_step", "d2c_workspace_bytes", "d2c_set_tunable"]
+           "d2c_attention", "d2c_influence", "d2c_linear", "d2c_step", "d2c_workspace_bytes", "d2c_set_tunable"]
 
 
 def load_library() -> C.CDLL:
@@ -71,6 +71,7 @@ def load_library() -> C.CDLL:
     lib.d2c_refresh_layer.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp]
     lib.d2c_attention.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, i32, vp, vp, vp]
     lib.d2c_influence.argtypes = [vp, vp, vp, i32, i32, vp, vp]
+    lib.d2c_linear.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
     lib.d2c_step.argtypes = [vp, C.POINTER(d2c_params), C.POINTER(d2c_seq_state), i32, vp]
     lib.d2c_workspace_bytes.argtypes = [vp]
     lib.d2c_workspace_bytes.restype = C.c_int64
@@ -202,6 +203,9 @@ class Context:
     def d2c_attention(self, q, idx, m, new_k, new_v, k_cache, v_cache, L, out, attn_avg=None) -> None:
         self._check(_lib.d2c_attention(self.handle, _ptr(q), _ptr(idx), m, _ptr(new_k), _ptr(new_v), _ptr(k_cache),
                                        _ptr(v_cache), L, _ptr(out), _ptr(attn_avg), _stream()))
+
+    def d2c_linear(self, a, w, m, N, K, out) -> None:
+        self._check(_lib.d2c_linear(self.handle, _ptr(a), _ptr(w), m, N, K, _ptr(out), _stream()))
 
     def d2c_influence(self, rollout, idx, m, L, influence) -> None:
         self._check(_lib.d2c_influence(self.handle, _ptr(rollout), _ptr(idx), m, L, _ptr(influence), _stream()))

@@ -317,6 +317,27 @@ int d2c_attention(d2c_ctx* c, const void* q, const int32_t* idx, int32_t m, cons
   return D2C_OK;
 }
 
+int d2c_linear(d2c_ctx* c, const void* a, const void* w, int32_t m, int32_t N, int32_t K, float* out, void* stream) {
+  if (!c) return D2C_EINVAL;
+  if (m < 0 || N <= 0 || K <= 0) return fail(c, D2C_EINVAL, "bad m, N or K");
+  if (m > c->dims.max_seq) return fail(c, D2C_ESHAPE, "m exceeds max_seq of the context");
+  if (K % (c->dims.dtype == D2C_BF16 ? 8 : 4)) return fail(c, D2C_ESHAPE, "K must be a multiple of 16 bytes of T");
+  if (m == 0) return D2C_OK;
+  if (!a || !w || !out) return fail(c, D2C_EINVAL, "null buffer");
+  hipStream_t st = (hipStream_t)stream;
+  GemmPlan pl = plan_gemm(c->dims.dtype, m, N, K);
+  const size_t stride = (size_t)m * N;
+  if (stride * pl.splits > c->partial_floats) pl = plan_gemm(c->dims.dtype, m, N, K, true);   // no room for partials
+  if (pl.splits == 1) {
+    D2C_HIP(c, launch_gemm(c->dims.dtype, pl, a, K, w, K, out, N, stride, m, N, K, st));
+    return D2C_OK;
+  }
+  if (stride * pl.splits > c->partial_floats) return fail(c, D2C_ESHAPE, "projection partials exceed workspace");
+  D2C_HIP(c, launch_gemm(c->dims.dtype, pl, a, K, w, K, c->partial, N, stride, m, N, K, st));
+  D2C_HIP(c, launch_sum_splits(out, c->partial, pl.splits, stride, stride, st));
+  return D2C_OK;
+}
+
 int d2c_influence(d2c_ctx* c, const float* rollout, const int32_t* idx, int32_t m, int32_t L, float* influence,
                   void* stream) {
   if (!c) return D2C_EINVAL;

@@ -47,10 +47,11 @@ __device__ __forceinline__ void mfma16(f32x4& acc, const Frag<bf16>& a, const Fr
                                                 __builtin_bit_cast(bf16x8, b.raw), acc, 0, 0, 0);
 }
 __device__ __forceinline__ void mfma16(f32x4& acc, const Frag<float>& a, const Frag<float>& b) {
-#pragma unroll
-  for (int e = 0; e < 4; ++e)
-    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__builtin_bit_cast(float, a.raw[e]),
-                                               __builtin_bit_cast(float, b.raw[e]), acc, 0, 0, 0);
+  const f32x4 af = __builtin_bit_cast(f32x4, a.raw), bf = __builtin_bit_cast(f32x4, b.raw);
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(af.x, bf.x, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(af.y, bf.y, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(af.z, bf.z, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(af.w, bf.w, acc, 0, 0, 0);
 }
 
 __device__ __forceinline__ u32x4 ld16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }

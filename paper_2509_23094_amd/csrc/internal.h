@@ -54,6 +54,8 @@ hipError_t launch_swiglu(int dtype, const float* P, int n_splits, size_t split_s
 hipError_t launch_scatter_rows(int dtype, const void* rows, const int32_t* idx, int m, int width, void* cache,
                                hipStream_t st);
 hipError_t launch_copy_f32(float* dst, const float* src, size_t n, hipStream_t st);
+// dst[i] = sum_s P[s*split_stride + i], i < n
+hipError_t launch_sum_splits(float* dst, const float* P, int n_splits, size_t split_stride, size_t n, hipStream_t st);
 // cos/sin table [max_pos, head_dim/2], angles evaluated in fp64
 hipError_t launch_rope_table(float* cos_t, float* sin_t, int max_pos, int head_dim, float theta, hipStream_t st);
 

@@ -155,6 +155,17 @@ __global__ void copy_f32_kernel(float* __restrict__ dst, const float* __restrict
   for (; i < n; i += stride) dst[i] = src[i];
 }
 
+__global__ void sum_splits_kernel(float* __restrict__ dst, const float* __restrict__ P, int n_splits,
+                                  size_t split_stride, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    float v = 0.f;
+    for (int s = 0; s < n_splits; ++s) v += P[(size_t)s * split_stride + i];
+    dst[i] = v;
+  }
+}
+
 // Angles in fp64 so that the table is the correctly rounded cos/sin of
 // pos * theta^(-2i/head_dim) at every position the cache can hold.
 __global__ void rope_table_kernel(float* __restrict__ cos_t, float* __restrict__ sin_t, int max_pos, int half,
@@ -250,6 +261,13 @@ hipError_t launch_copy_f32(float* dst, const float* src, size_t n, hipStream_t s
   if (n == 0) return hipSuccess;
   const int blocks = (int)((n + 1023) / 1024 < 2048 ? (n + 1023) / 1024 : 2048);
   hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks), dim3(256), 0, st, dst, src, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_sum_splits(float* dst, const float* P, int n_splits, size_t split_stride, size_t n, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  const int blocks = (int)((n + 1023) / 1024 < 2048 ? (n + 1023) / 1024 : 2048);
+  hipLaunchKernelGGL(sum_splits_kernel, dim3(blocks), dim3(256), 0, st, dst, P, n_splits, split_stride, n);
   return hipGetLastError();
 }
 

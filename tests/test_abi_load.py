@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
 def test_binding_names_match_header():
     from paper_2509_23094_amd import binding
     assert sorted(binding.EXPORTS) == _declared_functions()
-    for name in ("d2c_select", "d2c_refresh_layer", "d2c_step", "d2c_attention", "d2c_influence", "d2c_seq_reset"):
+    for name in ("d2c_select", "d2c_refresh_layer", "d2c_step", "d2c_attention", "d2c_influence", "d2c_seq_reset", "d2c_linear"):
         assert hasattr(binding.Context, name)
 
 

@@ -28,6 +28,33 @@ def _ctx_for(B, wd, max_seq, n_layers=1, seed=0, tiny_vocab=None):
     return B.Context(dims, mdl, max_seq), dims, mdl
 
 
+# ------------------------------------------------------------------ the ragged-row projection
+LINEAR_CASES = [
+    # dtype, m, N, K
+    ("f32", 1, 16, 16), ("f32", 72, 768, 256), ("f32", 128, 1376, 256), ("f32", 37, 256, 688), ("f32", 5, 40, 20),
+    ("f32", 200, 100, 132),
+    ("bf16", 1, 64, 128), ("bf16", 83, 1024, 512), ("bf16", 17, 40, 72), ("bf16", 96, 4096, 1408),
+    ("bf16", 130, 200, 264), ("bf16", 300, 3000, 520), ("bf16", 64, 33000, 256),
+]
+
+
+@pytest.mark.parametrize("dtype,m,N,K", LINEAR_CASES)
+def test_linear_parity(B, dtype, m, N, K):
+    say(f"linear dtype={dtype} m={m} N={N} K={K}")
+    wd = W.ModelDims(1, 256, 4, 4, 64, 80, 64, dtype=dtype)
+    ctx, _, _ = _ctx_for(B, wd, max_seq=max(m, 16))
+    a = W.hidden_rows(11, m, K)
+    w = W.hidden_rows(12, N, K, std=0.05)
+    if dtype == "bf16":
+        a, w = W.round_bf16(a), W.round_bf16(w)
+    out = torch.full((m, N), 7.0, dtype=torch.float32, device="cuda")
+    ctx.d2c_linear(B.to_device(a, dtype), B.to_device(w, dtype), m, N, K, out)
+    torch.cuda.synchronize()
+    ref = a.astype(np.float64) @ w.astype(np.float64).T          # exact inputs on both sides: fp32 accumulation only
+    assert rel_l2(host(out), ref) < 1e-5
+    ctx.close()
+
+
 # ------------------------------------------------------------------ attention (config "C2" and edge shapes)
 ATTN_CASES = [
     # dtype, H, Hkv, dh, L, m
