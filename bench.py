@@ -1,0 +1,221 @@
+"""Benchmark of the d2Cache selective-refresh decoding step on one MI355X.
+
+Workload: the LLaDA-8B-shaped random-init model (32 layers, d_model 4096, 32x128
+heads, SwiGLU 12288, vocabulary 126464, bf16), prompt 256 + 256 generated
+positions, blocks of 32, one token unmasked per step, sigma 10 / k 32 / p 0.1.
+A "step" is one d2c_step: partial forward of the selected rows through all 32
+layers with rollout, LM head + Eq. 1 on the masked rows, two-stage selection and
+unmasking.  Step 0 (all 512 rows) fills the caches before the clock starts.
+
+Prints one JSON line; see the design doc for how each field is measured.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def device_model(W, dims, seed, torch):
+    """Random-init weights N(0, 0.02) drawn on the device (seeded), in the storage type."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    tdt = torch.bfloat16 if dims.dtype == "bf16" else torch.float32
+
+    def normal(*shape):
+        t = torch.empty(shape, dtype=torch.float32, device="cuda")
+        t.normal_(0.0, 0.02, generator=g)
+        return t.to(tdt).contiguous()
+
+    ones = lambda n: torch.ones(n, dtype=torch.float32, device="cuda")
+    d, dq, dkv, f = dims.d_model, dims.d_q, dims.d_kv, dims.d_ffn
+    layers = []
+    for _ in range(dims.n_layers):
+        layers.append({"attn_norm": ones(d), "wqkv": normal(dq + 2 * dkv, d), "wo": normal(d, dq),
+                       "ffn_norm": ones(d), "w_gate_up": normal(2 * f, d), "w_down": normal(d, f)})
+    return {"tok_emb": normal(dims.vocab, d), "final_norm": ones(d), "lm_head": normal(dims.vocab, d),
+            "layers": layers}
+
+
+def fresh_sequence(B, W, ctx, dims, su, seed):
+    y0, m0 = W.initial_sequence(dims, su, seed)
+    return B.Sequence_(ctx, y0, m0, su.prompt_len)
+
+
+def cpu_baseline(W, dims, su, m_rows, n_logit_rows):
+    """The oracle on this machine's host cores, on a bounded sample of the same workload: one full-width
+    layer on m_rows selected rows, the LM head + Eq. 1 on n_logit_rows rows, rollout and both
+    selections at L = 512; the layer time is scaled by n_layers to a whole step."""
+    import numpy as np
+    from oracle import d2cache_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    od = O.Dims(1, dims.d_model, dims.n_heads, dims.n_kv_heads, dims.head_dim, dims.d_ffn, dims.vocab,
+                dims.rms_eps, dims.rope_theta)
+    L = su.seq_len
+    lw = W.layer_weights(dims, 0, 0)
+    head = W.lm_head(dims, 0)
+    S = W.distinct_sorted_rows(0, L, m_rows)
+    h = W.hidden_rows(0, m_rows, dims.d_model, std=0.5)
+    kc = W.round_bf16(W.hidden_rows(1, L, dims.d_kv)).astype(np.float64)
+    vc = W.round_bf16(W.hidden_rows(2, L, dims.d_kv)).astype(np.float64)
+    t0 = time.perf_counter()
+    h2, abar = O.refresh_layer(od, lw, h, S, kc, vc)
+    t_layer = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    C = O.rollout([abar], S, L)
+    t_roll = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    logits = O.lm_logits(od, {"final_norm": np.ones(dims.d_model), "lm_head": head}, h2[:n_logit_rows])
+    s, xh = O.confidence(logits)
+    t_head = time.perf_counter() - t0
+    is_masked = W.random_mask(0, L, su.prompt_len, 0.3).astype(bool)
+    conf = W.random_scores(0, L)
+    t0 = time.perf_counter()
+    O.select(O.Params(sigma=su.sigma, k=su.k, p=su.p, block_len=su.block_len, n_unmask=su.n_unmask), is_masked,
+             su.prompt_len, conf, O.influence(C).astype(np.float32))
+    t_sel = time.perf_counter() - t0
+    step_s = dims.n_layers * (t_layer + t_roll) + t_head + t_sel
+    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+            "sample": ("1 of %d full-width layers on %d rows (%.2f s) + its L x L rollout update (%.2f s), scaled x%d; "
+                       "LM head + Eq. 1 on %d rows (%.2f s); selection at L=%d (%.3f s)"
+                       % (dims.n_layers, m_rows, t_layer, t_roll, dims.n_layers, n_logit_rows, t_head, L, t_sel))}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=128)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="C3", choices=["C3", "C4"])
+    ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (the result is then not the metric)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-vanilla", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported (the path shards by sequence, "
+              "see DESIGN.md)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2509_23094_amd import binding as B
+    from paper_2509_23094_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dims, su = W.DIMS[args.workload], W.SETUP[args.workload]
+    if args.layers:
+        dims = W.with_layers(dims, args.layers)
+    K, Wm = args.steps, args.warmup
+    per_gen = su.gen_len // su.n_unmask - 1              # d2Cache steps one generation offers after step 0
+    assert Wm < per_gen, "warmup must be shorter than one generation"
+
+    mdl = device_model(W, dims, 0, torch)
+    ctx = B.Context(dims, mdl, su.seq_len, device_weights=True)
+    prm = B.make_params(su.sigma, su.k, su.p, su.block_len, su.n_unmask, 0)
+
+    def run_steps(seq, n, collect=None):
+        for _ in range(n):
+            if collect is not None:
+                collect.append((seq.n_s, seq.n_rows))
+            ctx.d2c_step(prm, [seq])
+
+    # ---- timed region: exactly K d2Cache steps (in as many generations as needed), after W warm-up steps
+    elapsed, done, shapes, gen = 0.0, 0, [], 0
+    while done < K:
+        seq = fresh_sequence(B, W, ctx, dims, su, gen)
+        run_steps(seq, 1)                                 # step 0: every row, fills the caches (not timed)
+        run_steps(seq, Wm if gen == 0 else 0)             # warm-up
+        n = min(K - done, per_gen - (Wm if gen == 0 else 0))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_steps(seq, n, shapes)
+        torch.cuda.synchronize()
+        elapsed += time.perf_counter() - t0
+        done += n
+        gen += 1
+    ms_per_step = 1e3 * elapsed / K
+    mean_m = float(np.mean([s[0] for s in shapes]))
+    mean_rows = float(np.mean([s[1] for s in shapes]))
+
+    # ---- roofline pass: the same steps again with an event pair around every launch
+    seq = fresh_sequence(B, W, ctx, dims, su, 0)
+    run_steps(seq, 1 + Wm)
+    n_prof = min(K, per_gen - Wm)
+    torch.cuda.synchronize()
+    ctx.d2c_profile_begin()
+    run_steps(seq, n_prof)
+    prof = ctx.d2c_profile_end()
+    gm = prof["gemm"]
+    gemm_ms = gm["ms"] / max(1, gm["launches"])
+    gemm_gbs = gm["bytes"] / max(1e-12, gm["ms"] * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "gemm_rows_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+    roofline = {"bound": "hbm", "kernel": "gemm_rows_kernel", "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(gemm_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "avg_launch_us": round(1e3 * gemm_ms, 2), "launches_per_step": gm["launches"] / n_prof,
+                "bytes_per_launch": gm["bytes"] / max(1, gm["launches"]),
+                "measured": "HIP events around every projection launch, repeat of the timed steps"}
+    by_class = {k: {"ms_per_step": round(v["ms"] / n_prof, 4), "launches_per_step": v["launches"] / n_prof}
+                for k, v in prof.items()}
+    step_bytes = gm["bytes"] / n_prof + prof["attention"]["bytes"] / n_prof
+
+    # ---- full recomputation (the paper's Vanilla): the same engine with every row selected
+    vanilla = None
+    if not args.no_vanilla:
+        seqv = fresh_sequence(B, W, ctx, dims, su, 0)
+        # k >= |M|, p = 1 and a single block select every row at every step
+        pv = B.make_params(su.sigma, su.seq_len, 1.0, su.gen_len, su.n_unmask, 0)
+        for _ in range(2):
+            ctx.d2c_step(pv, [seqv])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        nv = 4
+        for _ in range(nv):
+            assert seqv.n_s == su.seq_len
+            ctx.d2c_step(pv, [seqv])
+        torch.cuda.synchronize()
+        vanilla = {"ms_per_step": round(1e3 * (time.perf_counter() - t0) / nv, 3), "rows_per_step": su.seq_len}
+        vanilla["steps_per_sec"] = round(1e3 / vanilla["ms_per_step"], 2)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(W, dims, su, int(round(mean_m)), max(1, int(round(mean_rows))))
+
+    out = {
+        "metric": "d2cache_steps_per_sec", "value": round(K / elapsed, 3), "unit": "steps/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dims.dtype,
+        "data": "synthetic",
+        "config": {"workload": "%s: %s-shaped random-init model, %d layers, d_model %d, %dx%d heads, FFN %d, "
+                               "vocab %d; prompt %d + gen %d, block %d, %d token/step, sigma %g k %d p %g"
+                               % (args.workload, {"C3": "LLaDA-8B", "C4": "Dream-7B"}[args.workload], dims.n_layers, dims.d_model, dims.n_heads, dims.head_dim, dims.d_ffn,
+                                  dims.vocab, su.prompt_len, su.gen_len, su.block_len, su.n_unmask, su.sigma, su.k,
+                                  su.p),
+                   "batch": 1, "seq_len": su.seq_len, "mean_rows_per_step": round(mean_m, 2),
+                   "mean_logit_rows_per_step": round(mean_rows, 2)},
+        "tokens_per_sec": round(su.n_unmask * K / elapsed, 3),
+        "algorithmic_gb_per_step": round(step_bytes / 1e9, 3),
+        "step_hbm_frac": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "roofline": roofline, "kernel_classes": by_class, "full_recompute": vanilla, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

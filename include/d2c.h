@@ -205,6 +205,21 @@ int d2c_step(d2c_ctx* ctx, const d2c_params* params, d2c_seq_state* seqs, int32_
 /* Bytes of device workspace the context holds. */
 int64_t d2c_workspace_bytes(const d2c_ctx* ctx);
 
+/* Per-launch timing with HIP events on the stream the kernels run on, by kernel class.
+ * Between d2c_profile_begin and d2c_profile_end every launch of the calls above is
+ * bracketed by an event pair (this perturbs the stream: do not time end-to-end while
+ * it is on).  d2c_profile_end waits for the events and returns, per class, the summed
+ * kernel time in milliseconds, the number of launches and the summed algorithmic
+ * bytes (projection: the weight matrix once; attention: the K and V cache once). */
+#define D2C_PROF_GEMM      0
+#define D2C_PROF_ATTENTION 1
+#define D2C_PROF_ROLLOUT   2
+#define D2C_PROF_ROWWISE   3
+#define D2C_PROF_SELECT    4
+#define D2C_PROF_CLASSES   5
+int d2c_profile_begin(d2c_ctx* ctx);
+int d2c_profile_end(d2c_ctx* ctx, double* ms, int64_t* launches, double* bytes);
+
 /* Launch-shape tunables of the projection kernel, process-wide; set them before
  * d2c_init.  Names: "gemm_target_wgs", "gemm_max_splits" (1..8), "gemm_nt_big_n".
  * Returns D2C_EINVAL for an unknown name. */

@@ -19,6 +19,9 @@ D2C_F32, D2C_BF16 = 0, 1
 CNT_MSTAR, CNT_U, CNT_S, CNT_DECODE, CNT_NEXT_ROWS, CNT_MASKED, CNT_BLOCK_LO, CNT_BLOCK_HI, N_COUNTS = range(9)
 
 
+PROF_CLASSES = ("gemm", "attention", "rollout", "rowwise", "select")
+
+
 class D2CError(RuntimeError):
     def __init__(self, code: int, msg: str):
         super().__init__("d2c error %d: %s" % (code, msg))
@@ -52,7 +55,7 @@ class d2c_seq_state(C.Structure):
 
 
 EXPORTS = ["d2c_init", "d2c_destroy", "d2c_last_error", "d2c_seq_reset", "d2c_select", "d2c_refresh_layer",
-           "d2c_attention", "d2c_influence", "d2c_linear", "d2c_step", "d2c_workspace_bytes", "d2c_set_tunable"]
+           "d2c_attention", "d2c_influence", "d2c_linear", "d2c_step", "d2c_profile_begin", "d2c_profile_end", "d2c_workspace_bytes", "d2c_set_tunable"]
 
 
 def load_library() -> C.CDLL:
@@ -73,6 +76,8 @@ def load_library() -> C.CDLL:
     lib.d2c_influence.argtypes = [vp, vp, vp, i32, i32, vp, vp]
     lib.d2c_linear.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
     lib.d2c_step.argtypes = [vp, C.POINTER(d2c_params), C.POINTER(d2c_seq_state), i32, vp]
+    lib.d2c_profile_begin.argtypes = [vp]
+    lib.d2c_profile_end.argtypes = [vp, vp, vp, vp]
     lib.d2c_workspace_bytes.argtypes = [vp]
     lib.d2c_workspace_bytes.restype = C.c_int64
     lib.d2c_set_tunable.argtypes = [C.c_char_p, i32]
@@ -203,6 +208,15 @@ class Context:
     def d2c_attention(self, q, idx, m, new_k, new_v, k_cache, v_cache, L, out, attn_avg=None) -> None:
         self._check(_lib.d2c_attention(self.handle, _ptr(q), _ptr(idx), m, _ptr(new_k), _ptr(new_v), _ptr(k_cache),
                                        _ptr(v_cache), L, _ptr(out), _ptr(attn_avg), _stream()))
+
+    def d2c_profile_begin(self) -> None:
+        self._check(_lib.d2c_profile_begin(self.handle))
+
+    def d2c_profile_end(self) -> Dict[str, Dict[str, float]]:
+        n = len(PROF_CLASSES)
+        ms, cnt, by = (C.c_double * n)(), (C.c_int64 * n)(), (C.c_double * n)()
+        self._check(_lib.d2c_profile_end(self.handle, ms, cnt, by))
+        return {name: {"ms": ms[i], "launches": int(cnt[i]), "bytes": by[i]} for i, name in enumerate(PROF_CLASSES)}
 
     def d2c_linear(self, a, w, m, N, K, out) -> None:
         self._check(_lib.d2c_linear(self.handle, _ptr(a), _ptr(w), m, N, K, _ptr(out), _stream()))

@@ -43,6 +43,12 @@ struct d2c_ctx {
   float* rope_sin = nullptr;
   int32_t* counts_host = nullptr;   // pinned
   int counts_host_cap = 0;
+  // optional per-launch timing with HIP events (d2c_profile_begin / d2c_profile_end)
+  bool prof_on = false;
+  std::vector<hipEvent_t> prof_ev;  // start/stop pairs
+  std::vector<int> prof_cls;
+  std::vector<double> prof_bytes;
+  size_t prof_used = 0;
   std::string err;
 };
 
@@ -60,6 +66,38 @@ int fail(d2c_ctx* ctx, int code, const std::string& msg) {
     hipError_t e_ = (expr);                                                                 \
     if (e_ != hipSuccess)                                                                   \
       return fail(ctx, D2C_EHIP, std::string(#expr) + ": " + hipGetErrorString(e_));        \
+  } while (0)
+
+constexpr size_t kProfMaxPairs = 1 << 17;
+
+// Records a start event for one launch of class cls; returns the pair's slot or -1.
+int prof_start(d2c_ctx* c, hipStream_t st, int cls, double bytes) {
+  if (!c->prof_on || c->prof_used >= kProfMaxPairs) return -1;
+  const size_t slot = c->prof_used;
+  if (c->prof_ev.size() < 2 * (slot + 1)) {
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess) return -1;
+    if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return -1; }
+    c->prof_ev.push_back(a);
+    c->prof_ev.push_back(b);
+    c->prof_cls.push_back(0);
+    c->prof_bytes.push_back(0.0);
+  }
+  c->prof_cls[slot] = cls;
+  c->prof_bytes[slot] = bytes;
+  if (hipEventRecord(c->prof_ev[2 * slot], st) != hipSuccess) return -1;
+  c->prof_used = slot + 1;
+  return (int)slot;
+}
+void prof_stop(d2c_ctx* c, hipStream_t st, int slot) {
+  if (slot >= 0) (void)hipEventRecord(c->prof_ev[2 * (size_t)slot + 1], st);
+}
+
+#define D2C_TIMED(ctx, st, cls, nbytes, expr)              \
+  do {                                                     \
+    const int slot_ = prof_start(ctx, st, cls, nbytes);    \
+    D2C_HIP(ctx, expr);                                    \
+    prof_stop(ctx, st, slot_);                             \
   } while (0)
 
 template <typename P>
@@ -88,7 +126,8 @@ int project(d2c_ctx* c, const void* A, int lda, const void* W, int m, int N, int
   const size_t stride = (size_t)m * N;
   float* P = dst ? dst : c->partial;
   if (!dst && stride * pl.splits > c->partial_floats) return fail(c, D2C_ESHAPE, "projection partials exceed workspace");
-  D2C_HIP(c, launch_gemm(c->dims.dtype, pl, A, lda, W, K, P, N, stride, m, N, K, st));
+  D2C_TIMED(c, st, D2C_PROF_GEMM, (double)N * K * tsize(c),
+            launch_gemm(c->dims.dtype, pl, A, lda, W, K, P, N, stride, m, N, K, st));
   *plan_out = pl;
   *stride_out = stride;
   return D2C_OK;
@@ -105,22 +144,28 @@ int layer_impl(d2c_ctx* c, int layer, float* hidden, const int32_t* idx, int m, 
   size_t stride;
   int rc;
   if (!a_ready)
-    D2C_HIP(c, launch_add_norm(dt, hidden, nullptr, 0, 0, d, m, d, c->attn_norm[layer], D.rms_eps, c->a_norm, st));
+    D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
+              launch_add_norm(dt, hidden, nullptr, 0, 0, d, m, d, c->attn_norm[layer], D.rms_eps, c->a_norm, st));
   if ((rc = project(c, c->a_norm, d, c->wqkv[layer], m, dq + 2 * dkv, d, &pl, &stride, st)) != D2C_OK) return rc;
-  D2C_HIP(c, launch_qkv_rope_scatter(dt, c->partial, pl.splits, stride, dq + 2 * dkv,
-                                     c->bqkv.empty() ? nullptr : c->bqkv[layer], idx, m, D.n_heads, D.n_kv_heads,
-                                     D.head_dim, c->rope_cos, c->rope_sin, c->q, k_cache, v_cache, st));
-  D2C_HIP(c, launch_attention(dt, c->q, k_cache, v_cache, m, L, D.n_heads, D.n_kv_heads, D.head_dim, c->attn_o,
-                              c->lse, abar, st));
-  if (abar && roll_out) D2C_HIP(c, launch_rollout(abar, roll_in, roll_out, idx, m, L, layer == 0, st));
+  D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
+            launch_qkv_rope_scatter(dt, c->partial, pl.splits, stride, dq + 2 * dkv,
+                                    c->bqkv.empty() ? nullptr : c->bqkv[layer], idx, m, D.n_heads, D.n_kv_heads,
+                                    D.head_dim, c->rope_cos, c->rope_sin, c->q, k_cache, v_cache, st));
+  D2C_TIMED(c, st, D2C_PROF_ATTENTION, 2.0 * L * dkv * tsize(c),
+            launch_attention(dt, c->q, k_cache, v_cache, m, L, D.n_heads, D.n_kv_heads, D.head_dim, c->attn_o,
+                             c->lse, abar, st));
+  if (abar && roll_out)
+    D2C_TIMED(c, st, D2C_PROF_ROLLOUT, 0.0, launch_rollout(abar, roll_in, roll_out, idx, m, L, layer == 0, st));
   if ((rc = project(c, c->attn_o, dq, c->wo[layer], m, d, dq, &pl, &stride, st)) != D2C_OK) return rc;
-  D2C_HIP(c, launch_add_norm(dt, hidden, c->partial, pl.splits, stride, d, m, d, c->ffn_norm[layer], D.rms_eps,
-                             c->a_norm, st));
+  D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
+            launch_add_norm(dt, hidden, c->partial, pl.splits, stride, d, m, d, c->ffn_norm[layer], D.rms_eps,
+                            c->a_norm, st));
   if ((rc = project(c, c->a_norm, d, c->w_gate_up[layer], m, 2 * F, d, &pl, &stride, st)) != D2C_OK) return rc;
-  D2C_HIP(c, launch_swiglu(dt, c->partial, pl.splits, stride, 2 * F, m, F, c->act, st));
+  D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0, launch_swiglu(dt, c->partial, pl.splits, stride, 2 * F, m, F, c->act, st));
   if ((rc = project(c, c->act, F, c->w_down[layer], m, d, F, &pl, &stride, st)) != D2C_OK) return rc;
-  D2C_HIP(c, launch_add_norm(dt, hidden, c->partial, pl.splits, stride, d, m, d, next_gain, D.rms_eps,
-                             next_gain ? c->a_norm : nullptr, st));
+  D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
+            launch_add_norm(dt, hidden, c->partial, pl.splits, stride, d, m, d, next_gain, D.rms_eps,
+                            next_gain ? c->a_norm : nullptr, st));
   return D2C_OK;
 }
 
@@ -221,6 +266,7 @@ int d2c_destroy(d2c_ctx* c) {
   if (!c) return D2C_OK;
   for (void* p : c->allocs) (void)hipFree(p);
   if (c->counts_host) (void)hipHostFree(c->counts_host);
+  for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
   delete c;
   return D2C_OK;
 }
@@ -236,6 +282,31 @@ int d2c_set_tunable(const char* name, int32_t value) {
   else if (!strcmp(name, "gemm_max_splits")) t.gemm_max_splits = std::max(1, std::min(8, (int)value));
   else if (!strcmp(name, "gemm_nt_big_n")) t.gemm_nt_big_n = value;
   else return D2C_EINVAL;
+  return D2C_OK;
+}
+
+int d2c_profile_begin(d2c_ctx* c) {
+  if (!c) return D2C_EINVAL;
+  c->prof_on = true;
+  c->prof_used = 0;
+  return D2C_OK;
+}
+
+int d2c_profile_end(d2c_ctx* c, double* ms, int64_t* launches, double* bytes) {
+  if (!c) return D2C_EINVAL;
+  if (!ms || !launches || !bytes) return fail(c, D2C_EINVAL, "null output");
+  c->prof_on = false;
+  for (int k = 0; k < D2C_PROF_CLASSES; ++k) { ms[k] = 0.0; launches[k] = 0; bytes[k] = 0.0; }
+  for (size_t i = 0; i < c->prof_used; ++i) {
+    D2C_HIP(c, hipEventSynchronize(c->prof_ev[2 * i + 1]));
+    float t = 0.f;
+    D2C_HIP(c, hipEventElapsedTime(&t, c->prof_ev[2 * i], c->prof_ev[2 * i + 1]));
+    const int k = c->prof_cls[i];
+    ms[k] += (double)t;
+    launches[k] += 1;
+    bytes[k] += c->prof_bytes[i];
+  }
+  c->prof_used = 0;
   return D2C_OK;
 }
 
@@ -312,8 +383,9 @@ int d2c_attention(d2c_ctx* c, const void* q, const int32_t* idx, int32_t m, cons
     D2C_HIP(c, launch_scatter_rows(D.dtype, new_k, idx, m, d_kv(c), k_cache, st));
     D2C_HIP(c, launch_scatter_rows(D.dtype, new_v, idx, m, d_kv(c), v_cache, st));
   }
-  D2C_HIP(c, launch_attention(D.dtype, q, k_cache, v_cache, m, L, D.n_heads, D.n_kv_heads, D.head_dim, out, c->lse,
-                              attn_avg, st));
+  D2C_TIMED(c, st, D2C_PROF_ATTENTION, 2.0 * L * d_kv(c) * tsize(c),
+            launch_attention(D.dtype, q, k_cache, v_cache, m, L, D.n_heads, D.n_kv_heads, D.head_dim, out, c->lse,
+                             attn_avg, st));
   return D2C_OK;
 }
 
@@ -329,11 +401,13 @@ int d2c_linear(d2c_ctx* c, const void* a, const void* w, int32_t m, int32_t N, i
   const size_t stride = (size_t)m * N;
   if (stride * pl.splits > c->partial_floats) pl = plan_gemm(c->dims.dtype, m, N, K, true);   // no room for partials
   if (pl.splits == 1) {
-    D2C_HIP(c, launch_gemm(c->dims.dtype, pl, a, K, w, K, out, N, stride, m, N, K, st));
+    D2C_TIMED(c, st, D2C_PROF_GEMM, (double)N * K * tsize(c),
+              launch_gemm(c->dims.dtype, pl, a, K, w, K, out, N, stride, m, N, K, st));
     return D2C_OK;
   }
   if (stride * pl.splits > c->partial_floats) return fail(c, D2C_ESHAPE, "projection partials exceed workspace");
-  D2C_HIP(c, launch_gemm(c->dims.dtype, pl, a, K, w, K, c->partial, N, stride, m, N, K, st));
+  D2C_TIMED(c, st, D2C_PROF_GEMM, (double)N * K * tsize(c),
+            launch_gemm(c->dims.dtype, pl, a, K, w, K, c->partial, N, stride, m, N, K, st));
   D2C_HIP(c, launch_sum_splits(out, c->partial, pl.splits, stride, stride, st));
   return D2C_OK;
 }
@@ -370,8 +444,9 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
     const int m = s.n_s, L = s.L;
     float* roll_final = nullptr;
     if (m > 0) {
-      D2C_HIP(c, launch_embed_norm(dt, c->tok_emb, s.tokens, s.s_idx, m, d, c->attn_norm[0], D.rms_eps, c->hidden,
-                                   c->a_norm, st));
+      D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
+                launch_embed_norm(dt, c->tok_emb, s.tokens, s.s_idx, m, d, c->attn_norm[0], D.rms_eps, c->hidden,
+                                  c->a_norm, st));
       for (int l = 0; l < D.n_layers; ++l) {
         char* kc = (char*)s.k_cache + (size_t)l * L * cache_layer;
         char* vc = (char*)s.v_cache + (size_t)l * L * cache_layer;
@@ -383,15 +458,17 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
       if (s.hidden_out)
         D2C_HIP(c, hipMemcpyAsync(s.hidden_out, c->hidden, (size_t)m * d * 4, hipMemcpyDeviceToDevice, st));
     }
-    D2C_HIP(c, launch_influence(roll_final, s.s_idx, m, L, s.influence, st));
+    D2C_TIMED(c, st, D2C_PROF_ROLLOUT, 0.0, launch_influence(roll_final, s.s_idx, m, L, s.influence, st));
     // Eq. 1 on the rows of S_t that are still masked, head_rows rows at a time
     for (int r0 = 0; r0 < s.n_rows; r0 += c->head_rows) {
       const int nr = std::min(c->head_rows, s.n_rows - r0);
-      D2C_HIP(c, launch_gather_norm(dt, c->hidden, s.s_rows + r0, nr, d, c->final_norm, D.rms_eps, c->head_a, st));
+      D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
+                launch_gather_norm(dt, c->hidden, s.s_rows + r0, nr, d, c->final_norm, D.rms_eps, c->head_a, st));
       GemmPlan pl;
       size_t stride;
       if ((rc = project(c, c->head_a, d, c->lm_head, nr, D.vocab, d, &pl, &stride, st, true, c->logits))) return rc;
-      D2C_HIP(c, launch_confidence(c->logits, s.s_rows + r0, s.s_idx, nr, D.vocab, s.conf, s.pred, st));
+      D2C_TIMED(c, st, D2C_PROF_SELECT, 0.0,
+                launch_confidence(c->logits, s.s_rows + r0, s.s_idx, nr, D.vocab, s.conf, s.pred, st));
       if (s.logits_out)
         D2C_HIP(c, hipMemcpyAsync(s.logits_out + (size_t)r0 * D.vocab, c->logits, (size_t)nr * D.vocab * 4,
                                   hipMemcpyDeviceToDevice, st));
@@ -399,7 +476,7 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
     SelectArgs a{p->sigma, p->k, p->p, p->block_len, p->n_unmask, p->cand_mode, s.tokens, s.is_masked, L,
                  s.prompt_len, s.conf, s.pred, s.influence, s.mstar, s.u_set, s.decode_idx, s.s_idx, s.s_rows,
                  s.counts, s.score};
-    D2C_HIP(c, launch_select(a, st));
+    D2C_TIMED(c, st, D2C_PROF_SELECT, 0.0, launch_select(a, st));
     D2C_HIP(c, hipMemcpyAsync(ch, s.counts, sizeof(int32_t) * D2C_N_COUNTS, hipMemcpyDeviceToHost, st));
   }
   D2C_HIP(c, hipStreamSynchronize(st));
