@@ -216,7 +216,8 @@ int64_t d2c_workspace_bytes(const d2c_ctx* ctx);
 #define D2C_PROF_ROLLOUT   2
 #define D2C_PROF_ROWWISE   3
 #define D2C_PROF_SELECT    4
-#define D2C_PROF_CLASSES   5
+#define D2C_PROF_ATTN_AVG  5
+#define D2C_PROF_CLASSES   6
 int d2c_profile_begin(d2c_ctx* ctx);
 int d2c_profile_end(d2c_ctx* ctx, double* ms, int64_t* launches, double* bytes);
 

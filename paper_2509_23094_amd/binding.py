@@ -19,7 +19,7 @@ D2C_F32, D2C_BF16 = 0, 1
 CNT_MSTAR, CNT_U, CNT_S, CNT_DECODE, CNT_NEXT_ROWS, CNT_MASKED, CNT_BLOCK_LO, CNT_BLOCK_HI, N_COUNTS = range(9)
 
 
-PROF_CLASSES = ("gemm", "attention", "rollout", "rowwise", "select")
+PROF_CLASSES = ("gemm", "attention", "rollout", "rowwise", "select", "attn_avg")
 
 
 class D2CError(RuntimeError):

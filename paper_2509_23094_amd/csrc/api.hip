@@ -28,10 +28,10 @@ struct d2c_ctx {
   int64_t ws_bytes = 0;
   float* hidden = nullptr;      // [max_seq, d]
   void* a_norm = nullptr;       // T [max_seq, d]
-  void* q = nullptr;            // T [max_seq, d_q]
+  void* q = nullptr;            // T [n_layers, max_seq, d_q]: one slot per layer (read later by the side stream)
   void* attn_o = nullptr;       // T [max_seq, d_q]
   void* act = nullptr;          // T [max_seq, F]
-  float* lse = nullptr;         // [H, max_seq]
+  float* lse = nullptr;         // [n_layers, H, max_seq]
   float* partial = nullptr;     // split partials of the current projection
   size_t partial_floats = 0;
   float* abar = nullptr;        // [max_seq, max_seq]
@@ -41,6 +41,12 @@ struct d2c_ctx {
   int head_rows = 0;
   float* rope_cos = nullptr;    // [max_seq, head_dim/2]
   float* rope_sin = nullptr;
+  // The head-averaged attention rows and the rollout only feed the selection at the end of a step, so
+  // d2c_step runs them on a second stream beside the projections: fwd_done[l] is recorded on the caller's
+  // stream after layer l's attention, side_done on the side stream after the last rollout update.
+  hipStream_t side = nullptr;
+  std::vector<hipEvent_t> fwd_done;
+  hipEvent_t side_done = nullptr;
   int32_t* counts_host = nullptr;   // pinned
   int counts_host_cap = 0;
   // optional per-launch timing with HIP events (d2c_profile_begin / d2c_profile_end)
@@ -135,11 +141,15 @@ int project(d2c_ctx* c, const void* A, int lda, const void* W, int m, int N, int
 
 // One block on m compact rows.  a_ready: ctx->a_norm already holds RMSNorm(hidden) * attn_norm[layer].
 // next_gain: when non-null the last kernel also leaves RMSNorm(hidden) * next_gain in ctx->a_norm.
+// side: the stream the head average and the rollout update run on; when it differs from st they are
+// ordered after this layer's attention by ctx->fwd_done[layer] and the caller joins them later.
 int layer_impl(d2c_ctx* c, int layer, float* hidden, const int32_t* idx, int m, void* k_cache, void* v_cache, int L,
                float* abar, const float* roll_in, float* roll_out, bool a_ready, const float* next_gain,
-               hipStream_t st) {
+               hipStream_t st, hipStream_t side) {
   const d2c_dims& D = c->dims;
   const int dt = D.dtype, d = D.d_model, dq = d_q(c), dkv = d_kv(c), F = D.d_ffn;
+  void* q = (char*)c->q + (size_t)layer * D.max_seq * dq * tsize(c);
+  float* lse = c->lse + (size_t)layer * D.n_heads * D.max_seq;
   GemmPlan pl;
   size_t stride;
   int rc;
@@ -150,12 +160,20 @@ int layer_impl(d2c_ctx* c, int layer, float* hidden, const int32_t* idx, int m, 
   D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
             launch_qkv_rope_scatter(dt, c->partial, pl.splits, stride, dq + 2 * dkv,
                                     c->bqkv.empty() ? nullptr : c->bqkv[layer], idx, m, D.n_heads, D.n_kv_heads,
-                                    D.head_dim, c->rope_cos, c->rope_sin, c->q, k_cache, v_cache, st));
+                                    D.head_dim, c->rope_cos, c->rope_sin, q, k_cache, v_cache, st));
   D2C_TIMED(c, st, D2C_PROF_ATTENTION, 2.0 * L * dkv * tsize(c),
-            launch_attention(dt, c->q, k_cache, v_cache, m, L, D.n_heads, D.n_kv_heads, D.head_dim, c->attn_o,
-                             c->lse, abar, st));
-  if (abar && roll_out)
-    D2C_TIMED(c, st, D2C_PROF_ROLLOUT, 0.0, launch_rollout(abar, roll_in, roll_out, idx, m, L, layer == 0, st));
+            launch_attention_fwd(dt, q, k_cache, v_cache, m, L, D.n_heads, D.n_kv_heads, D.head_dim, c->attn_o, lse,
+                                 st));
+  if (abar) {
+    if (side != st) {
+      D2C_HIP(c, hipEventRecord(c->fwd_done[layer], st));
+      D2C_HIP(c, hipStreamWaitEvent(side, c->fwd_done[layer], 0));
+    }
+    D2C_TIMED(c, side, D2C_PROF_ATTN_AVG, 0.0,
+              launch_attention_avg(dt, q, k_cache, lse, m, L, D.n_heads, D.n_kv_heads, D.head_dim, abar, side));
+    if (roll_out)
+      D2C_TIMED(c, side, D2C_PROF_ROLLOUT, 0.0, launch_rollout(abar, roll_in, roll_out, idx, m, L, layer == 0, side));
+  }
   if ((rc = project(c, c->attn_o, dq, c->wo[layer], m, d, dq, &pl, &stride, st)) != D2C_OK) return rc;
   D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
             launch_add_norm(dt, hidden, c->partial, pl.splits, stride, d, m, d, c->ffn_norm[layer], D.rms_eps,
@@ -243,8 +261,9 @@ int d2c_init(const d2c_dims* dims, const d2c_weights* w, d2c_ctx** out) {
   c->partial_floats = pf;
   c->head_rows = (int)std::min<size_t>(Lm, 256);
   if ((rc = ws_alloc(c, &c->hidden, Lm * d * 4)) || (rc = ws_alloc(c, &c->a_norm, Lm * d * ts)) ||
-      (rc = ws_alloc(c, &c->q, Lm * dq * ts)) || (rc = ws_alloc(c, &c->attn_o, Lm * dq * ts)) ||
-      (rc = ws_alloc(c, &c->act, Lm * F * ts)) || (rc = ws_alloc(c, &c->lse, (size_t)D.n_heads * Lm * 4)) ||
+      (rc = ws_alloc(c, &c->q, (size_t)D.n_layers * Lm * dq * ts)) || (rc = ws_alloc(c, &c->attn_o, Lm * dq * ts)) ||
+      (rc = ws_alloc(c, &c->act, Lm * F * ts)) ||
+      (rc = ws_alloc(c, &c->lse, (size_t)D.n_layers * D.n_heads * Lm * 4)) ||
       (rc = ws_alloc(c, &c->partial, pf * 4)) || (rc = ws_alloc(c, &c->abar, Lm * Lm * 4)) ||
       (rc = ws_alloc(c, &c->roll[0], Lm * Lm * 4)) || (rc = ws_alloc(c, &c->roll[1], Lm * Lm * 4)) ||
       (rc = ws_alloc(c, &c->head_a, (size_t)c->head_rows * d * ts)) ||
@@ -255,6 +274,14 @@ int d2c_init(const d2c_dims* dims, const d2c_weights* w, d2c_ctx** out) {
   c->counts_host_cap = 64;
   if (hipHostMalloc((void**)&c->counts_host, sizeof(int32_t) * D2C_N_COUNTS * c->counts_host_cap) != hipSuccess)
     return bail(fail(c, D2C_ENOMEM, "hipHostMalloc failed"));
+  if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess)
+    return bail(fail(c, D2C_EHIP, "hipStreamCreateWithFlags failed"));
+  c->fwd_done.assign(D.n_layers, nullptr);
+  for (int l = 0; l < D.n_layers; ++l)
+    if (hipEventCreateWithFlags(&c->fwd_done[l], hipEventDisableTiming) != hipSuccess)
+      return bail(fail(c, D2C_EHIP, "hipEventCreateWithFlags failed"));
+  if (hipEventCreateWithFlags(&c->side_done, hipEventDisableTiming) != hipSuccess)
+    return bail(fail(c, D2C_EHIP, "hipEventCreateWithFlags failed"));
   hipError_t e2 = launch_rope_table(c->rope_cos, c->rope_sin, D.max_seq, D.head_dim, D.rope_theta, nullptr);
   if (e2 == hipSuccess) e2 = hipStreamSynchronize(nullptr);
   if (e2 != hipSuccess) return bail(fail(c, D2C_EHIP, std::string("rope table: ") + hipGetErrorString(e2)));
@@ -267,6 +294,10 @@ int d2c_destroy(d2c_ctx* c) {
   for (void* p : c->allocs) (void)hipFree(p);
   if (c->counts_host) (void)hipHostFree(c->counts_host);
   for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
+  for (hipEvent_t e : c->fwd_done)
+    if (e) (void)hipEventDestroy(e);
+  if (c->side_done) (void)hipEventDestroy(c->side_done);
+  if (c->side) (void)hipStreamDestroy(c->side);
   delete c;
   return D2C_OK;
 }
@@ -281,6 +312,7 @@ int d2c_set_tunable(const char* name, int32_t value) {
   if (!strcmp(name, "gemm_target_wgs")) t.gemm_target_wgs = value;
   else if (!strcmp(name, "gemm_max_splits")) t.gemm_max_splits = std::max(1, std::min(8, (int)value));
   else if (!strcmp(name, "gemm_nt_big_n")) t.gemm_nt_big_n = value;
+  else if (!strcmp(name, "side_stream")) t.side_stream = value != 0;
   else return D2C_EINVAL;
   return D2C_OK;
 }
@@ -362,7 +394,7 @@ int d2c_refresh_layer(d2c_ctx* c, int32_t layer, float* hidden, const int32_t* i
     return fail(c, D2C_EINVAL, "attn_avg and rollout must both be given or both be null");
   hipStream_t st = (hipStream_t)stream;
   rc = layer_impl(c, layer, hidden, idx, m, k_cache, v_cache, L, attn_avg, rollout, rollout ? c->roll[0] : nullptr,
-                  false, nullptr, st);
+                  false, nullptr, st, st);
   if (rc) return rc;
   if (rollout) D2C_HIP(c, launch_copy_f32(rollout, c->roll[0], (size_t)m * L, st));
   return D2C_OK;
@@ -384,8 +416,12 @@ int d2c_attention(d2c_ctx* c, const void* q, const int32_t* idx, int32_t m, cons
     D2C_HIP(c, launch_scatter_rows(D.dtype, new_v, idx, m, d_kv(c), v_cache, st));
   }
   D2C_TIMED(c, st, D2C_PROF_ATTENTION, 2.0 * L * d_kv(c) * tsize(c),
-            launch_attention(D.dtype, q, k_cache, v_cache, m, L, D.n_heads, D.n_kv_heads, D.head_dim, out, c->lse,
-                             attn_avg, st));
+            launch_attention_fwd(D.dtype, q, k_cache, v_cache, m, L, D.n_heads, D.n_kv_heads, D.head_dim, out, c->lse,
+                                 st));
+  if (attn_avg)
+    D2C_TIMED(c, st, D2C_PROF_ATTN_AVG, 0.0,
+              launch_attention_avg(D.dtype, q, k_cache, c->lse, m, L, D.n_heads, D.n_kv_heads, D.head_dim, attn_avg,
+                                   st));
   return D2C_OK;
 }
 
@@ -435,6 +471,7 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
     if (s.n_s < 0 || s.n_s > s.L || s.n_rows < 0 || s.n_rows > s.n_s) return fail(c, D2C_EINVAL, "bad set sizes");
   }
   hipStream_t st = (hipStream_t)stream;
+  hipStream_t side = tunables().side_stream ? c->side : st;
   const int dt = D.dtype, d = D.d_model;
   const size_t ts = tsize(c), cache_layer = (size_t)d_kv(c) * ts;
   for (int b = 0; b < batch; ++b) {
@@ -451,10 +488,14 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
         char* kc = (char*)s.k_cache + (size_t)l * L * cache_layer;
         char* vc = (char*)s.v_cache + (size_t)l * L * cache_layer;
         rc = layer_impl(c, l, c->hidden, s.s_idx, m, kc, vc, L, c->abar, c->roll[l & 1], c->roll[(l + 1) & 1], true,
-                        l + 1 < D.n_layers ? c->attn_norm[l + 1] : nullptr, st);
+                        l + 1 < D.n_layers ? c->attn_norm[l + 1] : nullptr, st, side);
         if (rc) return rc;
       }
       roll_final = c->roll[D.n_layers & 1];
+      if (side != st) {                       // join: the influence scores need the last rollout update
+        D2C_HIP(c, hipEventRecord(c->side_done, side));
+        D2C_HIP(c, hipStreamWaitEvent(st, c->side_done, 0));
+      }
       if (s.hidden_out)
         D2C_HIP(c, hipMemcpyAsync(s.hidden_out, c->hidden, (size_t)m * d * 4, hipMemcpyDeviceToDevice, st));
     }

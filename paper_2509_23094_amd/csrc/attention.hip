@@ -4,8 +4,9 @@
 // heads, Sec. 4.2 of the d2Cache paper), which the rollout (Eq. 6-8) consumes.
 //
 // bf16 path, two launches, no atomics (bit-reproducible):
-//   pass 1  one workgroup per (16-query tile, head); its 4 waves take key tiles
-//           round-robin, run an online softmax and merge through LDS.  Scores are
+//   pass 1  one workgroup per (16-query tile, head); its 8 waves take key tiles
+//           round-robin (next tile's loads in flight while one is consumed), run an
+//           online softmax each and merge through LDS.  Scores are
 //           computed transposed, S^T = K Q^T, so that the 16x16 accumulator layout
 //           (4 consecutive keys per lane for one query) IS the B operand of the
 //           16x16x16 matrix-core step of O^T = V^T P^T: P never leaves registers.
@@ -13,10 +14,10 @@
 //           values per lane and key) and a 4x4 in-register transpose turns them
 //           into the A operand (4 keys per lane for one head-dim value).
 //           Writes O (bf16) and the log-sum-exp per (head, row).
-//   pass 2  one wave per (16-query tile, 16-key tile) loops over the heads,
-//           recomputes S^T and accumulates exp(s - lse) in registers; one
-//           16-byte store per lane writes A-bar.
-// fp32 path (small test model only): one workgroup per query row, plain FMA.
+//   pass 2  one workgroup per (16-query tile, 16-key tile); its 4 waves split the
+//           heads, recompute S^T and accumulate exp(s - lse) in registers, then add
+//           their partial sums in a fixed order through LDS.
+// fp32 path (small test model only): the same two passes, one workgroup per query row, plain FMA.
 #include "common.cuh"
 #include "internal.h"
 
@@ -29,29 +30,42 @@ constexpr int kWaves = 4;
 __device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
 __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
 
-// S^T tile for 16 keys x 16 queries: acc[j] = <K[key0+4g+j], Q[q0+r]> (raw dot product)
+// Operands of one 16-key tile, loaded ahead of their use: K rows for S^T (DH/32 fragments) and,
+// per 64-wide head-dim block, four keys x four head-dim values of V.
 template <int DH>
-__device__ __forceinline__ f32x4 score_tile(const bf16* __restrict__ kbase, size_t k_pitch, int key0, int L,
-                                            const Frag<bf16> (&qf)[DH / 32], int r, int g) {
-  const int key = min(key0 + r, L - 1);
-  const bf16* krow = kbase + (size_t)key * k_pitch + g * 8;
-  Frag<bf16> kf[DH / 32];
-#pragma unroll
-  for (int s = 0; s < DH / 32; ++s) kf[s].raw = ld16(krow + s * 32);
-  f32x4 st = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int s = 0; s < DH / 32; ++s) mfma16(st, kf[s], qf[s]);
-  return st;
-}
+struct KvTile {
+  Frag<bf16> k[DH / 32];
+  u32x2 v[DH / 64][4];
+};
 
 template <int DH>
-__global__ __launch_bounds__(kThreads) void attn_fwd_bf16_kernel(
+__device__ __forceinline__ void load_kv_tile(KvTile<DH>& t, const bf16* __restrict__ kbase,
+                                             const bf16* __restrict__ vbase, size_t pitch, int key0, int L, int r,
+                                             int g) {
+  const int key = min(key0 + r, L - 1);
+  const bf16* krow = kbase + (size_t)key * pitch + g * 8;
+#pragma unroll
+  for (int s = 0; s < DH / 32; ++s) t.k[s].raw = ld16(krow + s * 32);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int vkey = min(key0 + 4 * g + e, L - 1);
+    const bf16* vrow = vbase + (size_t)vkey * pitch + 4 * r;
+#pragma unroll
+    for (int b = 0; b < DH / 64; ++b) t.v[b][e] = ld8(vrow + b * 64);
+  }
+}
+
+constexpr int kFwdWaves = 8;
+constexpr int kFwdThreads = kFwdWaves * 64;
+
+template <int DH>
+__global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
     const bf16* __restrict__ q, const bf16* __restrict__ k_cache, const bf16* __restrict__ v_cache, int m, int L,
     int n_heads, int n_kv_heads, float scale, bf16* __restrict__ out, float* __restrict__ lse) {
   constexpr int NS = DH / 32;     // contraction steps of Q K^T
   constexpr int NB = DH / 64;     // 64-wide head-dim blocks of the output
-  __shared__ float o_lds[kWaves][16][DH + 1];
-  __shared__ float m_lds[kWaves][16], l_lds[kWaves][16];
+  __shared__ float o_lds[kFwdWaves][16][DH + 1];
+  __shared__ float m_lds[kFwdWaves][16], l_lds[kFwdWaves][16];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 15, g = lane >> 4;
@@ -78,10 +92,10 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_bf16_kernel(
 #pragma unroll
     for (int i = 0; i < 4; ++i) acc[b][i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  const int n_tiles = (L + 15) / 16;
-  for (int t = wave; t < n_tiles; t += kWaves) {
-    const int key0 = t * 16;
-    f32x4 st = score_tile<DH>(kbase, kv_pitch, key0, L, qf, r, g);
+  auto consume = [&](const KvTile<DH>& t, int key0) {
+    f32x4 st = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < NS; ++s) mfma16(st, t.k[s], qf[s]);
     float x[4];
     float tmax = -INFINITY;
 #pragma unroll
@@ -104,21 +118,14 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_bf16_kernel(
     m_run = m_new;
     bf16x4 pb = {(bf16)p[0], (bf16)p[1], (bf16)p[2], (bf16)p[3]};
     const s16x4 pfrag = __builtin_bit_cast(s16x4, pb);
-
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-      // four keys (4g+e) x four head-dim values (b*64 + 4r + i), then transpose in registers
-      u32x2 v[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int key = min(key0 + 4 * g + e, L - 1);
-        v[e] = ld8(vbase + (size_t)key * kv_pitch + b * 64 + 4 * r);
-      }
+      // in-register 4x4 transpose: operand i holds keys 4g..4g+3 of head-dim value b*64 + 4r + i
       u32x2 op[4];
-      op[0] = u32x2{pack_lo(v[0].x, v[1].x), pack_lo(v[2].x, v[3].x)};
-      op[1] = u32x2{pack_hi(v[0].x, v[1].x), pack_hi(v[2].x, v[3].x)};
-      op[2] = u32x2{pack_lo(v[0].y, v[1].y), pack_lo(v[2].y, v[3].y)};
-      op[3] = u32x2{pack_hi(v[0].y, v[1].y), pack_hi(v[2].y, v[3].y)};
+      op[0] = u32x2{pack_lo(t.v[b][0].x, t.v[b][1].x), pack_lo(t.v[b][2].x, t.v[b][3].x)};
+      op[1] = u32x2{pack_hi(t.v[b][0].x, t.v[b][1].x), pack_hi(t.v[b][2].x, t.v[b][3].x)};
+      op[2] = u32x2{pack_lo(t.v[b][0].y, t.v[b][1].y), pack_lo(t.v[b][2].y, t.v[b][3].y)};
+      op[3] = u32x2{pack_hi(t.v[b][0].y, t.v[b][1].y), pack_hi(t.v[b][2].y, t.v[b][3].y)};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         acc[b][i] *= alpha;
@@ -126,9 +133,25 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_bf16_kernel(
                                                               0, 0);
       }
     }
+  };
+
+  // waves take key tiles round-robin; the next tile's loads are in flight while this one is consumed
+  const int n_tiles = (L + 15) / 16;
+  KvTile<DH> ta, tb;
+  int t = wave;
+  if (t < n_tiles) load_kv_tile<DH>(ta, kbase, vbase, kv_pitch, t * 16, L, r, g);
+  while (t < n_tiles) {
+    const int t1 = t + kFwdWaves;
+    if (t1 < n_tiles) load_kv_tile<DH>(tb, kbase, vbase, kv_pitch, t1 * 16, L, r, g);
+    consume(ta, t * 16);
+    if (t1 >= n_tiles) break;
+    const int t2 = t1 + kFwdWaves;
+    if (t2 < n_tiles) load_kv_tile<DH>(ta, kbase, vbase, kv_pitch, t2 * 16, L, r, g);
+    consume(tb, t1 * 16);
+    t = t2;
   }
 
-  // merge the four waves' partial softmaxes
+  // merge the waves' partial softmaxes
   l_run += __shfl_xor(l_run, 16, kWave);
   l_run += __shfl_xor(l_run, 32, kWave);
   if (g == 0) {
@@ -143,14 +166,14 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_bf16_kernel(
       for (int j = 0; j < 4; ++j) o_lds[wave][r][b * 64 + 16 * g + 4 * j + i] = acc[b][i][j];
   __syncthreads();
 
-  for (int o = tid; o < 16 * DH; o += kThreads) {
+  for (int o = tid; o < 16 * DH; o += kFwdThreads) {
     const int qi = o / DH, dcol = o - qi * DH;
     float mx = m_lds[0][qi];
 #pragma unroll
-    for (int w = 1; w < kWaves; ++w) mx = fmaxf(mx, m_lds[w][qi]);
+    for (int w = 1; w < kFwdWaves; ++w) mx = fmaxf(mx, m_lds[w][qi]);
     float lsum = 0.f, osum = 0.f;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
+    for (int w = 0; w < kFwdWaves; ++w) {
       const float f = __expf(m_lds[w][qi] - mx);
       lsum += l_lds[w][qi] * f;
       osum += o_lds[w][qi][dcol] * f;
@@ -162,6 +185,9 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_bf16_kernel(
   }
 }
 
+// Pass 2: one workgroup per (16-query tile, 16-key tile); its 4 waves split the heads (wave w takes
+// heads w, w+4, ..), each recomputes S^T for its heads and accumulates exp(s - lse); the four partial
+// sums are added in a fixed order through LDS.
 template <int DH>
 __global__ __launch_bounds__(kThreads) void attn_avg_bf16_kernel(const bf16* __restrict__ q,
                                                                  const bf16* __restrict__ k_cache,
@@ -169,47 +195,74 @@ __global__ __launch_bounds__(kThreads) void attn_avg_bf16_kernel(const bf16* __r
                                                                  int n_heads, int n_kv_heads, float scale,
                                                                  float* __restrict__ attn_avg) {
   constexpr int NS = DH / 32;
+  __shared__ f32x4 part[kWaves][64];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 15, g = lane >> 4;
   const int q0 = blockIdx.x * 16;
-  const int key0 = (blockIdx.y * kWaves + wave) * 16;
-  if (key0 >= L) return;
+  const int key0 = blockIdx.y * 16;
   const int dq = n_heads * DH;
   const size_t kv_pitch = (size_t)n_kv_heads * DH;
   const int group = n_heads / n_kv_heads;
   const int row = min(q0 + r, m - 1);
-  float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int head = 0; head < n_heads; ++head) {
-    Frag<bf16> qf[NS];
-    const bf16* qrow = q + (size_t)row * dq + head * DH + g * 8;
+  const int key = min(key0 + r, L - 1);
+  const bf16* qrow = q + (size_t)row * dq + g * 8;
+  const bf16* krow = k_cache + (size_t)key * kv_pitch + g * 8;
+
+  auto load_head = [&](Frag<bf16> (&qf)[NS], Frag<bf16> (&kf)[NS], float& e, int head) {
 #pragma unroll
-    for (int s = 0; s < NS; ++s) qf[s].raw = ld16(qrow + s * 32);
-    const f32x4 st = score_tile<DH>(k_cache + (size_t)(head / group) * DH, kv_pitch, key0, L, qf, r, g);
-    const float e = lse[(size_t)head * m + row];
+    for (int s = 0; s < NS; ++s) {
+      qf[s].raw = ld16(qrow + head * DH + s * 32);
+      kf[s].raw = ld16(krow + (head / group) * DH + s * 32);
+    }
+    e = lse[(size_t)head * m + row];
+  };
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  auto consume = [&](const Frag<bf16> (&qf)[NS], const Frag<bf16> (&kf)[NS], float e) {
+    f32x4 st = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < NS; ++s) mfma16(st, kf[s], qf[s]);
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[j] += __expf(st[j] * scale - e);
+  };
+  Frag<bf16> qa[NS], ka[NS], qb[NS], kb[NS];
+  float ea = 0.f, eb = 0.f;
+  int h = wave;
+  if (h < n_heads) load_head(qa, ka, ea, h);
+  while (h < n_heads) {
+    const int h1 = h + kWaves;
+    if (h1 < n_heads) load_head(qb, kb, eb, h1);
+    consume(qa, ka, ea);
+    if (h1 >= n_heads) break;
+    const int h2 = h1 + kWaves;
+    if (h2 < n_heads) load_head(qa, ka, ea, h2);
+    consume(qb, kb, eb);
+    h = h2;
   }
-  if (q0 + r >= m) return;
+  part[wave][lane] = acc;
+  __syncthreads();
+  if (wave != 0 || q0 + r >= m) return;
+  f32x4 sum = part[0][lane];
+#pragma unroll
+  for (int w = 1; w < kWaves; ++w) sum += part[w][lane];
   const float inv_h = 1.0f / (float)n_heads;
   float* dst = attn_avg + (size_t)(q0 + r) * L + key0 + 4 * g;
 #pragma unroll
   for (int j = 0; j < 4; ++j)
-    if (key0 + 4 * g + j < L) dst[j] = acc[j] * inv_h;
+    if (key0 + 4 * g + j < L) dst[j] = sum[j] * inv_h;
 }
 
-// fp32 path: one workgroup per query row, heads in sequence.
-__global__ __launch_bounds__(kThreads) void attn_f32_kernel(const float* __restrict__ q,
-                                                            const float* __restrict__ k_cache,
-                                                            const float* __restrict__ v_cache, int L, int n_heads,
-                                                            int n_kv_heads, int head_dim, float scale,
-                                                            float* __restrict__ out, float* __restrict__ attn_avg) {
-  extern __shared__ float smem[];          // scores[L], abar[L], red[8]
+// fp32 path (small test model): one workgroup per query row, heads in sequence, plain FMA.
+__global__ __launch_bounds__(kThreads) void attn_fwd_f32_kernel(const float* __restrict__ q,
+                                                                const float* __restrict__ k_cache,
+                                                                const float* __restrict__ v_cache, int m, int L,
+                                                                int n_heads, int n_kv_heads, int head_dim,
+                                                                float scale, float* __restrict__ out,
+                                                                float* __restrict__ lse) {
+  extern __shared__ float smem[];          // scores[L], red[8]
   float* scores = smem;
-  float* abar = smem + L;
-  float* red = abar + L;
+  float* red = smem + L;
   const int row = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int dq = n_heads * head_dim, dkv = n_kv_heads * head_dim, group = n_heads / n_kv_heads;
-  for (int j = tid; j < L; j += kThreads) abar[j] = 0.f;
   for (int head = 0; head < n_heads; ++head) {
     const float* qv = q + (size_t)row * dq + head * head_dim;
     const int kvh = head / group;
@@ -237,8 +290,9 @@ __global__ __launch_bounds__(kThreads) void attn_f32_kernel(const float* __restr
     __syncthreads();
     if (lane == 0) red[4 + wave] = sum;
     __syncthreads();
-    const float inv = 1.0f / (red[4] + red[5] + red[6] + red[7]);
-    for (int j = tid; j < L; j += kThreads) abar[j] += scores[j] * inv;
+    const float total = red[4] + red[5] + red[6] + red[7];
+    const float inv = 1.0f / total;
+    if (tid == 0) lse[(size_t)head * m + row] = mx + logf(total);
     for (int e = tid; e < head_dim; e += kThreads) {
       float o = 0.f;
       for (int j = 0; j < L; ++j) o = fmaf(scores[j], v_cache[(size_t)j * dkv + kvh * head_dim + e], o);
@@ -246,44 +300,80 @@ __global__ __launch_bounds__(kThreads) void attn_f32_kernel(const float* __restr
     }
     __syncthreads();
   }
-  if (attn_avg != nullptr) {
-    const float inv_h = 1.0f / (float)n_heads;
-    for (int j = tid; j < L; j += kThreads) attn_avg[(size_t)row * L + j] = abar[j] * inv_h;
+}
+
+// A-bar row of one query: mean over heads of exp(s - lse).
+__global__ __launch_bounds__(kThreads) void attn_avg_f32_kernel(const float* __restrict__ q,
+                                                                const float* __restrict__ k_cache,
+                                                                const float* __restrict__ lse, int m, int L,
+                                                                int n_heads, int n_kv_heads, int head_dim,
+                                                                float scale, float* __restrict__ attn_avg) {
+  const int row = blockIdx.x;
+  const int dq = n_heads * head_dim, dkv = n_kv_heads * head_dim, group = n_heads / n_kv_heads;
+  const float inv_h = 1.0f / (float)n_heads;
+  for (int j = threadIdx.x; j < L; j += kThreads) {
+    float acc = 0.f;
+    for (int head = 0; head < n_heads; ++head) {
+      const float* qv = q + (size_t)row * dq + head * head_dim;
+      const float* kv = k_cache + (size_t)j * dkv + (head / group) * head_dim;
+      float s = 0.f;
+      for (int e = 0; e < head_dim; ++e) s = fmaf(qv[e], kv[e], s);
+      acc += expf(s * scale - lse[(size_t)head * m + row]);
+    }
+    attn_avg[(size_t)row * L + j] = acc * inv_h;
   }
 }
 
 template <int DH>
-hipError_t launch_bf16(const void* q, const void* k_cache, const void* v_cache, int m, int L, int n_heads,
-                       int n_kv_heads, void* out, float* lse, float* attn_avg, hipStream_t st) {
+hipError_t launch_fwd_bf16(const void* q, const void* k_cache, const void* v_cache, int m, int L, int n_heads,
+                           int n_kv_heads, void* out, float* lse, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)DH);
-  const int q_tiles = (m + 15) / 16;
-  hipLaunchKernelGGL(attn_fwd_bf16_kernel<DH>, dim3(q_tiles, n_heads), dim3(kThreads), 0, st, (const bf16*)q,
+  hipLaunchKernelGGL(attn_fwd_bf16_kernel<DH>, dim3((m + 15) / 16, n_heads), dim3(kFwdThreads), 0, st, (const bf16*)q,
                      (const bf16*)k_cache, (const bf16*)v_cache, m, L, n_heads, n_kv_heads, scale, (bf16*)out, lse);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess || attn_avg == nullptr) return e;
-  const int key_blocks = (L + 16 * kWaves - 1) / (16 * kWaves);
-  hipLaunchKernelGGL(attn_avg_bf16_kernel<DH>, dim3(q_tiles, key_blocks), dim3(kThreads), 0, st, (const bf16*)q,
+  return hipGetLastError();
+}
+
+template <int DH>
+hipError_t launch_avg_bf16(const void* q, const void* k_cache, const float* lse, int m, int L, int n_heads,
+                           int n_kv_heads, float* attn_avg, hipStream_t st) {
+  const float scale = 1.0f / sqrtf((float)DH);
+  const int key_blocks = (L + 15) / 16;
+  hipLaunchKernelGGL(attn_avg_bf16_kernel<DH>, dim3((m + 15) / 16, key_blocks), dim3(kThreads), 0, st, (const bf16*)q,
                      (const bf16*)k_cache, lse, m, L, n_heads, n_kv_heads, scale, attn_avg);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_attention(int dtype, const void* q, const void* k_cache, const void* v_cache, int m, int L,
-                            int n_heads, int n_kv_heads, int head_dim, void* out, float* lse, float* attn_avg,
-                            hipStream_t st) {
+hipError_t launch_attention_fwd(int dtype, const void* q, const void* k_cache, const void* v_cache, int m, int L,
+                                int n_heads, int n_kv_heads, int head_dim, void* out, float* lse, hipStream_t st) {
   if (m <= 0) return hipSuccess;
   if (L <= 0 || n_heads % n_kv_heads) return hipErrorInvalidValue;
   if (dtype == kBF16) {
-    if (head_dim == 128) return launch_bf16<128>(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, attn_avg, st);
-    if (head_dim == 64) return launch_bf16<64>(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, attn_avg, st);
+    if (head_dim == 128) return launch_fwd_bf16<128>(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, st);
+    if (head_dim == 64) return launch_fwd_bf16<64>(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, st);
     return hipErrorInvalidValue;
   }
-  const size_t smem = ((size_t)2 * L + 8) * sizeof(float);
+  const size_t smem = ((size_t)L + 8) * sizeof(float);
   if (smem > 64 * 1024) return hipErrorInvalidValue;   // default dynamic LDS limit
   const float scale = 1.0f / sqrtf((float)head_dim);
-  hipLaunchKernelGGL(attn_f32_kernel, dim3(m), dim3(kThreads), smem, st, (const float*)q, (const float*)k_cache,
-                     (const float*)v_cache, L, n_heads, n_kv_heads, head_dim, scale, (float*)out, attn_avg);
+  hipLaunchKernelGGL(attn_fwd_f32_kernel, dim3(m), dim3(kThreads), smem, st, (const float*)q, (const float*)k_cache,
+                     (const float*)v_cache, m, L, n_heads, n_kv_heads, head_dim, scale, (float*)out, lse);
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_avg(int dtype, const void* q, const void* k_cache, const float* lse, int m, int L,
+                                int n_heads, int n_kv_heads, int head_dim, float* attn_avg, hipStream_t st) {
+  if (m <= 0) return hipSuccess;
+  if (L <= 0 || n_heads % n_kv_heads) return hipErrorInvalidValue;
+  if (dtype == kBF16) {
+    if (head_dim == 128) return launch_avg_bf16<128>(q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, st);
+    if (head_dim == 64) return launch_avg_bf16<64>(q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, st);
+    return hipErrorInvalidValue;
+  }
+  const float scale = 1.0f / sqrtf((float)head_dim);
+  hipLaunchKernelGGL(attn_avg_f32_kernel, dim3(m), dim3(kThreads), 0, st, (const float*)q, (const float*)k_cache, lse,
+                     m, L, n_heads, n_kv_heads, head_dim, scale, attn_avg);
   return hipGetLastError();
 }
 

@@ -15,6 +15,7 @@ struct Tunables {
   int gemm_target_wgs = 512;   // aim for at least this many workgroups per GEMM
   int gemm_max_splits = 8;
   int gemm_nt_big_n = 16384;   // N above this uses two column tiles per wave
+  bool side_stream = true;     // d2c_step: head average + rollout on a second stream
 };
 Tunables& tunables();
 
@@ -59,11 +60,13 @@ hipError_t launch_sum_splits(float* dst, const float* P, int n_splits, size_t sp
 // cos/sin table [max_pos, head_dim/2], angles evaluated in fp64
 hipError_t launch_rope_table(float* cos_t, float* sin_t, int max_pos, int head_dim, float theta, hipStream_t st);
 
-// ---- attention of m query rows against all L cached keys, no mask
-// out: T [m, H*dh]; lse: float [H, m] workspace; attn_avg: float [m, L] or null
-hipError_t launch_attention(int dtype, const void* q, const void* k_cache, const void* v_cache, int m, int L,
-                            int n_heads, int n_kv_heads, int head_dim, void* out, float* lse, float* attn_avg,
-                            hipStream_t st);
+// ---- attention of m query rows against all L cached keys, no mask, in two launches
+// fwd: out T [m, H*dh] and the log-sum-exp per (head, row), lse float [H, m]
+hipError_t launch_attention_fwd(int dtype, const void* q, const void* k_cache, const void* v_cache, int m, int L,
+                                int n_heads, int n_kv_heads, int head_dim, void* out, float* lse, hipStream_t st);
+// avg: attn_avg float [m, L] = mean over heads of exp(q k / sqrt(dh) - lse); needs fwd's lse
+hipError_t launch_attention_avg(int dtype, const void* q, const void* k_cache, const float* lse, int m, int L,
+                                int n_heads, int n_kv_heads, int head_dim, float* attn_avg, hipStream_t st);
 
 // ---- rollout on the compact block: c_out = (A[:,S] c_in + A[:,notS] + c_in) / 2; first: c_in = one-hot rows
 hipError_t launch_rollout(const float* attn_avg, const float* c_in, float* c_out, const int32_t* idx, int m, int L,

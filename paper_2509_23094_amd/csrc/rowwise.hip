@@ -67,6 +67,55 @@ __global__ __launch_bounds__(kThreads) void add_norm_kernel(float* __restrict__ 
   for (int c = threadIdx.x; c < d; c += kThreads) ar[c] = from_f32<T>(hr[c] * inv * gain[c]);
 }
 
+__device__ __forceinline__ void store4(float* dst, const f32x4& v) { *reinterpret_cast<f32x4*>(dst) = v; }
+__device__ __forceinline__ void store4(bf16* dst, const f32x4& v) {
+  bf16x4 o = {(bf16)v.x, (bf16)v.y, (bf16)v.z, (bf16)v.w};
+  *reinterpret_cast<bf16x4*>(dst) = o;
+}
+
+// Same as add_norm_kernel for d <= NI*1024, d % 4 == 0: the row stays in registers and every
+// access is a 16-byte vector, all of a thread's loads independent of each other.
+template <typename T, int NI>
+__global__ __launch_bounds__(kThreads) void add_norm_vec_kernel(float* __restrict__ h, const float* __restrict__ P,
+                                                                int n_splits, size_t split_stride, int ldp, int d,
+                                                                const float* __restrict__ gain, float eps,
+                                                                T* __restrict__ a) {
+  __shared__ float red[kThreads / 64];
+  const int r = blockIdx.x;
+  float* hr = h + (size_t)r * d;
+  const float* pr = P + (size_t)r * ldp;
+  f32x4 v[NI];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int c = (threadIdx.x + i * kThreads) * 4;
+    v[i] = c < d ? *reinterpret_cast<const f32x4*>(hr + c) : f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  if (n_splits > 0) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int c = (threadIdx.x + i * kThreads) * 4;
+      if (c < d) {
+        f32x4 add = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+        for (int s = 0; s < n_splits; ++s) add += *reinterpret_cast<const f32x4*>(pr + (size_t)s * split_stride + c);
+        v[i] += add;
+        store4(hr + c, v[i]);
+      }
+    }
+  }
+  if (a == nullptr) return;
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < NI; ++i) ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
+  const float inv = 1.0f / sqrtf(block_sum(ss, red) / (float)d + eps);
+  T* ar = a + (size_t)r * d;
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int c = (threadIdx.x + i * kThreads) * 4;
+    if (c < d) store4(ar + c, v[i] * inv * *reinterpret_cast<const f32x4*>(gain + c));
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(kThreads) void gather_norm_kernel(const float* __restrict__ h,
                                                                const int32_t* __restrict__ rows, int d,
@@ -122,6 +171,48 @@ __global__ __launch_bounds__(kThreads) void qkv_rope_scatter_kernel(
   }
   for (int c = threadIdx.x; c < dkv; c += kThreads)
     v_cache[(size_t)pos * dkv + c] = from_f32<T>(col(dq + dkv + c));
+}
+
+// Vector form for head_dim % 8 == 0: a work item is four consecutive rotation pairs of one head
+// (two 16-byte loads per split) or four consecutive value columns; blockIdx.y strides over items.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void qkv_rope_scatter_vec_kernel(
+    const float* __restrict__ P, int n_splits, size_t split_stride, int ldp, const float* __restrict__ bias,
+    const int32_t* __restrict__ idx, int n_heads, int n_kv_heads, int head_dim, const float* __restrict__ rope_cos,
+    const float* __restrict__ rope_sin, T* __restrict__ q_out, T* __restrict__ k_cache, T* __restrict__ v_cache) {
+  const int r = blockIdx.x;
+  const int pos = idx[r];
+  const int half = head_dim >> 1, q4 = half >> 2;            // 4-wide items per half head
+  const int dq = n_heads * head_dim, dkv = n_kv_heads * head_dim;
+  const float* pr = P + (size_t)r * ldp;
+  auto col4 = [&](int c) {
+    f32x4 v = bias ? *reinterpret_cast<const f32x4*>(bias + c) : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int s = 0; s < n_splits; ++s) v += *reinterpret_cast<const f32x4*>(pr + (size_t)s * split_stride + c);
+    return v;
+  };
+  const int n_rot = (n_heads + n_kv_heads) * q4;
+  const int n_items = n_rot + (dkv >> 2);
+  for (int t = blockIdx.y * kThreads + threadIdx.x; t < n_items; t += gridDim.y * kThreads) {
+    if (t < n_rot) {
+      const int head = t / q4, i = (t - head * q4) * 4;
+      const int c1 = head * head_dim + i, c2 = c1 + half;
+      const f32x4 x1 = col4(c1), x2 = col4(c2);
+      const f32x4 c = *reinterpret_cast<const f32x4*>(rope_cos + (size_t)pos * half + i);
+      const f32x4 sn = *reinterpret_cast<const f32x4*>(rope_sin + (size_t)pos * half + i);
+      const f32x4 o1 = x1 * c - x2 * sn, o2 = x2 * c + x1 * sn;
+      if (head < n_heads) {
+        store4(q_out + (size_t)r * dq + c1, o1);
+        store4(q_out + (size_t)r * dq + c2, o2);
+      } else {
+        store4(k_cache + (size_t)pos * dkv + (c1 - dq), o1);
+        store4(k_cache + (size_t)pos * dkv + (c2 - dq), o2);
+      }
+    } else {
+      const int c = (t - n_rot) * 4;
+      store4(v_cache + (size_t)pos * dkv + c, col4(dq + dkv + c));
+    }
+  }
 }
 
 template <typename T>
@@ -199,6 +290,14 @@ hipError_t launch_embed_norm(int dtype, const void* emb, const int32_t* tokens, 
 hipError_t launch_add_norm(int dtype, float* h, const float* P, int n_splits, size_t split_stride, int ldp, int m,
                            int d, const float* gain, float eps, void* a, hipStream_t st) {
   if (m <= 0) return hipSuccess;
+  if (d % 4 == 0 && d <= 4096 && ldp % 4 == 0 && split_stride % 4 == 0) {
+    D2C_DISPATCH(dtype,
+                 hipLaunchKernelGGL((add_norm_vec_kernel<bf16, 4>), dim3(m), dim3(kThreads), 0, st, h, P, n_splits,
+                                    split_stride, ldp, d, gain, eps, (bf16*)a),
+                 hipLaunchKernelGGL((add_norm_vec_kernel<float, 4>), dim3(m), dim3(kThreads), 0, st, h, P, n_splits,
+                                    split_stride, ldp, d, gain, eps, (float*)a));
+    return hipGetLastError();
+  }
   D2C_DISPATCH(dtype,
                hipLaunchKernelGGL(add_norm_kernel<bf16>, dim3(m), dim3(kThreads), 0, st, h, P, n_splits, split_stride,
                                   ldp, d, gain, eps, (bf16*)a),
@@ -224,6 +323,18 @@ hipError_t launch_qkv_rope_scatter(int dtype, const float* P, int n_splits, size
                                    void* k_cache, void* v_cache, hipStream_t st) {
   if (m <= 0) return hipSuccess;
   if (head_dim % 2) return hipErrorInvalidValue;
+  if (head_dim % 8 == 0 && ldp % 4 == 0 && split_stride % 4 == 0) {
+    const int items = ((n_heads + n_kv_heads) * (head_dim / 8) + n_kv_heads * head_dim / 4);
+    const dim3 grid(m, (items + 2 * kThreads - 1) / (2 * kThreads));
+    D2C_DISPATCH(dtype,
+                 hipLaunchKernelGGL(qkv_rope_scatter_vec_kernel<bf16>, grid, dim3(kThreads), 0, st, P, n_splits,
+                                    split_stride, ldp, bias, idx, n_heads, n_kv_heads, head_dim, rope_cos, rope_sin,
+                                    (bf16*)q_out, (bf16*)k_cache, (bf16*)v_cache),
+                 hipLaunchKernelGGL(qkv_rope_scatter_vec_kernel<float>, grid, dim3(kThreads), 0, st, P, n_splits,
+                                    split_stride, ldp, bias, idx, n_heads, n_kv_heads, head_dim, rope_cos, rope_sin,
+                                    (float*)q_out, (float*)k_cache, (float*)v_cache));
+    return hipGetLastError();
+  }
   D2C_DISPATCH(dtype,
                hipLaunchKernelGGL(qkv_rope_scatter_kernel<bf16>, dim3(m), dim3(kThreads), 0, st, P, n_splits,
                                   split_stride, ldp, bias, idx, n_heads, n_kv_heads, head_dim, rope_cos, rope_sin,

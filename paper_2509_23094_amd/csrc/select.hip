@@ -66,55 +66,57 @@ __global__ __launch_bounds__(kConfThreads) void confidence_kernel(const float* _
 // c_out[i, c] = ( sum_r A[i, S_r] c_in[r, c] + A[i, c] [c not in S] + c_in[i, c] ) / 2
 // Rows outside S stay one-hot under Eq. 6-7, so only these m rows ever change.
 constexpr int kRollThreads = 256;
-constexpr int kRollRows = 16;
-constexpr int kRollChunk = 128;
 
+// First layer: C^(0) = I, so sum_r A[i,S_r][c == S_r] + A[i,c][c not in S] = A[i,c] and c_in[i,c] = [c == S_i].
+__global__ __launch_bounds__(kRollThreads) void rollout_first_kernel(const float* __restrict__ A,
+                                                                     float* __restrict__ c_out,
+                                                                     const int32_t* __restrict__ idx, int m, int L) {
+  const int col = blockIdx.x * kRollThreads + threadIdx.x;
+  const int i = blockIdx.y;
+  if (col >= L) return;
+  c_out[(size_t)i * L + col] = 0.5f * (A[(size_t)i * L + col] + (idx[i] == col ? 1.f : 0.f));
+}
+
+// Later layers: the m x m by m x L product runs on the fp32 matrix cores, one wave per 16 x 16
+// output tile (4 waves = 16 rows x 64 columns per workgroup).  Per 16-long step of the
+// contraction a lane holds A[i0 + l%16][S[k0 + 4(l/16) + e]] and C[k0 + 4(l/16) + e][c0 + l%16],
+// e = 0..3, one 16x16x4 instruction per e.
 __global__ __launch_bounds__(kRollThreads) void rollout_kernel(const float* __restrict__ A,
                                                                const float* __restrict__ c_in,
                                                                float* __restrict__ c_out,
-                                                               const int32_t* __restrict__ idx, int m, int L,
-                                                               int first) {
-  __shared__ float a_sel[kRollRows][kRollChunk + 1];
-  const int col = blockIdx.x * kRollThreads + threadIdx.x;
-  const int i0 = blockIdx.y * kRollRows;
-  const bool live = col < L;
-  const int self = live ? find_sorted(idx, m, col) : -1;     // row of S that sits at this column, or -1
-  float acc[kRollRows];
+                                                               const int32_t* __restrict__ idx, int m, int L) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = lane & 15, g = lane >> 4;
+  const int i0 = blockIdx.y * 16;
+  const int c0 = (blockIdx.x * 4 + wave) * 16;
+  if (c0 >= L) return;
+  const int arow = min(i0 + r, m - 1);
+  const int bcol = min(c0 + r, L - 1);
+  const float* a_row = A + (size_t)arow * L;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int k0 = 0; k0 < m; k0 += 16) {
+    float av[4], bv[4];
 #pragma unroll
-  for (int ii = 0; ii < kRollRows; ++ii) acc[ii] = 0.f;
-
-  if (first) {
-    // C^(0) = I: sum_r A[i,S_r] [c == S_r] + A[i,c][c not in S] = A[i,c];  c_in[i,c] = [c == S_i]
-    if (live)
-      for (int ii = 0; ii < kRollRows && i0 + ii < m; ++ii)
-        c_out[(size_t)(i0 + ii) * L + col] = 0.5f * (A[(size_t)(i0 + ii) * L + col] + (self == i0 + ii ? 1.f : 0.f));
-    return;
-  }
-  for (int rc = 0; rc < m; rc += kRollChunk) {
-    __syncthreads();
-    for (int e = threadIdx.x; e < kRollRows * kRollChunk; e += kRollThreads) {
-      const int ii = e / kRollChunk, rr = e - ii * kRollChunk;
-      float v = 0.f;
-      if (i0 + ii < m && rc + rr < m) v = A[(size_t)(i0 + ii) * L + idx[rc + rr]];
-      a_sel[ii][rr] = v;
+    for (int e = 0; e < 4; ++e) {
+      const int k = k0 + 4 * g + e;
+      const bool ok = k < m;
+      const int kk = ok ? k : m - 1;
+      const float x = a_row[idx[kk]];
+      av[e] = ok ? x : 0.f;
+      bv[e] = c_in[(size_t)kk * L + bcol];
     }
-    __syncthreads();
-    if (live) {
-      const int n = min(kRollChunk, m - rc);
-      for (int rr = 0; rr < n; ++rr) {
-        const float cv = c_in[(size_t)(rc + rr) * L + col];
 #pragma unroll
-        for (int ii = 0; ii < kRollRows; ++ii) acc[ii] = fmaf(a_sel[ii][rr], cv, acc[ii]);
-      }
-    }
+    for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[e], bv[e], acc, 0, 0, 0);
   }
-  if (!live) return;
+  const int col = c0 + r;
+  if (col >= L) return;
+  const bool in_s = find_sorted(idx, m, col) >= 0;
 #pragma unroll
-  for (int ii = 0; ii < kRollRows; ++ii) {
-    const int i = i0 + ii;
+  for (int j = 0; j < 4; ++j) {
+    const int i = i0 + 4 * g + j;
     if (i >= m) break;
-    const float direct = self < 0 ? A[(size_t)i * L + col] : 0.f;
-    c_out[(size_t)i * L + col] = 0.5f * (acc[ii] + direct + c_in[(size_t)i * L + col]);
+    const float direct = in_s ? 0.f : A[(size_t)i * L + col];
+    c_out[(size_t)i * L + col] = 0.5f * (acc[j] + direct + c_in[(size_t)i * L + col]);
   }
 }
 
@@ -392,9 +394,13 @@ hipError_t launch_confidence(const float* logits, const int32_t* pos, const int3
 hipError_t launch_rollout(const float* attn_avg, const float* c_in, float* c_out, const int32_t* idx, int m, int L,
                           bool first, hipStream_t st) {
   if (m <= 0) return hipSuccess;
-  dim3 grid((L + kRollThreads - 1) / kRollThreads, (m + kRollRows - 1) / kRollRows);
-  hipLaunchKernelGGL(rollout_kernel, grid, dim3(kRollThreads), 0, st, attn_avg, c_in, c_out, idx, m, L,
-                     first ? 1 : 0);
+  if (first) {
+    hipLaunchKernelGGL(rollout_first_kernel, dim3((L + kRollThreads - 1) / kRollThreads, m), dim3(kRollThreads), 0, st,
+                       attn_avg, c_out, idx, m, L);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL(rollout_kernel, dim3((L + 63) / 64, (m + 15) / 16), dim3(kRollThreads), 0, st, attn_avg, c_in,
+                     c_out, idx, m, L);
   return hipGetLastError();
 }
 
