@@ -98,6 +98,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="C3", choices=["C3", "C4"])
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (the result is then not the metric)")
+    ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
+                    help="library tunable (see d2c_set_tunable), e.g. --tune gemm_target_wgs=768")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-vanilla", action="store_true")
     args = ap.parse_args()
@@ -113,6 +115,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    for kv in args.tune:
+        name, value = kv.split("=")
+        B.d2c_set_tunable(name, int(value))
     dims, su = W.DIMS[args.workload], W.SETUP[args.workload]
     if args.layers:
         dims = W.with_layers(dims, args.layers)

@@ -15,6 +15,7 @@ struct Tunables {
   int gemm_target_wgs = 512;   // aim for at least this many workgroups per GEMM
   int gemm_max_splits = 8;
   int gemm_nt_big_n = 16384;   // N above this uses two column tiles per wave
+  int gemm_ring = 2;           // weight chunks per wave in registers (2 or 4)
   bool side_stream = true;     // d2c_step: head average + rollout on a second stream
 };
 Tunables& tunables();
@@ -23,6 +24,7 @@ Tunables& tunables();
 struct GemmPlan {
   int mt;        // 16-row tiles per workgroup (1..8)
   int nt;        // 16-column tiles per wave (1 or 2)
+  int ring;      // weight chunks a wave holds in registers (2 or 4)
   int splits;    // k splits (partials to be summed by the consumer)
   int k_per_split;
   int row_chunks;
