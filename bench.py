@@ -100,6 +100,9 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (the result is then not the metric)")
     ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
                     help="library tunable (see d2c_set_tunable), e.g. --tune gemm_target_wgs=768")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run five plain 256 MiB device copies (known size, for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE) and exit")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-vanilla", action="store_true")
     args = ap.parse_args()
@@ -118,6 +121,14 @@ def main():
     for kv in args.tune:
         name, value = kv.split("=")
         B.d2c_set_tunable(name, int(value))
+    if args.copy_calibration:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.zeros_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": 256 << 20, "copies": 5}))
+        return
     dims, su = W.DIMS[args.workload], W.SETUP[args.workload]
     if args.layers:
         dims = W.with_layers(dims, args.layers)

@@ -313,6 +313,9 @@ int d2c_set_tunable(const char* name, int32_t value) {
   else if (!strcmp(name, "gemm_max_splits")) t.gemm_max_splits = std::max(1, std::min(8, (int)value));
   else if (!strcmp(name, "gemm_nt_big_n")) t.gemm_nt_big_n = value;
   else if (!strcmp(name, "gemm_ring")) t.gemm_ring = value == 2 ? 2 : 4;
+  else if (!strcmp(name, "gemm_wide")) t.gemm_wide = value != 0;
+  else if (!strcmp(name, "gemm_pre")) t.gemm_pre = value != 0;
+  else if (!strcmp(name, "gemm_cg2_min_n")) t.gemm_cg2_min_n = value;
   else if (!strcmp(name, "side_stream")) t.side_stream = value != 0;
   else return D2C_EINVAL;
   return D2C_OK;

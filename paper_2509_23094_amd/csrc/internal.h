@@ -15,6 +15,9 @@ struct Tunables {
   int gemm_target_wgs = 512;   // aim for at least this many workgroups per GEMM
   int gemm_max_splits = 8;
   int gemm_nt_big_n = 16384;   // N above this uses two column tiles per wave
+  int gemm_pre = 1;            // rows kernel with register prefetch of the activation fragments
+  int gemm_wide = 0;           // 1: gemm_wide_kernel, 0: gemm_rows_kernel
+  int gemm_cg2_min_n = 8192;   // wide kernel: N above this uses 128-column workgroups
   int gemm_ring = 2;           // weight chunks per wave in registers (2 or 4)
   bool side_stream = true;     // d2c_step: head average + rollout on a second stream
 };
@@ -24,6 +27,9 @@ Tunables& tunables();
 struct GemmPlan {
   int mt;        // 16-row tiles per workgroup (1..8)
   int nt;        // 16-column tiles per wave (1 or 2)
+  bool pre;      // rows kernel: next chunk's activation fragments prefetched into registers
+  bool wide;     // gemm_wide_kernel (64 columns per wave) instead of gemm_rows_kernel
+  int cg;        // wide kernel: column groups per workgroup (1: 64 columns x 4 k-groups, 2: 128 columns x 2 k-groups)
   int ring;      // weight chunks a wave holds in registers (2 or 4)
   int splits;    // k splits (partials to be summed by the consumer)
   int k_per_split;
