@@ -38,6 +38,7 @@ struct d2c_ctx {
   float* roll[2] = {nullptr, nullptr};
   void* head_a = nullptr;       // T [head_rows, d]
   float* logits = nullptr;      // [head_rows, vocab]
+  float* conf_part = nullptr;   // per-chunk (max, argmax, sum) triples of Eq. 1 for up to max_seq rows
   int head_rows = 0;
   float* rope_cos = nullptr;    // [max_seq, head_dim/2]
   float* rope_sin = nullptr;
@@ -268,6 +269,7 @@ int d2c_init(const d2c_dims* dims, const d2c_weights* w, d2c_ctx** out) {
       (rc = ws_alloc(c, &c->roll[0], Lm * Lm * 4)) || (rc = ws_alloc(c, &c->roll[1], Lm * Lm * 4)) ||
       (rc = ws_alloc(c, &c->head_a, (size_t)c->head_rows * d * ts)) ||
       (rc = ws_alloc(c, &c->logits, (size_t)c->head_rows * D.vocab * 4)) ||
+      (rc = ws_alloc(c, &c->conf_part, confidence_scratch_floats(D.max_seq) * 4)) ||
       (rc = ws_alloc(c, &c->rope_cos, Lm * (D.head_dim / 2) * 4)) ||
       (rc = ws_alloc(c, &c->rope_sin, Lm * (D.head_dim / 2) * 4)))
     return bail(rc);
@@ -313,9 +315,6 @@ int d2c_set_tunable(const char* name, int32_t value) {
   else if (!strcmp(name, "gemm_max_splits")) t.gemm_max_splits = std::max(1, std::min(8, (int)value));
   else if (!strcmp(name, "gemm_nt_big_n")) t.gemm_nt_big_n = value;
   else if (!strcmp(name, "gemm_ring")) t.gemm_ring = value == 2 ? 2 : 4;
-  else if (!strcmp(name, "gemm_wide")) t.gemm_wide = value != 0;
-  else if (!strcmp(name, "gemm_pre")) t.gemm_pre = value != 0;
-  else if (!strcmp(name, "gemm_cg2_min_n")) t.gemm_cg2_min_n = value;
   else if (!strcmp(name, "side_stream")) t.side_stream = value != 0;
   else return D2C_EINVAL;
   return D2C_OK;
@@ -378,7 +377,8 @@ int d2c_select(d2c_ctx* c, const d2c_params* p, const float* logits, const int32
   if (L <= 0 || L > c->dims.max_seq) return fail(c, D2C_ESHAPE, "L outside (0, max_seq]");
   if (prompt_len < 0 || prompt_len > L) return fail(c, D2C_EINVAL, "prompt_len outside [0, L]");
   hipStream_t st = (hipStream_t)stream;
-  D2C_HIP(c, launch_confidence(logits, logit_pos, nullptr, n_rows, c->dims.vocab, conf, pred, st));
+  if (n_rows > c->dims.max_seq) return fail(c, D2C_ESHAPE, "n_rows exceeds max_seq of the context");
+  D2C_HIP(c, launch_confidence(logits, logit_pos, nullptr, n_rows, c->dims.vocab, conf, pred, c->conf_part, st));
   SelectArgs a{p->sigma, p->k, p->p, p->block_len, p->n_unmask, p->cand_mode, tokens, is_masked, L, prompt_len,
                conf, pred, influence, mstar, u_set, decode_idx, s_next, s_rows_next, counts, score_out};
   D2C_HIP(c, launch_select(a, st));
@@ -513,7 +513,7 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
       size_t stride;
       if ((rc = project(c, c->head_a, d, c->lm_head, nr, D.vocab, d, &pl, &stride, st, true, c->logits))) return rc;
       D2C_TIMED(c, st, D2C_PROF_SELECT, 0.0,
-                launch_confidence(c->logits, s.s_rows + r0, s.s_idx, nr, D.vocab, s.conf, s.pred, st));
+                launch_confidence(c->logits, s.s_rows + r0, s.s_idx, nr, D.vocab, s.conf, s.pred, c->conf_part, st));
       if (s.logits_out)
         D2C_HIP(c, hipMemcpyAsync(s.logits_out + (size_t)r0 * D.vocab, c->logits, (size_t)nr * D.vocab * 4,
                                   hipMemcpyDeviceToDevice, st));

@@ -135,20 +135,24 @@ __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
     }
   };
 
-  // waves take key tiles round-robin; the next tile's loads are in flight while this one is consumed
+  // waves take key tiles round-robin; up to four tiles of a wave are in flight: a slot is refilled
+  // with the tile four strides ahead as soon as it has been consumed
   const int n_tiles = (L + 15) / 16;
-  KvTile<DH> ta, tb;
-  int t = wave;
-  if (t < n_tiles) load_kv_tile<DH>(ta, kbase, vbase, kv_pitch, t * 16, L, r, g);
-  while (t < n_tiles) {
-    const int t1 = t + kFwdWaves;
-    if (t1 < n_tiles) load_kv_tile<DH>(tb, kbase, vbase, kv_pitch, t1 * 16, L, r, g);
-    consume(ta, t * 16);
-    if (t1 >= n_tiles) break;
-    const int t2 = t1 + kFwdWaves;
-    if (t2 < n_tiles) load_kv_tile<DH>(ta, kbase, vbase, kv_pitch, t2 * 16, L, r, g);
-    consume(tb, t1 * 16);
-    t = t2;
+  KvTile<DH> ring[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int t = wave + u * kFwdWaves;
+    if (t < n_tiles) load_kv_tile<DH>(ring[u], kbase, vbase, kv_pitch, t * 16, L, r, g);
+  }
+  for (int t0 = wave; t0 < n_tiles; t0 += 4 * kFwdWaves) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int t = t0 + u * kFwdWaves;
+      if (t >= n_tiles) break;
+      consume(ring[u], t * 16);
+      const int tn = t + 4 * kFwdWaves;
+      if (tn < n_tiles) load_kv_tile<DH>(ring[u], kbase, vbase, kv_pitch, tn * 16, L, r, g);
+    }
   }
 
   // merge the waves' partial softmaxes

@@ -154,146 +154,12 @@ __global__ __launch_bounds__(kThreads) void gemm_rows_kernel(
     }
 }
 
-// Variant with the activation fragments of the NEXT chunk read from LDS into registers while the
-// current chunk is multiplied: after a barrier no matrix-core step waits on LDS.  Staging runs two
-// chunks ahead in LDS (buffers c&1 and (c+1)&1 hold chunks c+1.. when chunk c is consumed from
-// registers) and a third chunk is in flight from global memory.
-template <typename T, int MT, int NT>
-__global__ __launch_bounds__(kThreads) void gemm_rows_pre_kernel(
-    const T* __restrict__ A, int lda, const T* __restrict__ W, int ldw, float* __restrict__ P, int ldp,
-    size_t split_stride, int m, int N, int K, int k_per_split) {
-  constexpr int E = Frag<T>::kElems;
-  constexpr int KS = Frag<T>::kStep;
-  constexpr int KC = kSteps * KS;
-  __shared__ __attribute__((aligned(16))) unsigned char lds[2][MT * 16 * kRowStride];
-
-  const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63;
-  const int r = lane & 15, g = lane >> 4;
-  const int row0 = blockIdx.z * (MT * 16);
-  const int k_begin = blockIdx.y * k_per_split;
-  const int k_end = min(K, k_begin + k_per_split);
-  const int n_base = (blockIdx.x * kWaves + wave) * (16 * NT);
-  const int n_chunks = (k_end - k_begin + KC - 1) / KC;
-
-  const T* wrow[NT];
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    int n = min(n_base + nt * 16 + r, N - 1);
-    wrow[nt] = W + (size_t)n * ldw;
-  }
-
-  Frag<T> areg[2][MT];                 // areg[j & 1]: chunk j between global memory and LDS
-  Frag<T> af[kSteps][MT];              // operand fragments of the chunk being multiplied; each slot is refilled
-                                       // with the next chunk's fragment right after its last use
-  Frag<T> breg[2][NT][kSteps];
-  f32x4 acc[MT][NT];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  auto load_a = [&](Frag<T> (&a)[MT], int chunk) {
-    const int kc = k_begin + chunk * KC;
-#pragma unroll
-    for (int i = 0; i < MT; ++i) {
-      const int f = tid + i * kThreads;
-      const int row = row0 + (f >> 4);
-      const int k = kc + (f & 15) * E;
-      if (row < m && k < k_end) a[i].raw = ld16(A + (size_t)row * lda + k);
-      else a[i].raw = u32x4{0u, 0u, 0u, 0u};
-    }
-  };
-  auto store_a = [&](const Frag<T> (&a)[MT], int buf) {
-#pragma unroll
-    for (int i = 0; i < MT; ++i) {
-      const int f = tid + i * kThreads;
-      *reinterpret_cast<u32x4*>(&lds[buf][(f >> 4) * kRowStride + (f & 15) * 16]) = a[i].raw;
-    }
-  };
-  auto read_af = [&](Frag<T> (&dst)[kSteps][MT], int buf) {
-#pragma unroll
-    for (int s = 0; s < kSteps; ++s)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        dst[s][mt].raw = *reinterpret_cast<const u32x4*>(&lds[buf][(mt * 16 + r) * kRowStride + (s * 4 + g) * 16]);
-  };
-  auto load_b = [&](Frag<T> (&b)[NT][kSteps], int chunk) {
-    const int kc = k_begin + chunk * KC;
-#pragma unroll
-    for (int s = 0; s < kSteps; ++s) {
-      const int k = kc + s * KS + g * E;
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        if (k < k_end) b[nt][s].raw = ld16(wrow[nt] + k);
-        else b[nt][s].raw = u32x4{0u, 0u, 0u, 0u};
-      }
-    }
-  };
-
-  // prologue: chunks 0 and 1 reach LDS, chunk 2 is requested, chunk 0's fragments reach registers
-  if (n_chunks > 0) {
-    load_b(breg[0], 0);
-    load_a(areg[0], 0);
-    if (n_chunks > 1) load_a(areg[1], 1);
-    store_a(areg[0], 0);
-    if (n_chunks > 1) store_a(areg[1], 1);
-    if (n_chunks > 2) load_a(areg[0], 2);
-  }
-  __syncthreads();
-  if (n_chunks > 0) read_af(af, 0);
-  __syncthreads();                     // buffer 0 may be overwritten from now on
-
-  for (int base = 0; base < n_chunks; base += 2) {
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int c = base + u;
-      if (c >= n_chunks) break;
-      const bool more = c + 1 < n_chunks;
-      if (more) load_b(breg[(u + 1) & 1], c + 1);
-      const unsigned char* nbuf = lds[(u + 1) & 1];
-#pragma unroll
-      for (int s = 0; s < kSteps; ++s)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-#pragma unroll
-          for (int nt = 0; nt < NT; ++nt) mfma16(acc[mt][nt], af[s][mt], breg[u][nt][s]);
-          // the slot just consumed is refilled with chunk c+1's fragment: LDS -> register, no wait
-          if (more)
-            af[s][mt].raw = *reinterpret_cast<const u32x4*>(&nbuf[(mt * 16 + r) * kRowStride + (s * 4 + g) * 16]);
-        }
-      // chunk c+2 (requested one iteration ago) replaces chunk c in LDS; chunk c+3 is requested
-      if (c + 2 < n_chunks) store_a(areg[u & 1], u & 1);
-      if (c + 3 < n_chunks) load_a(areg[(u + 1) & 1], c + 3);
-      __syncthreads();
-    }
-  }
-
-  float* out = P + (size_t)blockIdx.y * split_stride;
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const int col = n_base + nt * 16 + r;
-      if (col >= N) continue;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int row = row0 + mt * 16 + g * 4 + j;
-        if (row < m) out[(size_t)row * ldp + col] = acc[mt][nt][j];
-      }
-    }
-}
-
 template <typename T, int MT, int NT, int RING>
 hipError_t launch_t(const GemmPlan& pl, const void* A, int lda, const void* W, int ldw, float* P, int ldp,
                     size_t split_stride, int m, int N, int K, hipStream_t st) {
   dim3 grid((N + 64 * NT - 1) / (64 * NT), pl.splits, pl.row_chunks);
-  if (RING == 2 && pl.pre)
-    hipLaunchKernelGGL((gemm_rows_pre_kernel<T, MT, NT>), grid, dim3(kThreads), 0, st, (const T*)A, lda, (const T*)W,
-                       ldw, P, ldp, split_stride, m, N, K, pl.k_per_split);
-  else
-    hipLaunchKernelGGL((gemm_rows_kernel<T, MT, NT, RING>), grid, dim3(kThreads), 0, st, (const T*)A, lda,
-                       (const T*)W, ldw, P, ldp, split_stride, m, N, K, pl.k_per_split);
+  hipLaunchKernelGGL((gemm_rows_kernel<T, MT, NT, RING>), grid, dim3(kThreads), 0, st, (const T*)A, lda, (const T*)W,
+                     ldw, P, ldp, split_stride, m, N, K, pl.k_per_split);
   return hipGetLastError();
 }
 
@@ -313,190 +179,6 @@ hipError_t launch_mt(const GemmPlan& pl, const void* A, int lda, const void* W, 
   return hipErrorInvalidValue;
 }
 
-// ---------------------------------------------------------------------------------------------
-// Wide variant: every wave covers 64 output columns (4 column tiles), so one activation fragment
-// read from LDS feeds four matrix-core steps -- LDS traffic per weight byte is MT/4 instead of
-// MT/NT.  A workgroup is CG column groups x KW k-groups of waves: the KW waves of a column group
-// take different k-steps of each 256-byte chunk and their accumulators are added in a fixed order
-// through LDS at the end; the finished tile leaves LDS as 16-byte row-major stores.
-template <typename T, int MT, int CG, int KW, int RING>
-__global__ __launch_bounds__(64 * CG * KW) void gemm_wide_kernel(
-    const T* __restrict__ A, int lda, const T* __restrict__ W, int ldw, float* __restrict__ P, int ldp,
-    size_t split_stride, int m, int N, int K, int k_per_split) {
-  static_assert(RING == 2 || RING == 4, "ring index and A register parity must stay compile-time");
-  static_assert(KW == 1 || KW == 2 || KW == 4, "k-groups divide the four steps of a chunk");
-  constexpr int E = Frag<T>::kElems;
-  constexpr int KS = Frag<T>::kStep;
-  constexpr int KC = kSteps * KS;                // elements per chunk (= 256 bytes)
-  constexpr int PB = RING - 1;
-  constexpr int NT4 = 4;                         // column tiles per wave
-  constexpr int SPW = kSteps / KW;               // k-steps of a chunk this wave takes
-  constexpr int THREADS = 64 * CG * KW;
-  constexpr int BN = 64 * CG;                    // columns per workgroup
-  constexpr int AF = (MT * 256 + THREADS - 1) / THREADS;   // activation fragments per thread and chunk
-  constexpr int kTilePitch = BN + 4;             // floats per row of the output tile in LDS
-  constexpr int kABytes = 2 * MT * 16 * kRowStride;
-  constexpr int kTileBytes = MT * 16 * kTilePitch * 4;
-  __shared__ __attribute__((aligned(16))) unsigned char lds[kABytes > kTileBytes ? kABytes : kTileBytes];
-
-  const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63;
-  const int r = lane & 15, g = lane >> 4;
-  const int cg = wave / KW, kw = wave % KW;
-  const int row0 = blockIdx.z * (MT * 16);
-  const int k_begin = blockIdx.y * k_per_split;
-  const int k_end = min(K, k_begin + k_per_split);
-  const int n_base = blockIdx.x * BN + cg * 64;
-  const int n_chunks = (k_end - k_begin + KC - 1) / KC;
-
-  const T* wrow[NT4];
-#pragma unroll
-  for (int nt = 0; nt < NT4; ++nt) {
-    int n = min(n_base + nt * 16 + r, N - 1);
-    wrow[nt] = W + (size_t)n * ldw;
-  }
-
-  Frag<T> areg[2][AF];
-  Frag<T> breg[RING][NT4][SPW];
-  f32x4 acc[MT][NT4];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int nt = 0; nt < NT4; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  auto load_a = [&](Frag<T> (&a)[AF], int chunk) {
-    const int kc = k_begin + chunk * KC;
-#pragma unroll
-    for (int i = 0; i < AF; ++i) {
-      const int f = tid + i * THREADS;           // fragment id in the chunk: row f/16, 16-byte column f%16
-      const int row = row0 + (f >> 4);
-      const int k = kc + (f & 15) * E;
-      if (f < MT * 256 && row < m && k < k_end) a[i].raw = ld16(A + (size_t)row * lda + k);
-      else a[i].raw = u32x4{0u, 0u, 0u, 0u};
-    }
-  };
-  auto store_a = [&](const Frag<T> (&a)[AF], int buf) {
-#pragma unroll
-    for (int i = 0; i < AF; ++i) {
-      const int f = tid + i * THREADS;
-      if (f < MT * 256)
-        *reinterpret_cast<u32x4*>(&lds[buf * (MT * 16 * kRowStride) + (f >> 4) * kRowStride + (f & 15) * 16]) =
-            a[i].raw;
-    }
-  };
-  auto load_b = [&](Frag<T> (&b)[NT4][SPW], int chunk) {
-    const int kc = k_begin + chunk * KC;
-#pragma unroll
-    for (int s = 0; s < SPW; ++s) {
-      const int k = kc + (kw * SPW + s) * KS + g * E;
-#pragma unroll
-      for (int nt = 0; nt < NT4; ++nt) {
-        if (k < k_end) b[nt][s].raw = ld16(wrow[nt] + k);
-        else b[nt][s].raw = u32x4{0u, 0u, 0u, 0u};
-      }
-    }
-  };
-
-#pragma unroll
-  for (int u = 0; u < PB; ++u)
-    if (u < n_chunks) load_b(breg[u], u);
-  if (n_chunks > 0) {
-    load_a(areg[0], 0);
-    if (n_chunks > 1) load_a(areg[1], 1);
-    store_a(areg[0], 0);
-  }
-  __syncthreads();
-
-  for (int base = 0; base < n_chunks; base += RING) {
-#pragma unroll
-    for (int u = 0; u < RING; ++u) {
-      const int c = base + u;
-      if (c >= n_chunks) break;
-      if (c + 2 < n_chunks) load_a(areg[u & 1], c + 2);
-      if (c + PB < n_chunks) load_b(breg[(u + PB) % RING], c + PB);
-      const unsigned char* abuf = lds + (u & 1) * (MT * 16 * kRowStride);
-#pragma unroll
-      for (int s = 0; s < SPW; ++s) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          Frag<T> af;
-          af.raw = *reinterpret_cast<const u32x4*>(
-              &abuf[(mt * 16 + r) * kRowStride + ((kw * SPW + s) * 4 + g) * 16]);
-#pragma unroll
-          for (int nt = 0; nt < NT4; ++nt) mfma16(acc[mt][nt], af, breg[u][nt][s]);
-        }
-      }
-      if (c + 1 < n_chunks) store_a(areg[(u + 1) & 1], (u + 1) & 1);
-      __syncthreads();
-    }
-  }
-
-  // add the k-groups' accumulators in the order kw = 0, 1, .. into one tile in LDS (the activation
-  // buffers are free after the last barrier), then write the tile row-major
-  float* tile = reinterpret_cast<float*>(lds);
-#pragma unroll
-  for (int turn = 0; turn < KW; ++turn) {
-    if (kw == turn) {
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < NT4; ++nt)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            float* cell = &tile[(mt * 16 + g * 4 + j) * kTilePitch + cg * 64 + nt * 16 + r];
-            *cell = (turn == 0 ? 0.f : *cell) + acc[mt][nt][j];
-          }
-    }
-    __syncthreads();
-  }
-  float* out = P + (size_t)blockIdx.y * split_stride;
-  const int col0 = blockIdx.x * BN;
-  constexpr int V4 = BN / 4;                     // 16-byte vectors per tile row
-  if (((ldp | col0) & 3) == 0 && col0 + BN <= N) {
-    for (int e = tid; e < MT * 16 * V4; e += THREADS) {
-      const int row = e / V4, c4 = (e - row * V4) * 4;
-      if (row0 + row < m)
-        *reinterpret_cast<f32x4*>(&out[(size_t)(row0 + row) * ldp + col0 + c4]) =
-            *reinterpret_cast<const f32x4*>(&tile[row * kTilePitch + c4]);
-    }
-  } else {
-    for (int e = tid; e < MT * 16 * BN; e += THREADS) {
-      const int row = e / BN, c = e - row * BN;
-      if (row0 + row < m && col0 + c < N) out[(size_t)(row0 + row) * ldp + col0 + c] = tile[row * kTilePitch + c];
-    }
-  }
-}
-
-template <typename T, int MT, int CG, int KW, int RING>
-hipError_t launch_wide_t(const GemmPlan& pl, const void* A, int lda, const void* W, int ldw, float* P, int ldp,
-                         size_t split_stride, int m, int N, int K, hipStream_t st) {
-  dim3 grid((N + 64 * CG - 1) / (64 * CG), pl.splits, pl.row_chunks);
-  hipLaunchKernelGGL((gemm_wide_kernel<T, MT, CG, KW, RING>), grid, dim3(64 * CG * KW), 0, st, (const T*)A, lda,
-                     (const T*)W, ldw, P, ldp, split_stride, m, N, K, pl.k_per_split);
-  return hipGetLastError();
-}
-
-template <typename T, int CG, int KW>
-hipError_t launch_wide_mt(const GemmPlan& pl, const void* A, int lda, const void* W, int ldw, float* P, int ldp,
-                          size_t ss, int m, int N, int K, hipStream_t st) {
-  switch (pl.mt) {
-    case 1: return launch_wide_t<T, 1, CG, KW, 2>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 2: return launch_wide_t<T, 2, CG, KW, 2>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 3: return launch_wide_t<T, 3, CG, KW, 2>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 4: return launch_wide_t<T, 4, CG, KW, 2>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 5: return launch_wide_t<T, 5, CG, KW, 2>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 6: return launch_wide_t<T, 6, CG, KW, 2>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-  }
-  return hipErrorInvalidValue;
-}
-
-template <typename T>
-hipError_t launch_wide(const GemmPlan& pl, const void* A, int lda, const void* W, int ldw, float* P, int ldp,
-                       size_t ss, int m, int N, int K, hipStream_t st) {
-  if (pl.cg == 2) return launch_wide_mt<T, 2, 2>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-  return launch_wide_mt<T, 1, 4>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-}
-
 template <typename T>
 hipError_t launch_nt(const GemmPlan& pl, const void* A, int lda, const void* W, int ldw, float* P, int ldp,
                      size_t ss, int m, int N, int K, hipStream_t st) {
@@ -514,29 +196,13 @@ GemmPlan plan_gemm(int dtype, int m, int N, int K, bool single_split) {
   const Tunables& t = tunables();
   GemmPlan pl;
   const int tiles = (m + 15) / 16;
-  const int kc = dtype == kBF16 ? 128 : 64;                       // elements per 256-byte chunk
-  const int chunks = (K + kc - 1) / kc;
-  pl.wide = t.gemm_wide != 0;
-  pl.pre = t.gemm_pre != 0;
+  pl.mt = tiles <= 8 ? (tiles < 1 ? 1 : tiles) : 8;
+  pl.row_chunks = tiles <= 8 ? 1 : (tiles + 7) / 8;
+  pl.nt = N > t.gemm_nt_big_n ? 2 : 1;
   pl.ring = t.gemm_ring == 4 ? 4 : 2;
-  int cols_per_wg;
-  if (pl.wide) {
-    const int max_mt = 6;                                          // accumulators: 16 registers per row tile
-    pl.mt = tiles <= max_mt ? (tiles < 1 ? 1 : tiles) : max_mt;
-    pl.row_chunks = (tiles + pl.mt - 1) / pl.mt;
-    if (pl.row_chunks > 1) pl.mt = (tiles + pl.row_chunks - 1) / pl.row_chunks;
-    pl.cg = N > t.gemm_cg2_min_n ? 2 : 1;
-    pl.nt = 4;
-    pl.ring = 2;
-    cols_per_wg = 64 * pl.cg;
-  } else {
-    pl.mt = tiles <= 8 ? (tiles < 1 ? 1 : tiles) : 8;
-    pl.row_chunks = tiles <= 8 ? 1 : (tiles + 7) / 8;
-    pl.nt = N > t.gemm_nt_big_n ? 2 : 1;
-    pl.cg = 4;
-    cols_per_wg = 64 * pl.nt;
-  }
-  const int n_blocks = (N + cols_per_wg - 1) / cols_per_wg;
+  const int kc = dtype == kBF16 ? 128 : 64;                       // elements per 256-byte chunk
+  const int n_blocks = (N + 64 * pl.nt - 1) / (64 * pl.nt);
+  const int chunks = (K + kc - 1) / kc;
   int splits = 1;
   while (!single_split && splits < t.gemm_max_splits && n_blocks * pl.row_chunks * splits < t.gemm_target_wgs &&
          chunks / (splits * 2) >= 2)
@@ -555,10 +221,6 @@ hipError_t launch_gemm(int dtype, const GemmPlan& pl, const void* A, int lda, co
   if (K % e || lda % e || ldw % e) return hipErrorInvalidValue;
   if (pl.mt * 16 * pl.row_chunks < m || (size_t)pl.k_per_split * pl.splits < (size_t)K) return hipErrorInvalidValue;
   if (split_stride < (size_t)m * ldp || ldp < N) return hipErrorInvalidValue;
-  if (pl.wide) {
-    if (dtype == kBF16) return launch_wide<bf16>(pl, A, lda, W, ldw, P, ldp, split_stride, m, N, K, st);
-    return launch_wide<float>(pl, A, lda, W, ldw, P, ldp, split_stride, m, N, K, st);
-  }
   if (dtype == kBF16) return launch_nt<bf16>(pl, A, lda, W, ldw, P, ldp, split_stride, m, N, K, st);
   return launch_nt<float>(pl, A, lda, W, ldw, P, ldp, split_stride, m, N, K, st);
 }

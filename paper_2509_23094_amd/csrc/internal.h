@@ -15,9 +15,6 @@ struct Tunables {
   int gemm_target_wgs = 512;   // aim for at least this many workgroups per GEMM
   int gemm_max_splits = 8;
   int gemm_nt_big_n = 16384;   // N above this uses two column tiles per wave
-  int gemm_pre = 1;            // rows kernel with register prefetch of the activation fragments
-  int gemm_wide = 0;           // 1: gemm_wide_kernel, 0: gemm_rows_kernel
-  int gemm_cg2_min_n = 8192;   // wide kernel: N above this uses 128-column workgroups
   int gemm_ring = 2;           // weight chunks per wave in registers (2 or 4)
   bool side_stream = true;     // d2c_step: head average + rollout on a second stream
 };
@@ -27,9 +24,6 @@ Tunables& tunables();
 struct GemmPlan {
   int mt;        // 16-row tiles per workgroup (1..8)
   int nt;        // 16-column tiles per wave (1 or 2)
-  bool pre;      // rows kernel: next chunk's activation fragments prefetched into registers
-  bool wide;     // gemm_wide_kernel (64 columns per wave) instead of gemm_rows_kernel
-  int cg;        // wide kernel: column groups per workgroup (1: 64 columns x 4 k-groups, 2: 128 columns x 2 k-groups)
   int ring;      // weight chunks a wave holds in registers (2 or 4)
   int splits;    // k splits (partials to be summed by the consumer)
   int k_per_split;
@@ -84,8 +78,10 @@ hipError_t launch_influence(const float* c_block, const int32_t* idx, int m, int
 
 // ---- selection
 // Eq. 1 per logits row; the row's position is via ? via[pos[row]] : pos[row]
+// scratch: confidence_scratch_floats(n_rows) floats
+size_t confidence_scratch_floats(int n_rows);
 hipError_t launch_confidence(const float* logits, const int32_t* pos, const int32_t* via, int n_rows, int vocab,
-                             float* conf, int32_t* pred, hipStream_t st);
+                             float* conf, int32_t* pred, float* scratch, hipStream_t st);
 struct SelectArgs {
   float sigma; int k; float p; int block_len; int n_unmask; int cand_mode;
   int32_t* tokens; uint8_t* is_masked; int L; int prompt_len;

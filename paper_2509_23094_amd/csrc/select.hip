@@ -14,24 +14,28 @@ namespace d2c {
 namespace {
 
 // ------------------------------------------------------------------ Eq. 1
-constexpr int kConfThreads = 1024;
+// x-hat = argmax_v, s = 1 / sum_v exp(x_v - max).  A vocabulary row (0.5 MB at V = 126464) is cut into
+// chunks, one workgroup each, so that a few dozen rows still fill the chip: per chunk (max, first index of
+// the max, sum of exp(x - chunk max)); a second tiny launch merges the chunks of a row in ascending order
+// (ties keep the lowest index) -- fixed order, bit-reproducible.
+constexpr int kConfThreads = 256;
+constexpr int kConfMaxChunks = 64;
 
-__global__ __launch_bounds__(kConfThreads) void confidence_kernel(const float* __restrict__ logits,
-                                                                  const int32_t* __restrict__ pos,
-                                                                  const int32_t* __restrict__ via, int vocab,
-                                                                  float* __restrict__ conf,
-                                                                  int32_t* __restrict__ pred) {
+__global__ __launch_bounds__(kConfThreads) void confidence_chunk_kernel(const float* __restrict__ logits, int vocab,
+                                                                        int chunk, int n_chunks,
+                                                                        float* __restrict__ part) {
   __shared__ float s_val[kConfThreads / 64];
   __shared__ int s_idx[kConfThreads / 64];
   __shared__ float s_sum[kConfThreads / 64];
-  const float* row = logits + (size_t)blockIdx.x * vocab;
+  const int row = blockIdx.y, ck = blockIdx.x;
+  const float* x = logits + (size_t)row * vocab;
+  const int lo = ck * chunk, hi = min(vocab, lo + chunk);
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  // arg-max, ties to the lowest index: a thread scans its indices in ascending order
   float best = -INFINITY;
   int bidx = 0x7fffffff;
-  for (int v = tid; v < vocab; v += kConfThreads) {
-    const float x = row[v];
-    if (x > best || (x == best && v < bidx)) { best = x; bidx = v; }
+  for (int v = lo + tid; v < hi; v += kConfThreads) {       // ascending per thread: a tie keeps the lower index
+    const float xv = x[v];
+    if (xv > best) { best = xv; bidx = v; }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
@@ -47,19 +51,36 @@ __global__ __launch_bounds__(kConfThreads) void confidence_kernel(const float* _
     const int oi = s_idx[w];
     if (ob > best || (ob == best && oi < bidx)) { best = ob; bidx = oi; }
   }
-  // s = p(x-hat) = 1 / sum_v exp(x_v - max)
   float sum = 0.f;
-  for (int v = tid; v < vocab; v += kConfThreads) sum += expf(row[v] - best);
+  for (int v = lo + tid; v < hi; v += kConfThreads) sum += expf(x[v] - best);
   sum = wave_sum(sum);
   if (lane == 0) s_sum[wave] = sum;
   __syncthreads();
   if (tid == 0) {
     float t = 0.f;
     for (int w = 0; w < kConfThreads / 64; ++w) t += s_sum[w];
-    const int p = via ? via[pos[blockIdx.x]] : pos[blockIdx.x];    // row -> position, directly or through S
-    conf[p] = 1.0f / t;
-    pred[p] = bidx;
+    float* o = part + ((size_t)row * n_chunks + ck) * 3;
+    o[0] = best;
+    o[1] = __int_as_float(bidx);
+    o[2] = t;
   }
+}
+
+__global__ void confidence_merge_kernel(const float* __restrict__ part, int n_rows, int n_chunks,
+                                        const int32_t* __restrict__ pos, const int32_t* __restrict__ via,
+                                        float* __restrict__ conf, int32_t* __restrict__ pred) {
+  const int row = blockIdx.x * blockDim.x + threadIdx.x;
+  if (row >= n_rows) return;
+  const float* p = part + (size_t)row * n_chunks * 3;
+  float best = p[0];
+  int bidx = __float_as_int(p[1]);
+  for (int c = 1; c < n_chunks; ++c)
+    if (p[3 * c] > best) { best = p[3 * c]; bidx = __float_as_int(p[3 * c + 1]); }   // ascending chunks: lowest index wins
+  float sum = 0.f;
+  for (int c = 0; c < n_chunks; ++c) sum += p[3 * c + 2] * expf(p[3 * c] - best);
+  const int where = via ? via[pos[row]] : pos[row];            // row -> position, directly or through S
+  conf[where] = 1.0f / sum;
+  pred[where] = bidx;
 }
 
 // ------------------------------------------------------------------ Eq. 6-8 on the compact block
@@ -382,12 +403,21 @@ __global__ __launch_bounds__(kSelThreads) void seq_reset_kernel(const uint8_t* _
 
 int select_max_len() { return kSelMaxL; }
 
+size_t confidence_scratch_floats(int n_rows) { return (size_t)n_rows * kConfMaxChunks * 3; }
+
 hipError_t launch_confidence(const float* logits, const int32_t* pos, const int32_t* via, int n_rows, int vocab,
-                             float* conf, int32_t* pred, hipStream_t st) {
+                             float* conf, int32_t* pred, float* scratch, hipStream_t st) {
   if (n_rows <= 0) return hipSuccess;
-  if (vocab <= 0) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(confidence_kernel, dim3(n_rows), dim3(kConfThreads), 0, st, logits, pos, via, vocab, conf,
-                     pred);
+  if (vocab <= 0 || scratch == nullptr) return hipErrorInvalidValue;
+  int chunk = 8192;
+  while ((vocab + chunk - 1) / chunk > kConfMaxChunks) chunk *= 2;
+  const int n_chunks = (vocab + chunk - 1) / chunk;
+  hipLaunchKernelGGL(confidence_chunk_kernel, dim3(n_chunks, n_rows), dim3(kConfThreads), 0, st, logits, vocab, chunk,
+                     n_chunks, scratch);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(confidence_merge_kernel, dim3((n_rows + 63) / 64), dim3(64), 0, st, scratch, n_rows, n_chunks,
+                     pos, via, conf, pred);
   return hipGetLastError();
 }
 
