@@ -32,6 +32,16 @@ the HIP path takes too):
       floor(double(p) * double(sum)).
   R11 with block-wise semi-autoregressive decoding the stage-1 and decode
       candidates are the masked tokens of the leftmost unfinished block.
+  R15 parallel decoding (appendix, "parallel decoding settings", threshold 0.9):
+      besides the n_unmask best-scored candidates, every candidate whose
+      confidence s^i exceeds the threshold is unmasked in the same step; the
+      threshold is taken on s^i (a probability), not on D(i) s^i.
+  R16 confidence-based decoding (the `Conf` rows of the decoding-scheme table):
+      the decode set ranks candidates by s^i alone; M* still uses D(i) s^i.
+  R17 every token unmasked at step t is fed again at t+1: S_{t+1} = M* u I_t u U
+      (equal to M* u U whenever I_t is inside M*, i.e. without R15/R16).
+  R18 lightweight rollout (appendix, "lightweight variants of attention
+      rollout"): only the first r layers' A-bar enter Eq. 6-8.
 
 Parity status: every function below is pinned by tests/test_oracle_*.py to
 closed forms, invariants, library witnesses or brute force.  Agreement with the
@@ -73,6 +83,9 @@ class Params:
     block_len: int = 32
     n_unmask: int = 1
     cand_mode: int = 0
+    threshold: float = 0.0        # > 0: parallel decoding by confidence threshold (R15)
+    conf_decode: int = 0          # 1: decode by confidence alone (R16)
+    rollout_layers: int = 0       # r > 0: rollout over the first r layers only (R18)
 
 
 @dataclass
@@ -294,7 +307,7 @@ def forward_rows(dims: Dims, model: Dict, st: SeqState, S: np.ndarray
 def select(params: Params, is_masked: np.ndarray, prompt_len: int, conf: np.ndarray,
            c: np.ndarray) -> Dict[str, np.ndarray]:
     """Two-stage selection plus the decode set, from cached confidences and the
-    influence scores.  Returns D, score, M*, I_t, U and S_{t+1} = sort(M* u U)."""
+    influence scores.  Returns D, score, M*, I_t, U and S_{t+1} = sort(M* u I_t u U)."""
     L = len(is_masked)
     is_masked = np.asarray(is_masked, bool)
     D = certainty_density(is_masked, params.sigma)
@@ -302,13 +315,17 @@ def select(params: Params, is_masked: np.ndarray, prompt_len: int, conf: np.ndar
     lo, hi = current_block(is_masked, prompt_len, params.block_len)
     cand1 = np.array([i for i in range(lo, hi) if is_masked[i]], np.int64)
     mstar = top_k_select(score, cand1, params.k)
-    decode = top_k_select(score, cand1, params.n_unmask)
+    conf32 = np.asarray(conf, np.float32)
+    decode = top_k_select(conf32 if params.conf_decode else score, cand1, params.n_unmask)
+    if params.threshold > 0:
+        sure = [i for i in cand1 if conf32[i] > np.float32(params.threshold)]
+        decode = np.union1d(decode, np.array(sure, np.int32)).astype(np.int32)
     if params.cand_mode == 0:
         cand2 = np.flatnonzero(~is_masked)
     else:
         cand2 = np.setdiff1d(np.arange(L), mstar)
     u = top_p_select(np.asarray(c, np.float32), cand2, params.p)
-    s_next = np.union1d(mstar, u).astype(np.int32)
+    s_next = np.union1d(np.union1d(mstar, decode), u).astype(np.int32)
     return {"D": D, "score": score, "mstar": mstar, "decode": decode, "u": u, "s_next": s_next,
             "block": (lo, hi)}
 
@@ -320,7 +337,8 @@ def d2cache_step(dims: Dims, model: Dict, params: Params, st: SeqState) -> None:
     L = len(st.y)
     S = np.asarray(st.S, np.int64)
     h, abars = forward_rows(dims, model, st, S)
-    C = rollout(abars, S, L)
+    r = params.rollout_layers
+    C = rollout(abars[:r] if r > 0 else abars, S, L)
     c = influence(C)
     rows = np.array([r for r, i in enumerate(S) if st.is_masked[i]], np.int64)
     logits = np.zeros((0, dims.vocab), F64)

@@ -224,3 +224,57 @@ def test_select_contract():
     # select-all switch: k >= |M|, p = 1, one block
     sel2 = O.select(O.Params(k=L, p=1.0, block_len=L), is_masked, P, conf, c)
     assert list(sel2["s_next"]) == list(range(L))
+
+
+# ------------------------------------------------------------------ decoding-scheme switches
+def _toy(L=40, P=8):
+    is_masked = np.zeros(L, bool); is_masked[P:] = True
+    conf = np.linspace(0.2, 0.6, L).astype(np.float32)          # later positions are more confident
+    c = np.ones(L, np.float32)
+    return is_masked, conf, c
+
+
+def test_parallel_threshold_decoding():
+    is_masked, conf, c = _toy()
+    P = 8
+    base = O.select(O.Params(sigma=2.0, k=4, p=0.2, block_len=16, n_unmask=1), is_masked, P, conf, c)
+    assert len(base["decode"]) == 1
+    # nothing above the threshold: exactly the n_unmask best-scored ones, as without it
+    hi = O.select(O.Params(sigma=2.0, k=4, p=0.2, block_len=16, n_unmask=1, threshold=0.99), is_masked, P, conf, c)
+    assert list(hi["decode"]) == list(base["decode"])
+    # threshold below every confidence: the whole block is unmasked, and all of it is fed again (R17)
+    lo = O.select(O.Params(sigma=2.0, k=4, p=0.2, block_len=16, n_unmask=1, threshold=0.1), is_masked, P, conf, c)
+    assert list(lo["decode"]) == list(range(P, P + 16))
+    assert set(lo["decode"]) <= set(lo["s_next"]) and set(lo["mstar"]) <= set(lo["s_next"])
+    # a threshold in between takes exactly the candidates above it, plus the best-scored one
+    conf2 = conf.copy(); conf2[[10, 13]] = 0.95
+    mid = O.select(O.Params(sigma=2.0, k=4, p=0.2, block_len=16, n_unmask=1, threshold=0.9), is_masked, P, conf2, c)
+    assert set(mid["decode"]) == {10, 13} | set(O.top_k_select(mid["score"], np.arange(P, P + 16), 1))
+    # the comparison is strict
+    eq = O.select(O.Params(sigma=2.0, k=4, p=0.2, block_len=16, n_unmask=1, threshold=float(np.float32(0.95))),
+                  is_masked, P, conf2, c)
+    assert 13 not in set(eq["decode"]) - set(O.top_k_select(eq["score"], np.arange(P, P + 16), 1))
+
+
+def test_confidence_only_decoding():
+    is_masked, conf, c = _toy()
+    P = 8
+    # the certainty prior prefers the position next to the prompt, the confidence the end of the block
+    cp = O.select(O.Params(sigma=2.0, k=4, p=0.2, block_len=16, n_unmask=1), is_masked, P, conf, c)
+    cf = O.select(O.Params(sigma=2.0, k=4, p=0.2, block_len=16, n_unmask=1, conf_decode=1), is_masked, P, conf, c)
+    assert list(cp["decode"]) == [P]
+    assert list(cf["decode"]) == [P + 15]
+    assert list(cf["mstar"]) == list(cp["mstar"])                # stage 1 is unchanged
+    assert P + 15 in cf["s_next"]                                # R17
+
+
+def test_rollout_over_first_layers_only():
+    L, S = 12, np.array([1, 4, 7, 8])
+    rng = np.random.default_rng(0)
+    abars = []
+    for _ in range(4):
+        a = rng.random((4, L)); abars.append(a / a.sum(axis=1, keepdims=True))
+    full = O.rollout(abars, S, L)
+    first2 = O.rollout(abars[:2], S, L)
+    assert not np.allclose(full, first2)
+    np.testing.assert_allclose(first2.sum(axis=1), 1.0, atol=1e-14)
