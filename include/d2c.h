@@ -86,13 +86,19 @@ typedef struct {
   int32_t block_len;
   int32_t n_unmask;
   int32_t cand_mode;
+  float   threshold;       /* > 0: parallel decoding -- every stage-1 candidate whose confidence s^i
+                              exceeds it is unmasked too (appendix, parallel decoding, 0.9); 0 = off */
+  int32_t conf_decode;     /* 1: the decode set ranks by s^i alone (the `Conf` decoding of the
+                              decoding-scheme table); M* still ranks by D(i) s^i                   */
+  int32_t rollout_layers;  /* r > 0: only the first r layers enter the rollout (appendix,
+                              lightweight rollout); 0 = all layers                                  */
 } d2c_params;
 
 /* Slots of the `counts` array written by d2c_select. */
 enum {
   D2C_CNT_MSTAR = 0,      /* |M*|                                                 */
   D2C_CNT_U = 1,          /* |U|                                                  */
-  D2C_CNT_S = 2,          /* |S_{t+1}| = |M* u U|                                 */
+  D2C_CNT_S = 2,          /* |S_{t+1}| = |M* u I_t u U|                           */
   D2C_CNT_DECODE = 3,     /* |I_t|                                                */
   D2C_CNT_NEXT_ROWS = 4,  /* members of S_{t+1} still masked after unmasking      */
   D2C_CNT_MASKED = 5,     /* |M_{t+1}|                                            */
@@ -148,7 +154,7 @@ int d2c_seq_reset(d2c_ctx* ctx, d2c_seq_state* seq, void* stream);
  * generation slots; U = smallest prefix, in descending c_j, of the candidates
  * whose mass exceeds p * (candidates' total) (ties to the lowest index; masses
  * in fixed point floor(c*2^32)); tokens[i] <- pred[i], is_masked[i] <- 0 for
- * i in I_t.  Outputs (ascending): mstar, u_set, decode_idx, s_next = M* u U,
+ * i in I_t.  Outputs (ascending): mstar, u_set, decode_idx, s_next = M* u I_t u U,
  * s_rows_next = rows r of s_next whose token is still masked, counts, and (if
  * score_out is not NULL) the float scores D(i)*conf[i] the top-k was taken on,
  * 0 outside the stage-1 candidates.  influence must be finite and >= 0.

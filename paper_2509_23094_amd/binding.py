@@ -44,7 +44,8 @@ class d2c_weights(C.Structure):
 
 class d2c_params(C.Structure):
     _fields_ = [("sigma", C.c_float), ("k", C.c_int32), ("p", C.c_float), ("block_len", C.c_int32),
-                ("n_unmask", C.c_int32), ("cand_mode", C.c_int32)]
+                ("n_unmask", C.c_int32), ("cand_mode", C.c_int32), ("threshold", C.c_float),
+                ("conf_decode", C.c_int32), ("rollout_layers", C.c_int32)]
 
 
 class d2c_seq_state(C.Structure):
@@ -116,8 +117,10 @@ def d2c_set_tunable(name: str, value: int) -> None:
         raise D2CError(rc, "unknown tunable %r" % name)
 
 
-def make_params(sigma=10.0, k=32, p=0.1, block_len=32, n_unmask=1, cand_mode=0) -> d2c_params:
-    return d2c_params(float(sigma), int(k), float(p), int(block_len), int(n_unmask), int(cand_mode))
+def make_params(sigma=10.0, k=32, p=0.1, block_len=32, n_unmask=1, cand_mode=0, threshold=0.0, conf_decode=0,
+                rollout_layers=0) -> d2c_params:
+    return d2c_params(float(sigma), int(k), float(p), int(block_len), int(n_unmask), int(cand_mode),
+                      float(threshold), int(conf_decode), int(rollout_layers))
 
 
 class Context:

@@ -202,7 +202,8 @@ int check_idx_host(d2c_ctx* c, const int32_t* idx_host, int m, int L) {
 int check_params(d2c_ctx* c, const d2c_params* p) {
   if (!p) return fail(c, D2C_EINVAL, "params is null");
   if (!(p->sigma > 0.f) || p->k < 0 || p->block_len <= 0 || p->n_unmask < 0 || !(p->p >= 0.f) ||
-      (p->cand_mode != 0 && p->cand_mode != 1))
+      (p->cand_mode != 0 && p->cand_mode != 1) || !(p->threshold >= 0.f) ||
+      (p->conf_decode != 0 && p->conf_decode != 1) || p->rollout_layers < 0)
     return fail(c, D2C_EINVAL, "bad selection parameters");
   return D2C_OK;
 }
@@ -379,7 +380,8 @@ int d2c_select(d2c_ctx* c, const d2c_params* p, const float* logits, const int32
   hipStream_t st = (hipStream_t)stream;
   if (n_rows > c->dims.max_seq) return fail(c, D2C_ESHAPE, "n_rows exceeds max_seq of the context");
   D2C_HIP(c, launch_confidence(logits, logit_pos, nullptr, n_rows, c->dims.vocab, conf, pred, c->conf_part, st));
-  SelectArgs a{p->sigma, p->k, p->p, p->block_len, p->n_unmask, p->cand_mode, tokens, is_masked, L, prompt_len,
+  SelectArgs a{p->sigma, p->k, p->p, p->block_len, p->n_unmask, p->cand_mode, p->threshold, p->conf_decode,
+               tokens, is_masked, L, prompt_len,
                conf, pred, influence, mstar, u_set, decode_idx, s_next, s_rows_next, counts, score_out};
   D2C_HIP(c, launch_select(a, st));
   return D2C_OK;
@@ -488,14 +490,17 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
       D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
                 launch_embed_norm(dt, c->tok_emb, s.tokens, s.s_idx, m, d, c->attn_norm[0], D.rms_eps, c->hidden,
                                   c->a_norm, st));
+      const int roll_layers = p->rollout_layers > 0 ? std::min(p->rollout_layers, D.n_layers) : D.n_layers;
       for (int l = 0; l < D.n_layers; ++l) {
         char* kc = (char*)s.k_cache + (size_t)l * L * cache_layer;
         char* vc = (char*)s.v_cache + (size_t)l * L * cache_layer;
-        rc = layer_impl(c, l, c->hidden, s.s_idx, m, kc, vc, L, c->abar, c->roll[l & 1], c->roll[(l + 1) & 1], true,
+        const bool in_rollout = l < roll_layers;     // later layers skip the head average altogether
+        rc = layer_impl(c, l, c->hidden, s.s_idx, m, kc, vc, L, in_rollout ? c->abar : nullptr, c->roll[l & 1],
+                        in_rollout ? c->roll[(l + 1) & 1] : nullptr, true,
                         l + 1 < D.n_layers ? c->attn_norm[l + 1] : nullptr, st, side);
         if (rc) return rc;
       }
-      roll_final = c->roll[D.n_layers & 1];
+      roll_final = c->roll[roll_layers & 1];
       if (side != st) {                       // join: the influence scores need the last rollout update
         D2C_HIP(c, hipEventRecord(c->side_done, side));
         D2C_HIP(c, hipStreamWaitEvent(st, c->side_done, 0));
@@ -518,7 +523,8 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
         D2C_HIP(c, hipMemcpyAsync(s.logits_out + (size_t)r0 * D.vocab, c->logits, (size_t)nr * D.vocab * 4,
                                   hipMemcpyDeviceToDevice, st));
     }
-    SelectArgs a{p->sigma, p->k, p->p, p->block_len, p->n_unmask, p->cand_mode, s.tokens, s.is_masked, L,
+    SelectArgs a{p->sigma, p->k, p->p, p->block_len, p->n_unmask, p->cand_mode, p->threshold, p->conf_decode,
+                 s.tokens, s.is_masked, L,
                  s.prompt_len, s.conf, s.pred, s.influence, s.mstar, s.u_set, s.decode_idx, s.s_idx, s.s_rows,
                  s.counts, s.score};
     D2C_TIMED(c, st, D2C_PROF_SELECT, 0.0, launch_select(a, st));

@@ -83,7 +83,7 @@ size_t confidence_scratch_floats(int n_rows);
 hipError_t launch_confidence(const float* logits, const int32_t* pos, const int32_t* via, int n_rows, int vocab,
                              float* conf, int32_t* pred, float* scratch, hipStream_t st);
 struct SelectArgs {
-  float sigma; int k; float p; int block_len; int n_unmask; int cand_mode;
+  float sigma; int k; float p; int block_len; int n_unmask; int cand_mode; float threshold; int conf_decode;
   int32_t* tokens; uint8_t* is_masked; int L; int prompt_len;
   const float* conf; const int32_t* pred; const float* influence;
   int32_t *mstar, *u_set, *decode_idx, *s_next, *s_rows_next, *counts;

@@ -259,14 +259,24 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a, int N
   }
   __syncthreads();
 
-  // ---- phase 2: Eq. 4 (top-k) and the decode set (top-n_unmask) by rank counting
+  // ---- phase 2: Eq. 4 (top-k) and the decode set by rank counting.  The decode set ranks the same
+  // scores, or the confidences alone (conf_decode), and with a threshold also takes every candidate
+  // whose confidence exceeds it.
+  if (a.conf_decode)
+    for (int c = tid; c < n1; c += kSelThreads) keys[c] = make_key(a.conf[cand[c]], cand[c]);
+  __syncthreads();
+  const unsigned long long* dkeys = a.conf_decode ? keys : keys1;
   for (int c = tid; c < n1; c += kSelThreads) {
-    const unsigned long long mine = keys1[c];
-    int rank = 0;
-    for (int o = 0; o < n1; ++o) rank += keys1[o] > mine ? 1 : 0;
+    const unsigned long long mine = keys1[c], dmine = dkeys[c];
+    int rank = 0, drank = 0;
+    for (int o = 0; o < n1; ++o) {
+      rank += keys1[o] > mine ? 1 : 0;
+      drank += dkeys[o] > dmine ? 1 : 0;
+    }
     unsigned char f = 0;
     if (rank < a.k) f |= 1;
-    if (rank < a.n_unmask) f |= 4;
+    if (drank < a.n_unmask) f |= 4;
+    if (a.threshold > 0.f && a.conf[cand[c]] > a.threshold) f |= 4;
     sel[cand[c]] = f;
   }
   __syncthreads();
@@ -356,7 +366,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a, int N
   }
   const int n_u = block_compact(L, [&](int j) { return (sel[j] & 2) != 0; },
                                 [&](int slot, int j) { a.u_set[slot] = j; }, sh);
-  const int n_s = block_compact(L, [&](int j) { return (sel[j] & 3) != 0; },
+  const int n_s = block_compact(L, [&](int j) { return sel[j] != 0; },
                                 [&](int slot, int j) { a.s_next[slot] = j; slist[slot] = j; }, sh);
   const int n_rows = block_compact(n_s, [&](int rr) { return msk[slist[rr]] != 0; },
                                    [&](int slot, int rr) { a.s_rows_next[slot] = rr; }, sh);

@@ -246,7 +246,7 @@ def _run_select(B, ctx, prm, logits, logit_pos, y, is_masked, P, conf, pred, c):
 
 
 SELECT_CASES = [
-    # L, P, vocab, block_len, k, n_unmask, p, sigma, frac_known, cand_mode, skewed
+    # L, P, vocab, block_len, k, n_unmask, p, sigma, frac_known, cand_mode, skewed[, threshold, conf_decode]
     (128, 64, 1024, 32, 8, 1, 0.9, 10.0, 0.0, 0, False),
     (128, 64, 1024, 32, 8, 1, 0.9, 10.0, 0.4, 0, True),
     (512, 256, 126464, 32, 32, 1, 0.1, 10.0, 0.3, 0, True),      # LLaDA-8B-shaped step, full vocabulary
@@ -257,12 +257,17 @@ SELECT_CASES = [
     (64, 8, 64, 16, 100, 100, 1.0, 10.0, 0.2, 0, False),         # select-all switch, unmask the whole block
     (40, 40, 64, 8, 4, 1, 0.5, 10.0, 0.0, 0, False),             # nothing masked
     (97, 0, 64, 32, 5, 1, 0.0, 10.0, 0.1, 0, True),              # no prompt, p = 0
+    (512, 256, 4096, 32, 8, 1, 0.1, 10.0, 0.3, 0, True, 0.5, 0),     # parallel decoding: threshold on s^i
+    (512, 256, 4096, 32, 8, 2, 0.1, 10.0, 0.3, 0, True, 0.0, 1),     # decode by confidence alone
+    (300, 100, 512, 64, 4, 1, 0.2, 5.0, 0.5, 1, False, 0.9, 1),      # both, literal candidate mode
 ]
 
 
-@pytest.mark.parametrize("L,P,V,blk,k,nu,p,sigma,frac,mode,skew", SELECT_CASES)
-def test_select_parity(B, L, P, V, blk, k, nu, p, sigma, frac, mode, skew):
-    say(f"select L={L} P={P} V={V} block={blk} k={k} n_unmask={nu} p={p} sigma={sigma} mode={mode}")
+@pytest.mark.parametrize("case", SELECT_CASES, ids=[str(i) for i in range(len(SELECT_CASES))])
+def test_select_parity(B, case):
+    L, P, V, blk, k, nu, p, sigma, frac, mode, skew = case[:11]
+    thr, cdec = (case[11], case[12]) if len(case) > 11 else (0.0, 0)
+    say(f"select L={L} P={P} V={V} block={blk} k={k} n_unmask={nu} p={p} sigma={sigma} mode={mode} thr={thr} cdec={cdec}")
     wd = W.ModelDims(1, 64, 4, 4, 16, 80, V, dtype="f32")
     mdl = W.model_weights(W.ModelDims(1, 64, 4, 4, 16, 80, 8, dtype="f32"), 0)
     mdl["tok_emb"] = mdl["lm_head"] = np.zeros((V, 64), np.float32)      # the selection never touches them
@@ -279,7 +284,7 @@ def test_select_parity(B, L, P, V, blk, k, nu, p, sigma, frac, mode, skew):
     logits = W.logits_rows(seed, len(logit_pos), V) if len(logit_pos) else np.zeros((0, V), np.float32)
     if len(logit_pos) > 1:
         logits[1, 5] = logits[1, 2] = logits[1].max() + 1.0               # tied maxima: lowest index wins
-    prm = B.make_params(sigma, k, p, blk, nu, mode)
+    prm = B.make_params(sigma, k, p, blk, nu, mode, thr, cdec)
     res, cnt = _run_select(B, ctx, prm, logits, logit_pos, y, is_masked, P, conf0, pred0, c)
 
     # Eq. 1
@@ -290,7 +295,7 @@ def test_select_parity(B, L, P, V, blk, k, nu, p, sigma, frac, mode, skew):
     np.testing.assert_array_equal(res["pred"], pred_ref)
     np.testing.assert_allclose(res["conf"], conf_ref, rtol=1e-5)
     # Eq. 3: scores within tolerance
-    oprm = O.Params(sigma=sigma, k=k, p=p, block_len=blk, n_unmask=nu, cand_mode=mode)
+    oprm = O.Params(sigma=sigma, k=k, p=p, block_len=blk, n_unmask=nu, cand_mode=mode, threshold=thr, conf_decode=cdec)
     sel = O.select(oprm, is_masked, P, conf_ref.astype(np.float32), c)
     lo, hi = sel["block"]
     cand1 = np.array([i for i in range(lo, hi) if is_masked[i]], np.int64)
@@ -299,15 +304,19 @@ def test_select_parity(B, L, P, V, blk, k, nu, p, sigma, frac, mode, skew):
         np.testing.assert_allclose(res["score"][cand1], sel["score"][cand1], rtol=1e-5)
     # Eq. 4 and the decode set: integer-exact on the score array the GPU itself produced
     np.testing.assert_array_equal(res["mstar"], O.top_k_select(res["score"], cand1, k))
-    np.testing.assert_array_equal(res["decode_idx"], O.top_k_select(res["score"], cand1, nu))
+    dec_ref = O.top_k_select(res["conf"] if cdec else res["score"], cand1, nu)      # on the GPU's own float arrays
+    if thr > 0:
+        dec_ref = np.union1d(dec_ref, cand1[res["conf"][cand1] > np.float32(thr)]).astype(np.int32)
+    np.testing.assert_array_equal(res["decode_idx"], dec_ref)
     if topk_margin(sel["score"], cand1, k) > 1e-4:
         np.testing.assert_array_equal(res["mstar"], sel["mstar"])
-    if topk_margin(sel["score"], cand1, nu) > 1e-4:
+    conf_margin = np.min(np.abs(conf_ref[cand1] - thr) / max(thr, 1e-9)) if thr > 0 and len(cand1) else 1.0
+    if topk_margin(conf_ref if cdec else sel["score"], cand1, nu) > 1e-4 and conf_margin > 1e-4:
         np.testing.assert_array_equal(res["decode_idx"], sel["decode"])
     # stage 2 is decided on the given float32 influence array: bit-exact always
     cand2 = np.flatnonzero(~is_masked) if mode == 0 else np.setdiff1d(np.arange(L), res["mstar"])
     np.testing.assert_array_equal(res["u_set"], O.top_p_select(c, cand2, p))
-    np.testing.assert_array_equal(res["s_next"], np.union1d(res["mstar"], res["u_set"]))
+    np.testing.assert_array_equal(res["s_next"], np.union1d(np.union1d(res["mstar"], res["decode_idx"]), res["u_set"]))
     # Eq. 2
     y_ref, m_ref = y.copy(), is_masked.copy()
     y_ref[res["decode_idx"]] = pred_ref[res["decode_idx"]]
@@ -338,7 +347,8 @@ def test_select_large_equal_scores_and_errors(B):
     assert list(res["mstar"]) == [P, P + 1, P + 2, P + 3, P + 4]
     assert list(res["decode_idx"]) == [P, P + 1]
     assert list(res["u_set"]) == list(range(int(0.25 * P) + 1))
-    for bad in (dict(sigma=0.0), dict(k=-1), dict(block_len=0), dict(p=-0.5), dict(cand_mode=2)):
+    for bad in (dict(sigma=0.0), dict(k=-1), dict(block_len=0), dict(p=-0.5), dict(cand_mode=2), dict(threshold=-1.0),
+                dict(conf_decode=3), dict(rollout_layers=-2)):
         kw = dict(sigma=10.0, k=4, p=0.1, block_len=32, n_unmask=1, cand_mode=0)
         kw.update(bad)
         with pytest.raises(B.D2CError) as ei:

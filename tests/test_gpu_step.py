@@ -23,7 +23,8 @@ def B():
 
 
 def _gpu_params(B, prm: O.Params):
-    return B.make_params(prm.sigma, prm.k, prm.p, prm.block_len, prm.n_unmask, prm.cand_mode)
+    return B.make_params(prm.sigma, prm.k, prm.p, prm.block_len, prm.n_unmask, prm.cand_mode, prm.threshold,
+                         prm.conf_decode, prm.rollout_layers)
 
 
 def _sets(B, seq):
@@ -93,15 +94,18 @@ def _teacher_forced(B, dims, mdl, su, prm, n_steps, seed=0, check_free_run=True)
             np.testing.assert_allclose(score_g[cand1], tr["score"][cand1], rtol=max(tol, 1e-5) * 5)
         # --- index sets, integer-exact on the GPU's own float arrays
         np.testing.assert_array_equal(g["mstar"], O.top_k_select(score_g, cand1, prm.k))
-        np.testing.assert_array_equal(g["decode"], O.top_k_select(score_g, cand1, prm.n_unmask))
+        dec_ref = O.top_k_select(conf_g if prm.conf_decode else score_g, cand1, prm.n_unmask)
+        if prm.threshold > 0:
+            dec_ref = np.union1d(dec_ref, cand1[conf_g[cand1] > np.float32(prm.threshold)]).astype(np.int32)
+        np.testing.assert_array_equal(g["decode"], dec_ref)
         cand2 = np.flatnonzero(~masked_before)
         np.testing.assert_array_equal(g["u"], O.top_p_select(infl, cand2, prm.p))
-        np.testing.assert_array_equal(g["s_next"], np.union1d(g["mstar"], g["u"]))
+        np.testing.assert_array_equal(g["s_next"], np.union1d(np.union1d(g["mstar"], g["decode"]), g["u"]))
         # --- the same sets against the oracle's, while its margins are wide
         if free_running:
             safe = (topk_margin(tr["score"], cand1, prm.k) > 50 * tol and
                     topk_margin(tr["score"], cand1, prm.n_unmask) > 50 * tol and
-                    topp_margin(tr["c"], cand2, prm.p) > 50 * tol)
+                    topp_margin(tr["c"], cand2, prm.p) > 50 * tol and prm.threshold == 0 and not prm.conf_decode)
             if safe:
                 np.testing.assert_array_equal(g["mstar"], tr["mstar"])
                 np.testing.assert_array_equal(g["decode"], tr["decode"])
@@ -248,3 +252,18 @@ def test_step_llada_shape_reduced_depth(B):
     wd, su = W.with_layers(W.DIMS["C3"], 2), W.SETUP["C3"]
     mdl = W.model_weights(wd, 0)
     _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=3)
+
+
+def test_step_parallel_decoding_and_short_rollout(B):
+    """Parallel decoding by confidence threshold (1 to 7 tokens per step here), confidence-only decoding
+    and a rollout over the first layer only, on the small fp32 model with wider weights (so that the
+    confidences of the masked positions spread around the threshold)."""
+    wd, su = W.DIMS["C1"], W.DecodeSetup(32, 48, 16, 1, k=8, p=0.5)
+    mdl = W.model_weights(wd, 1)
+    for name in ("tok_emb", "lm_head"):
+        mdl[name] = mdl[name] * np.float32(16.0)
+    for lw in mdl["layers"]:
+        for name in ("wqkv", "wo", "w_gate_up", "w_down"):
+            lw[name] = lw[name] * np.float32(4.0)
+    prm = oracle_params(su, threshold=0.5, conf_decode=1, rollout_layers=1)
+    _teacher_forced(B, wd, mdl, su, prm, n_steps=su.gen_len)
