@@ -315,7 +315,8 @@ int d2c_set_tunable(const char* name, int32_t value) {
   if (!strcmp(name, "gemm_target_wgs")) t.gemm_target_wgs = value;
   else if (!strcmp(name, "gemm_max_splits")) t.gemm_max_splits = std::max(1, std::min(8, (int)value));
   else if (!strcmp(name, "gemm_nt_big_n")) t.gemm_nt_big_n = value;
-  else if (!strcmp(name, "gemm_ring")) t.gemm_ring = value == 2 ? 2 : 4;
+  else if (!strcmp(name, "gemm_waves")) t.gemm_waves = value == 16 ? 16 : value == 8 ? 8 : value == 4 ? 4 : 0;
+  else if (!strcmp(name, "gemm_rot")) t.gemm_rot = value < 0 ? 0 : value;
   else if (!strcmp(name, "side_stream")) t.side_stream = value != 0;
   else return D2C_EINVAL;
   return D2C_OK;

@@ -12,10 +12,14 @@
 //     through LDS in 256-byte-per-row chunks, double-buffered, one barrier per chunk;
 //     a chunk is requested two iterations before it is needed in LDS, so its
 //     latency never sits between two barriers;
-//   * the contraction axis can be split over blockIdx.y; every split writes its
-//     own fp32 partial and the consumer kernel sums the partials in a fixed order
+//   * the contraction axis can be split over several workgroups; every split writes
+//     its own fp32 partial and the consumer kernel sums the partials in a fixed order
 //     (deterministic, no atomics);
-//   * more than 128 rows are covered by blockIdx.z (step 0 and select-all mode).
+//   * more than 128 rows (step 0, select-all mode) are covered by several row chunks.
+//     The grid is one-dimensional and workgroup ids are dealt round-robin to the 8
+//     XCDs, each with its own L2: the mapping below gives the row chunks of one weight
+//     tile consecutive slots of the SAME XCD, so the tile comes from HBM once and the
+//     other chunks hit it in L2.
 #include "common.cuh"
 #include "internal.h"
 
@@ -28,18 +32,24 @@ Tunables& tunables() {
 
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = 4;
 constexpr int kChunkBytes = 256;                 // bytes of one row in one chunk
 constexpr int kRowStride = kChunkBytes + 16;     // LDS row pitch: 16-byte skew, conflict-free 16-byte reads
 constexpr int kSteps = 4;                        // matrix-core steps per chunk
 
 // RING = number of weight chunks a wave keeps in registers (one being consumed, RING-1 in flight).
-template <typename T, int MT, int NT, int RING>
-__global__ __launch_bounds__(kThreads) void gemm_rows_kernel(
+template <typename T, int MT, int NT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemm_rows_kernel(
     const T* __restrict__ A, int lda, const T* __restrict__ W, int ldw, float* __restrict__ P, int ldp,
-    size_t split_stride, int m, int N, int K, int k_per_split) {
-  static_assert(RING == 2 || RING == 4, "the ring index and the A register parity must stay compile-time");
+    size_t split_stride, int m, int N, int K, int k_per_split, int n_blocks, int n_splits, int row_chunks, int rot_mul) {
+  constexpr int RING = 2;
+  constexpr int kThreads = WAVES * 64;
+  constexpr int kAFrags = MT * 256;                              // 16-byte fragments of one activation chunk
+  constexpr int AI = (kAFrags + kThreads - 1) / kThreads;        // of which one thread moves this many
+  // workgroup id -> (weight tile, row chunk): id % 8 is the XCD, within an XCD the row chunk varies fastest
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int tile = (slot / row_chunks) * 8 + xcd;
+  if (tile >= n_blocks * n_splits) return;       // padding of the last group of 8 (whole workgroup leaves)
+  const int bz = slot % row_chunks, by = tile / n_blocks, bx = tile - by * n_blocks;
   constexpr int E = Frag<T>::kElems;
   constexpr int KS = Frag<T>::kStep;
   constexpr int KC = kSteps * KS;                // elements per chunk (= 256 bytes)
@@ -49,10 +59,10 @@ __global__ __launch_bounds__(kThreads) void gemm_rows_kernel(
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int r = lane & 15, g = lane >> 4;
-  const int row0 = blockIdx.z * (MT * 16);
-  const int k_begin = blockIdx.y * k_per_split;
+  const int row0 = bz * (MT * 16);
+  const int k_begin = by * k_per_split;
   const int k_end = min(K, k_begin + k_per_split);
-  const int n_base = (blockIdx.x * kWaves + wave) * (16 * NT);
+  const int n_base = (bx * WAVES + wave) * (16 * NT);
   const int n_chunks = (k_end - k_begin + KC - 1) / KC;
 
   // this lane's weight rows (clamped: out-of-range columns are computed on a valid row and dropped)
@@ -63,7 +73,7 @@ __global__ __launch_bounds__(kThreads) void gemm_rows_kernel(
     wrow[nt] = W + (size_t)n * ldw;
   }
 
-  Frag<T> areg[2][MT];                 // areg[c & 1]: activation chunk c on its way from global memory to LDS
+  Frag<T> areg[2][AI];                 // areg[c & 1]: activation chunk c on its way from global memory to LDS
   Frag<T> breg[RING][NT][kSteps];      // breg[c % RING]: weight chunk c
   f32x4 acc[MT][NT];
 #pragma unroll
@@ -71,75 +81,93 @@ __global__ __launch_bounds__(kThreads) void gemm_rows_kernel(
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  auto load_a = [&](Frag<T> (&a)[MT], int chunk) {
-    const int kc = k_begin + chunk * KC;
+  // The loop below has no conditional loads or stores.  A load under a branch makes the compiler wait
+  // for ALL outstanding loads before the next use, which would drain the prefetch ring every iteration;
+  // so addresses are clamped instead: rows >= m read row m-1 (their accumulators are never stored),
+  // chunks past the end re-read the last chunk (an L2 hit, never used), and the weight fragments of the
+  // last chunk's tail are masked to zero where they are consumed.
+  const int last_row = m - 1;
+  const int last_chunk = n_chunks - 1;
+  // Workgroups walk their k-range from different starting chunks (a rotation by a multiple of the
+  // column-block index), so that at one moment they do not all ask for the same offsets within a row.
+  const int rot = n_chunks > 0 ? (int)(((unsigned)bx * (unsigned)rot_mul) % (unsigned)n_chunks) : 0;
+  auto chunk_k = [&](int chunk) {
+    int p = min(chunk, last_chunk) + rot;
+    if (p >= n_chunks) p -= n_chunks;
+    return k_begin + p * KC;
+  };
+  auto load_a = [&](Frag<T> (&a)[AI], int chunk) {
+    const int kc = chunk_k(chunk);
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
-      const int f = tid + i * kThreads;          // fragment id in the chunk: row f/16, 16-byte column f%16
-      const int row = row0 + (f >> 4);
-      const int k = kc + (f & 15) * E;
-      if (row < m && k < k_end) a[i].raw = ld16(A + (size_t)row * lda + k);
-      else a[i].raw = u32x4{0u, 0u, 0u, 0u};
+    for (int i = 0; i < AI; ++i) {
+      // fragment id in the chunk: row f/16, 16-byte column f%16; ids past the end repeat the last one
+      const int f = min(tid + i * kThreads, kAFrags - 1);
+      const int row = min(row0 + (f >> 4), last_row);
+      const int k = min(kc + (f & 15) * E, k_end - E);
+      a[i].raw = ld16(A + (size_t)row * lda + k);
     }
   };
-  auto store_a = [&](const Frag<T> (&a)[MT], int buf) {
+  auto store_a = [&](const Frag<T> (&a)[AI], int buf) {
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
-      const int f = tid + i * kThreads;
+    for (int i = 0; i < AI; ++i) {
+      const int f = min(tid + i * kThreads, kAFrags - 1);
       *reinterpret_cast<u32x4*>(&lds[buf][(f >> 4) * kRowStride + (f & 15) * 16]) = a[i].raw;
     }
   };
   auto load_b = [&](Frag<T> (&b)[NT][kSteps], int chunk) {
-    const int kc = k_begin + chunk * KC;
+    const int kc = chunk_k(chunk);
 #pragma unroll
     for (int s = 0; s < kSteps; ++s) {
-      const int k = kc + s * KS + g * E;
+      const int k = min(kc + s * KS + g * E, k_end - E);
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        if (k < k_end) b[nt][s].raw = ld16(wrow[nt] + k);
-        else b[nt][s].raw = u32x4{0u, 0u, 0u, 0u};
-      }
+      for (int nt = 0; nt < NT; ++nt) b[nt][s].raw = ld16(wrow[nt] + k);
     }
   };
 
   // prologue: weight chunks 0..PB-1 and activation chunks 0, 1 are requested; chunk 0 reaches LDS
+  if (n_chunks <= 0) return;
 #pragma unroll
-  for (int u = 0; u < PB; ++u)
-    if (u < n_chunks) load_b(breg[u], u);
-  if (n_chunks > 0) {
-    load_a(areg[0], 0);
-    if (n_chunks > 1) load_a(areg[1], 1);
-    store_a(areg[0], 0);
-  }
+  for (int u = 0; u < PB; ++u) load_b(breg[u], u);
+  load_a(areg[0], 0);
+  load_a(areg[1], 1);
+  store_a(areg[0], 0);
   __syncthreads();
 
   for (int base = 0; base < n_chunks; base += RING) {
 #pragma unroll
     for (int u = 0; u < RING; ++u) {
+      // no early exit: iterations past the last chunk (at most RING-1) re-read it and contribute zero,
+      // which keeps the RING iterations one basic block that the scheduler can interleave freely
       const int c = base + u;
-      if (c >= n_chunks) break;
       // requests first: activation chunk c+2 (its registers were emptied into LDS one iteration ago)
       // and weight chunk c+PB
-      if (c + 2 < n_chunks) load_a(areg[u & 1], c + 2);
-      if (c + PB < n_chunks) load_b(breg[(u + PB) % RING], c + PB);
+      load_a(areg[u & 1], c + 2);
+      load_b(breg[(u + PB) % RING], c + PB);
+      __builtin_amdgcn_sched_barrier(0);   // the requests stay ahead of this iteration's arithmetic
       const unsigned char* abuf = lds[u & 1];
+      const int kc = chunk_k(c);
 #pragma unroll
       for (int s = 0; s < kSteps; ++s) {
+        const unsigned keep = (c < n_chunks && kc + s * KS + g * E < k_end) ? 0xffffffffu : 0u;   // zero in the tail of the last chunk and past it
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
           Frag<T> af;
           af.raw = *reinterpret_cast<const u32x4*>(&abuf[(mt * 16 + r) * kRowStride + (s * 4 + g) * 16]);
 #pragma unroll
-          for (int nt = 0; nt < NT; ++nt) mfma16(acc[mt][nt], af, breg[u][nt][s]);
+          for (int nt = 0; nt < NT; ++nt) {
+            Frag<T> bf;
+            bf.raw = breg[u][nt][s].raw & u32x4{keep, keep, keep, keep};
+            mfma16(acc[mt][nt], af, bf);
+          }
         }
       }
       // activation chunk c+1 was requested one iteration ago: its latency is behind us
-      if (c + 1 < n_chunks) store_a(areg[(u + 1) & 1], (u + 1) & 1);
+      store_a(areg[(u + 1) & 1], (u + 1) & 1);
       __syncthreads();
     }
   }
 
-  float* out = P + (size_t)blockIdx.y * split_stride;
+  float* out = P + (size_t)by * split_stride;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -154,27 +182,37 @@ __global__ __launch_bounds__(kThreads) void gemm_rows_kernel(
     }
 }
 
-template <typename T, int MT, int NT, int RING>
+template <typename T, int MT, int NT, int WAVES>
 hipError_t launch_t(const GemmPlan& pl, const void* A, int lda, const void* W, int ldw, float* P, int ldp,
                     size_t split_stride, int m, int N, int K, hipStream_t st) {
-  dim3 grid((N + 64 * NT - 1) / (64 * NT), pl.splits, pl.row_chunks);
-  hipLaunchKernelGGL((gemm_rows_kernel<T, MT, NT, RING>), grid, dim3(kThreads), 0, st, (const T*)A, lda, (const T*)W,
-                     ldw, P, ldp, split_stride, m, N, K, pl.k_per_split);
+  const int cols = 16 * NT * WAVES;
+  const int n_blocks = (N + cols - 1) / cols;
+  const int groups = (n_blocks * pl.splits + 7) / 8;            // weight tiles are dealt to the XCDs in groups of 8
+  dim3 grid(groups * 8 * pl.row_chunks);
+  hipLaunchKernelGGL((gemm_rows_kernel<T, MT, NT, WAVES>), grid, dim3(WAVES * 64), 0, st, (const T*)A, lda,
+                     (const T*)W, ldw, P, ldp, split_stride, m, N, K, pl.k_per_split, n_blocks, pl.splits,
+                     pl.row_chunks, pl.rot);
   return hipGetLastError();
 }
 
-template <typename T, int NT, int RING>
+template <typename T, int NT, int WAVES>
 hipError_t launch_mt(const GemmPlan& pl, const void* A, int lda, const void* W, int ldw, float* P, int ldp,
                      size_t ss, int m, int N, int K, hipStream_t st) {
   switch (pl.mt) {
-    case 1: return launch_t<T, 1, NT, RING>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 2: return launch_t<T, 2, NT, RING>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 3: return launch_t<T, 3, NT, RING>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 4: return launch_t<T, 4, NT, RING>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 5: return launch_t<T, 5, NT, RING>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 6: return launch_t<T, 6, NT, RING>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 7: return launch_t<T, 7, NT, RING>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 8: return launch_t<T, 8, NT, RING>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    case 1: return launch_t<T, 1, NT, WAVES>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    case 2: return launch_t<T, 2, NT, WAVES>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    case 3: return launch_t<T, 3, NT, WAVES>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    case 4: return launch_t<T, 4, NT, WAVES>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    default: break;
+  }
+  if constexpr (WAVES <= 8) {      // 16 waves leave 128 registers per lane: not enough for more row tiles
+    switch (pl.mt) {
+      case 5: return launch_t<T, 5, NT, WAVES>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+      case 6: return launch_t<T, 6, NT, WAVES>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+      case 7: return launch_t<T, 7, NT, WAVES>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+      case 8: return launch_t<T, 8, NT, WAVES>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+      default: break;
+    }
   }
   return hipErrorInvalidValue;
 }
@@ -183,11 +221,13 @@ template <typename T>
 hipError_t launch_nt(const GemmPlan& pl, const void* A, int lda, const void* W, int ldw, float* P, int ldp,
                      size_t ss, int m, int N, int K, hipStream_t st) {
   if (pl.nt == 1) {
-    if (pl.ring == 4) return launch_mt<T, 1, 4>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    return launch_mt<T, 1, 2>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    if (pl.waves == 16) return launch_mt<T, 1, 16>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    if (pl.waves == 8) return launch_mt<T, 1, 8>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    return launch_mt<T, 1, 4>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
   }
-  if (pl.ring == 4) return launch_mt<T, 2, 4>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-  return launch_mt<T, 2, 2>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+  if (pl.waves == 16) return launch_mt<T, 2, 16>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+  if (pl.waves == 8) return launch_mt<T, 2, 8>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+  return launch_mt<T, 2, 4>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
 }
 
 }  // namespace
@@ -199,12 +239,15 @@ GemmPlan plan_gemm(int dtype, int m, int N, int K, bool single_split) {
   pl.mt = tiles <= 8 ? (tiles < 1 ? 1 : tiles) : 8;
   pl.row_chunks = tiles <= 8 ? 1 : (tiles + 7) / 8;
   pl.nt = N > t.gemm_nt_big_n ? 2 : 1;
-  pl.ring = t.gemm_ring == 4 ? 4 : 2;
+  pl.rot = t.gemm_rot;
+  // narrow outputs with a deep k split gain from 8 waves sharing one activation chunk; wide ones from more workgroups
+  pl.waves = t.gemm_waves == 16 ? 16 : t.gemm_waves == 8 ? 8 : t.gemm_waves == 4 ? 4 : (N <= 8192 ? 8 : 4);
+  if (pl.waves == 16 && pl.mt > 4) pl.waves = 8;
   const int kc = dtype == kBF16 ? 128 : 64;                       // elements per 256-byte chunk
-  const int n_blocks = (N + 64 * pl.nt - 1) / (64 * pl.nt);
+  const int n_blocks = (N + 16 * pl.nt * pl.waves - 1) / (16 * pl.nt * pl.waves);
   const int chunks = (K + kc - 1) / kc;
   int splits = 1;
-  while (!single_split && splits < t.gemm_max_splits && n_blocks * pl.row_chunks * splits < t.gemm_target_wgs &&
+  while (!single_split && splits < t.gemm_max_splits && n_blocks * (pl.waves / 4) * pl.row_chunks * splits < t.gemm_target_wgs &&
          chunks / (splits * 2) >= 2)
     splits *= 2;
   const int chunks_per_split = (chunks + splits - 1) / splits;

@@ -12,10 +12,11 @@ inline size_t dtype_size(int dt) { return dt == kBF16 ? 2 : 4; }
 
 // Tunables (defaults chosen by measurement; d2c_set_tunable changes them).
 struct Tunables {
-  int gemm_target_wgs = 512;   // aim for at least this many workgroups per GEMM
+  int gemm_target_wgs = 512;   // aim for at least this many groups of 4 waves per GEMM
   int gemm_max_splits = 8;
   int gemm_nt_big_n = 16384;   // N above this uses two column tiles per wave
-  int gemm_ring = 2;           // weight chunks per wave in registers (2 or 4)
+  int gemm_waves = 0;          // waves per workgroup sharing one activation chunk in LDS: 4, 8, 16; 0 = by shape
+  int gemm_rot = 0;            // start chunk of a workgroup's k walk = (column block * this) % chunks
   bool side_stream = true;     // d2c_step: head average + rollout on a second stream
 };
 Tunables& tunables();
@@ -24,10 +25,11 @@ Tunables& tunables();
 struct GemmPlan {
   int mt;        // 16-row tiles per workgroup (1..8)
   int nt;        // 16-column tiles per wave (1 or 2)
-  int ring;      // weight chunks a wave holds in registers (2 or 4)
+  int waves;     // waves per workgroup (4, 8 or 16), each owning 16*nt output columns
   int splits;    // k splits (partials to be summed by the consumer)
   int k_per_split;
   int row_chunks;
+  int rot;       // multiplier of the per-workgroup start-chunk rotation (0 = none)
 };
 GemmPlan plan_gemm(int dtype, int m, int N, int K, bool single_split = false);
 // P must hold plan.splits * split_stride floats; split_stride >= m * ldp.
