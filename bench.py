@@ -20,6 +20,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0        # dense bf16 matrix-core peak of the chip
 
 
 def device_model(W, dims, seed, torch):
@@ -91,12 +92,64 @@ def cpu_baseline(W, dims, su, m_rows, n_logit_rows):
                        % (dims.n_layers, m_rows, t_layer, t_roll, dims.n_layers, n_logit_rows, t_head, L, t_sel))}
 
 
+def bench_attention_op(args, B, W, torch, np):
+    """The isolated selective-refresh attention op: scatter of m new K/V rows, then m queries against all
+    L cached keys, no mask, with and without the head-averaged probabilities.  One "step" = one call."""
+    H, Hkv, dh, L, m = 32, 32, 128, 2048, 256
+    wd = W.with_layers(W.ModelDims(1, H * dh, H, Hkv, dh, 64, 64, dtype="bf16"), 1)
+    ctx = B.Context(wd, W.model_weights(wd, 0), L)
+    case = W.attention_case(1, H, Hkv, dh, L, m, dtype="bf16")
+    q = B.to_device(case["q"], "bf16")
+    kc, vc = B.to_device(case["k_cache"], "bf16"), B.to_device(case["v_cache"], "bf16")
+    nk, nv = B.to_device(case["new_k"], "bf16"), B.to_device(case["new_v"], "bf16")
+    idx = torch.from_numpy(case["idx"]).cuda()
+    out = torch.zeros((m, H * dh), dtype=torch.bfloat16, device="cuda")
+    abar = torch.zeros((m, L), dtype=torch.float32, device="cuda")
+    K, Wm = args.steps, args.warmup
+    flops = 4.0 * H * m * L * dh
+    # K, V once; Q, O; scatter reads and writes 2 m d_kv; A-bar write when asked for
+    base_bytes = 2 * (2 * L * Hkv * dh) + 2 * (2 * m * H * dh) + 2 * 2 * (2 * m * Hkv * dh)
+    res = {}
+    for name, ab in (("with_head_average", abar), ("output_only", None)):
+        for _ in range(Wm):
+            ctx.d2c_attention(q, idx, m, nk, nv, kc, vc, L, out, ab)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(K):
+            ctx.d2c_attention(q, idx, m, nk, nv, kc, vc, L, out, ab)
+        e1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        us = 1e3 * e0.elapsed_time(e1) / K
+        by = base_bytes + (4 * m * L if ab is not None else 0)
+        # the head average recomputes Q K^T in a second pass: those flops are overhead, not counted
+        res[name] = {"us_per_call": round(us, 2), "wall_us_per_call": round(1e6 * wall / K, 2),
+                     "tflops": round(flops / us / 1e6, 1), "mfma_frac": round(flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "gbs": round(by / us / 1e3, 1), "hbm_frac": round(by / us / 1e3 / HBM_PEAK_GBS, 4)}
+    ctx.close()
+    main_r = res["with_head_average"]
+    return {
+        "metric": "selective_attention_calls_per_sec", "value": round(1e6 / main_r["us_per_call"], 1), "unit": "calls/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(main_r["us_per_call"] / 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "C2: isolated selective-refresh attention, 32 heads x 128, L 2048, m 256 query rows, "
+                               "scatter of 256 new K/V rows, no mask"},
+        "roofline": {"bound": "mfma", "achieved": main_r["tflops"], "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": main_r["mfma_frac"], "traffic": None, "flops_per_call": flops,
+                     "hbm_frac": main_r["hbm_frac"], "bytes_per_call": base_bytes + 4 * m * L},
+        "variants": res, "cpu_baseline": None,
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=128)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="C3", choices=["C3", "C4"])
+    ap.add_argument("--workload", default="C3", choices=["C3", "C4", "C2"],
+                    help="C3 (default, the metric's workload), C4, or C2 = the isolated selective-refresh attention op")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (the result is then not the metric)")
     ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
                     help="library tunable (see d2c_set_tunable), e.g. --tune gemm_target_wgs=768")
@@ -128,6 +181,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes": 256 << 20, "copies": 5}))
+        return
+    if args.workload == "C2":
+        print(json.dumps(bench_attention_op(args, B, W, torch, np)))
         return
     dims, su = W.DIMS[args.workload], W.SETUP[args.workload]
     if args.layers:

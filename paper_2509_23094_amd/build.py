@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libd2c.so")
-SOURCES = ["gemm.hip", "rowwise.hip", "attention.hip", "select.hip", "api.hip"]
+SOURCES = ["gemm.hip", "rowwise.hip", "attention.hip", "attention_tiled.hip", "select.hip", "api.hip"]
 # packed FP32 instructions are switched off for every device compile
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

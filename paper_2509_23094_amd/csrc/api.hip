@@ -32,6 +32,9 @@ struct d2c_ctx {
   void* attn_o = nullptr;       // T [max_seq, d_q]
   void* act = nullptr;          // T [max_seq, F]
   float* lse = nullptr;         // [n_layers, H, max_seq]
+  float* attn_part = nullptr;   // partial outputs of an attention launch that splits the key range
+  size_t attn_part_floats = 0, avg_part_floats = 0;
+  float* avg_part = nullptr;    // per-head-group partials of the head average (used on the side stream)
   float* partial = nullptr;     // split partials of the current projection
   size_t partial_floats = 0;
   float* abar = nullptr;        // [max_seq, max_seq]
@@ -164,14 +167,15 @@ int layer_impl(d2c_ctx* c, int layer, float* hidden, const int32_t* idx, int m, 
                                     D.head_dim, c->rope_cos, c->rope_sin, q, k_cache, v_cache, st));
   D2C_TIMED(c, st, D2C_PROF_ATTENTION, 2.0 * L * dkv * tsize(c),
             launch_attention_fwd(dt, q, k_cache, v_cache, m, L, D.n_heads, D.n_kv_heads, D.head_dim, c->attn_o, lse,
-                                 st));
+                                 c->attn_part, c->attn_part_floats, st));
   if (abar) {
     if (side != st) {
       D2C_HIP(c, hipEventRecord(c->fwd_done[layer], st));
       D2C_HIP(c, hipStreamWaitEvent(side, c->fwd_done[layer], 0));
     }
     D2C_TIMED(c, side, D2C_PROF_ATTN_AVG, 0.0,
-              launch_attention_avg(dt, q, k_cache, lse, m, L, D.n_heads, D.n_kv_heads, D.head_dim, abar, side));
+              launch_attention_avg(dt, q, k_cache, lse, m, L, D.n_heads, D.n_kv_heads, D.head_dim, abar, c->avg_part,
+                                   c->avg_part_floats, side));
     if (roll_out)
       D2C_TIMED(c, side, D2C_PROF_ROLLOUT, 0.0, launch_rollout(abar, roll_in, roll_out, idx, m, L, layer == 0, side));
   }
@@ -262,10 +266,14 @@ int d2c_init(const d2c_dims* dims, const d2c_weights* w, d2c_ctx** out) {
     }
   c->partial_floats = pf;
   c->head_rows = (int)std::min<size_t>(Lm, 256);
+  c->attn_part_floats = attention_scratch_floats(D.dtype, D.max_seq, D.max_seq, D.n_heads, D.head_dim);
+  c->avg_part_floats = attention_avg_scratch_floats(D.dtype, D.max_seq, D.max_seq, D.n_heads);
   if ((rc = ws_alloc(c, &c->hidden, Lm * d * 4)) || (rc = ws_alloc(c, &c->a_norm, Lm * d * ts)) ||
       (rc = ws_alloc(c, &c->q, (size_t)D.n_layers * Lm * dq * ts)) || (rc = ws_alloc(c, &c->attn_o, Lm * dq * ts)) ||
       (rc = ws_alloc(c, &c->act, Lm * F * ts)) ||
       (rc = ws_alloc(c, &c->lse, (size_t)D.n_layers * D.n_heads * Lm * 4)) ||
+      (rc = ws_alloc(c, &c->attn_part, std::max<size_t>(1, c->attn_part_floats) * 4)) ||
+      (rc = ws_alloc(c, &c->avg_part, std::max<size_t>(1, c->avg_part_floats) * 4)) ||
       (rc = ws_alloc(c, &c->partial, pf * 4)) || (rc = ws_alloc(c, &c->abar, Lm * Lm * 4)) ||
       (rc = ws_alloc(c, &c->roll[0], Lm * Lm * 4)) || (rc = ws_alloc(c, &c->roll[1], Lm * Lm * 4)) ||
       (rc = ws_alloc(c, &c->head_a, (size_t)c->head_rows * d * ts)) ||
@@ -317,6 +325,10 @@ int d2c_set_tunable(const char* name, int32_t value) {
   else if (!strcmp(name, "gemm_nt_big_n")) t.gemm_nt_big_n = value;
   else if (!strcmp(name, "gemm_waves")) t.gemm_waves = value == 16 ? 16 : value == 8 ? 8 : value == 4 ? 4 : 0;
   else if (!strcmp(name, "gemm_rot")) t.gemm_rot = value < 0 ? 0 : value;
+  else if (!strcmp(name, "attn_tiled_min_m")) t.attn_tiled_min_m = value < 1 ? 1 : value;
+  else if (!strcmp(name, "attn_max_splits")) t.attn_max_splits = std::max(1, std::min(8, (int)value));
+  else if (!strcmp(name, "attn_qt")) t.attn_qt = value == 1 ? 1 : value == 2 ? 2 : 0;
+  else if (!strcmp(name, "attn_target_wgs")) t.attn_target_wgs = std::max(1, (int)value);
   else if (!strcmp(name, "side_stream")) t.side_stream = value != 0;
   else return D2C_EINVAL;
   return D2C_OK;
@@ -419,16 +431,15 @@ int d2c_attention(d2c_ctx* c, const void* q, const int32_t* idx, int32_t m, cons
   hipStream_t st = (hipStream_t)stream;
   const d2c_dims& D = c->dims;
   if (new_k) {
-    D2C_HIP(c, launch_scatter_rows(D.dtype, new_k, idx, m, d_kv(c), k_cache, st));
-    D2C_HIP(c, launch_scatter_rows(D.dtype, new_v, idx, m, d_kv(c), v_cache, st));
+    D2C_HIP(c, launch_scatter_rows(D.dtype, new_k, k_cache, new_v, v_cache, idx, m, d_kv(c), st));
   }
   D2C_TIMED(c, st, D2C_PROF_ATTENTION, 2.0 * L * d_kv(c) * tsize(c),
             launch_attention_fwd(D.dtype, q, k_cache, v_cache, m, L, D.n_heads, D.n_kv_heads, D.head_dim, out, c->lse,
-                                 st));
+                                 c->attn_part, c->attn_part_floats, st));
   if (attn_avg)
     D2C_TIMED(c, st, D2C_PROF_ATTN_AVG, 0.0,
               launch_attention_avg(D.dtype, q, k_cache, c->lse, m, L, D.n_heads, D.n_kv_heads, D.head_dim, attn_avg,
-                                   st));
+                                   c->avg_part, c->avg_part_floats, st));
   return D2C_OK;
 }
 

@@ -349,11 +349,19 @@ hipError_t launch_avg_bf16(const void* q, const void* k_cache, const float* lse,
 
 }  // namespace
 
+size_t attention_scratch_floats(int dtype, int max_m, int max_L, int n_heads, int head_dim) {
+  return dtype == kBF16 ? attention_tiled_scratch_floats(max_m, max_L, n_heads, head_dim) : 0;
+}
+
 hipError_t launch_attention_fwd(int dtype, const void* q, const void* k_cache, const void* v_cache, int m, int L,
-                                int n_heads, int n_kv_heads, int head_dim, void* out, float* lse, hipStream_t st) {
+                                int n_heads, int n_kv_heads, int head_dim, void* out, float* lse, float* scratch,
+                                size_t scratch_floats, hipStream_t st) {
   if (m <= 0) return hipSuccess;
   if (L <= 0 || n_heads % n_kv_heads) return hipErrorInvalidValue;
   if (dtype == kBF16) {
+    if (m >= tunables().attn_tiled_min_m)
+      return launch_attention_tiled_fwd(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, head_dim, out, lse, scratch,
+                                        scratch_floats, st);
     if (head_dim == 128) return launch_fwd_bf16<128>(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, st);
     if (head_dim == 64) return launch_fwd_bf16<64>(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, st);
     return hipErrorInvalidValue;
@@ -366,11 +374,19 @@ hipError_t launch_attention_fwd(int dtype, const void* q, const void* k_cache, c
   return hipGetLastError();
 }
 
+size_t attention_avg_scratch_floats(int dtype, int max_m, int max_L, int n_heads) {
+  return dtype == kBF16 ? attention_tiled_avg_scratch_floats(max_m, max_L, n_heads) : 0;
+}
+
 hipError_t launch_attention_avg(int dtype, const void* q, const void* k_cache, const float* lse, int m, int L,
-                                int n_heads, int n_kv_heads, int head_dim, float* attn_avg, hipStream_t st) {
+                                int n_heads, int n_kv_heads, int head_dim, float* attn_avg, float* scratch,
+                                size_t scratch_floats, hipStream_t st) {
   if (m <= 0) return hipSuccess;
   if (L <= 0 || n_heads % n_kv_heads) return hipErrorInvalidValue;
   if (dtype == kBF16) {
+    if (m >= tunables().attn_tiled_min_m)
+      return launch_attention_tiled_avg(q, k_cache, lse, m, L, n_heads, n_kv_heads, head_dim, attn_avg, scratch,
+                                        scratch_floats, st);
     if (head_dim == 128) return launch_avg_bf16<128>(q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, st);
     if (head_dim == 64) return launch_avg_bf16<64>(q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, st);
     return hipErrorInvalidValue;

@@ -17,6 +17,10 @@ struct Tunables {
   int gemm_nt_big_n = 16384;   // N above this uses two column tiles per wave
   int gemm_waves = 0;          // waves per workgroup sharing one activation chunk in LDS: 4, 8, 16; 0 = by shape
   int gemm_rot = 0;            // start chunk of a workgroup's k walk = (column block * this) % chunks
+  int attn_tiled_min_m = 64;   // bf16 attention: from this many query rows on, the LDS-tiled kernels
+  int attn_max_splits = 8;     // key-range splits of one attention launch (1..8)
+  int attn_qt = 0;             // 16-row query tiles per wave in the tiled forward kernel: 1, 2; 0 = by m
+  int attn_target_wgs = 256;   // split the key range until the forward grid has this many workgroups
   bool side_stream = true;     // d2c_step: head average + rollout on a second stream
 };
 Tunables& tunables();
@@ -55,9 +59,10 @@ hipError_t launch_qkv_rope_scatter(int dtype, const float* P, int n_splits, size
 // act[r,f] = T(silu(g) * u), g/u = split sums of columns f and F+f
 hipError_t launch_swiglu(int dtype, const float* P, int n_splits, size_t split_stride, int ldp, int m, int F,
                          void* act, hipStream_t st);
-// cache[idx[r],:] = rows[r,:]
-hipError_t launch_scatter_rows(int dtype, const void* rows, const int32_t* idx, int m, int width, void* cache,
-                               hipStream_t st);
+// cache_a[idx[r],:] = rows_a[r,:] and, when rows_b is given, cache_b[idx[r],:] = rows_b[r,:].
+// Pointers and width*sizeof(T) must be multiples of 16 bytes for the wide path (else element copies).
+hipError_t launch_scatter_rows(int dtype, const void* rows_a, void* cache_a, const void* rows_b, void* cache_b,
+                               const int32_t* idx, int m, int width, hipStream_t st);
 hipError_t launch_copy_f32(float* dst, const float* src, size_t n, hipStream_t st);
 // dst[i] = sum_s P[s*split_stride + i], i < n
 hipError_t launch_sum_splits(float* dst, const float* P, int n_splits, size_t split_stride, size_t n, hipStream_t st);
@@ -66,11 +71,27 @@ hipError_t launch_rope_table(float* cos_t, float* sin_t, int max_pos, int head_d
 
 // ---- attention of m query rows against all L cached keys, no mask, in two launches
 // fwd: out T [m, H*dh] and the log-sum-exp per (head, row), lse float [H, m]
+// scratch: attention_scratch_floats(...) floats (partials of a split key range), may be null for fp32
+size_t attention_scratch_floats(int dtype, int max_m, int max_L, int n_heads, int head_dim);
 hipError_t launch_attention_fwd(int dtype, const void* q, const void* k_cache, const void* v_cache, int m, int L,
-                                int n_heads, int n_kv_heads, int head_dim, void* out, float* lse, hipStream_t st);
+                                int n_heads, int n_kv_heads, int head_dim, void* out, float* lse, float* scratch,
+                                size_t scratch_floats, hipStream_t st);
 // avg: attn_avg float [m, L] = mean over heads of exp(q k / sqrt(dh) - lse); needs fwd's lse
+// scratch: attention_avg_scratch_floats(...) floats (per-head-group partials), may be null for fp32
+size_t attention_avg_scratch_floats(int dtype, int max_m, int max_L, int n_heads);
 hipError_t launch_attention_avg(int dtype, const void* q, const void* k_cache, const float* lse, int m, int L,
-                                int n_heads, int n_kv_heads, int head_dim, float* attn_avg, hipStream_t st);
+                                int n_heads, int n_kv_heads, int head_dim, float* attn_avg, float* scratch,
+                                size_t scratch_floats, hipStream_t st);
+
+// the bf16 kernels for many query rows (K/V blocks staged through LDS, optional key split + merge)
+size_t attention_tiled_scratch_floats(int max_m, int L, int n_heads, int head_dim);
+hipError_t launch_attention_tiled_fwd(const void* q, const void* k_cache, const void* v_cache, int m, int L,
+                                      int n_heads, int n_kv_heads, int head_dim, void* out, float* lse,
+                                      float* scratch, size_t scratch_floats, hipStream_t st);
+size_t attention_tiled_avg_scratch_floats(int max_m, int L, int n_heads);
+hipError_t launch_attention_tiled_avg(const void* q, const void* k_cache, const float* lse, int m, int L,
+                                      int n_heads, int n_kv_heads, int head_dim, float* attn_avg, float* scratch,
+                                      size_t scratch_floats, hipStream_t st);
 
 // ---- rollout on the compact block: c_out = (A[:,S] c_in + A[:,notS] + c_in) / 2; first: c_in = one-hot rows
 hipError_t launch_rollout(const float* attn_avg, const float* c_in, float* c_out, const int32_t* idx, int m, int L,

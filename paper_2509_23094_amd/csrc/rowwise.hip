@@ -230,14 +230,22 @@ __global__ __launch_bounds__(kThreads) void swiglu_kernel(const float* __restric
   act[(size_t)r * F + f] = from_f32<T>(g / (1.0f + expf(-g)) * u);
 }
 
+// blockIdx.y picks one of two (rows, cache) pairs that share idx and width: new K rows and new V rows go
+// out in one launch
 template <typename T>
-__global__ __launch_bounds__(kThreads) void scatter_rows_kernel(const T* __restrict__ rows,
-                                                                const int32_t* __restrict__ idx, int width,
-                                                                T* __restrict__ cache) {
+__global__ __launch_bounds__(kThreads) void scatter_rows_kernel(const T* __restrict__ rows_a, T* __restrict__ cache_a,
+                                                                const T* __restrict__ rows_b, T* __restrict__ cache_b,
+                                                                const int32_t* __restrict__ idx, int width, int wide) {
   const int r = blockIdx.x;
-  const T* src = rows + (size_t)r * width;
-  T* dst = cache + (size_t)idx[r] * width;
-  for (int c = threadIdx.x; c < width; c += kThreads) dst[c] = src[c];
+  const T* src = (blockIdx.y ? rows_b : rows_a) + (size_t)r * width;
+  T* dst = (blockIdx.y ? cache_b : cache_a) + (size_t)idx[r] * width;
+  if (wide) {                              // rows are whole, aligned 16-byte pieces
+    const int n16 = (int)(sizeof(T) * width / 16);
+    for (int c = threadIdx.x; c < n16; c += kThreads)
+      reinterpret_cast<u32x4*>(dst)[c] = reinterpret_cast<const u32x4*>(src)[c];
+  } else {
+    for (int c = threadIdx.x; c < width; c += kThreads) dst[c] = src[c];
+  }
 }
 
 __global__ void copy_f32_kernel(float* __restrict__ dst, const float* __restrict__ src, size_t n) {
@@ -357,14 +365,17 @@ hipError_t launch_swiglu(int dtype, const float* P, int n_splits, size_t split_s
   return hipGetLastError();
 }
 
-hipError_t launch_scatter_rows(int dtype, const void* rows, const int32_t* idx, int m, int width, void* cache,
-                               hipStream_t st) {
+hipError_t launch_scatter_rows(int dtype, const void* rows_a, void* cache_a, const void* rows_b, void* cache_b,
+                               const int32_t* idx, int m, int width, hipStream_t st) {
   if (m <= 0) return hipSuccess;
+  const dim3 grid(m, rows_b ? 2 : 1);
+  const uintptr_t bits = (uintptr_t)rows_a | (uintptr_t)cache_a | (uintptr_t)rows_b | (uintptr_t)cache_b;
+  const int wide = (bits % 16 == 0) && (dtype_size(dtype) * (size_t)width % 16 == 0);
   D2C_DISPATCH(dtype,
-               hipLaunchKernelGGL(scatter_rows_kernel<bf16>, dim3(m), dim3(kThreads), 0, st, (const bf16*)rows, idx,
-                                  width, (bf16*)cache),
-               hipLaunchKernelGGL(scatter_rows_kernel<float>, dim3(m), dim3(kThreads), 0, st, (const float*)rows, idx,
-                                  width, (float*)cache));
+               hipLaunchKernelGGL(scatter_rows_kernel<bf16>, grid, dim3(kThreads), 0, st, (const bf16*)rows_a,
+                                  (bf16*)cache_a, (const bf16*)rows_b, (bf16*)cache_b, idx, width, wide),
+               hipLaunchKernelGGL(scatter_rows_kernel<float>, grid, dim3(kThreads), 0, st, (const float*)rows_a,
+                                  (float*)cache_a, (const float*)rows_b, (float*)cache_b, idx, width, wide));
   return hipGetLastError();
 }
 

@@ -57,20 +57,39 @@ def test_linear_parity(B, dtype, m, N, K):
 
 # ------------------------------------------------------------------ attention (config "C2" and edge shapes)
 ATTN_CASES = [
-    # dtype, H, Hkv, dh, L, m
-    ("bf16", 32, 32, 128, 2048, 256),      # the isolated selective-refresh attention workload, full size
-    ("bf16", 28, 4, 128, 768, 83),         # Dream geometry (GQA 28/4), ragged m
-    ("bf16", 4, 2, 64, 203, 37),           # head_dim 64, ragged L and m
-    ("bf16", 8, 8, 128, 17, 1),            # one query, L smaller than a workgroup's key span
-    ("bf16", 4, 4, 128, 130, 130),         # every row selected
-    ("f32", 4, 4, 64, 128, 73),            # the small fp32 model's geometry
-    ("f32", 4, 2, 8, 19, 5),
+    # dtype, H, Hkv, dh, L, m, kernels ("few": the few-row kernels, "tiled": the LDS-tiled ones, "": fp32)
+    ("bf16", 32, 32, 128, 2048, 256, "tiled"),    # the isolated selective-refresh attention workload, full size
+    ("bf16", 32, 32, 128, 2048, 256, "few"),
+    ("bf16", 28, 4, 128, 768, 83, "few"),         # Dream geometry (GQA 28/4), ragged m
+    ("bf16", 28, 4, 128, 768, 83, "tiled"),       # two query tiles per wave, split key range, ragged last block
+    ("bf16", 4, 2, 64, 203, 37, "few"),           # head_dim 64, ragged L and m
+    ("bf16", 4, 2, 64, 203, 37, "tiled"),
+    ("bf16", 8, 8, 128, 17, 1, "few"),            # one query, L smaller than a workgroup's key span
+    ("bf16", 8, 8, 128, 17, 1, "tiled"),          # a single, mostly empty key block
+    ("bf16", 4, 4, 128, 130, 130, "few"),         # every row selected
+    ("bf16", 4, 4, 128, 130, 130, "tiled"),
+    ("bf16", 32, 32, 128, 3072, 300, "tiled"),    # long-context shape: no key split, 3 query blocks, 48 key blocks
+    ("bf16", 3, 1, 64, 1000, 129, "tiled"),       # odd head count (A-bar loop tail), head_dim 64, 3 query blocks
+    ("f32", 4, 4, 64, 128, 73, ""),               # the small fp32 model's geometry
+    ("f32", 4, 2, 8, 19, 5, ""),
 ]
 
 
-@pytest.mark.parametrize("dtype,H,Hkv,dh,L,m", ATTN_CASES)
-def test_attention_parity(B, dtype, H, Hkv, dh, L, m):
-    say(f"attention dtype={dtype} H={H} Hkv={Hkv} dh={dh} L={L} m={m}")
+@pytest.mark.parametrize("dtype,H,Hkv,dh,L,m,kernels", ATTN_CASES)
+def test_attention_parity(B, dtype, H, Hkv, dh, L, m, kernels):
+    say(f"attention dtype={dtype} H={H} Hkv={Hkv} dh={dh} L={L} m={m} kernels={kernels}")
+    if kernels:
+        B.d2c_set_tunable("attn_tiled_min_m", 1 if kernels == "tiled" else 1 << 30)
+    try:
+        _attention_parity(B, dtype, H, Hkv, dh, L, m)
+    finally:
+        B.d2c_set_tunable("attn_tiled_min_m", ATTN_TILED_MIN_M_DEFAULT)
+
+
+ATTN_TILED_MIN_M_DEFAULT = 64
+
+
+def _attention_parity(B, dtype, H, Hkv, dh, L, m):
     wd = W.ModelDims(1, H * dh, H, Hkv, dh, 64, 64, dtype=dtype)
     ctx, dims, _ = _ctx_for(B, wd, max_seq=L)
     case = W.attention_case(1, H, Hkv, dh, L, m, dtype=dtype)
