@@ -23,6 +23,9 @@ struct d2c_ctx {
   const void* lm_head = nullptr;
   std::vector<const float*> attn_norm, bqkv, ffn_norm;
   std::vector<const void*> wqkv, wo, w_gate_up, w_down;
+  // pre = the projection matrices above (and lm_head) point at library-owned pre-tiled copies made by
+  // d2c_init (16-row x 256-byte blocks in the order the projection kernel's waves load them)
+  bool pre = false;
   // workspace (device)
   std::vector<void*> allocs;
   int64_t ws_bytes = 0;
@@ -129,7 +132,10 @@ size_t tsize(const d2c_ctx* c) { return dtype_size(c->dims.dtype); }
 int d_q(const d2c_ctx* c) { return c->dims.n_heads * c->dims.head_dim; }
 int d_kv(const d2c_ctx* c) { return c->dims.n_kv_heads * c->dims.head_dim; }
 
-// One projection on m rows: P = A W^T as split partials in the context's buffer.
+int pre_chunks(const d2c_ctx* c, int K) { return (int)(((size_t)K * tsize(c) + 255) / 256); }
+
+// One projection on m rows: P = A W^T as split partials in the context's buffer.  W is one of the
+// context's own projection matrices (pre-tiled when c->pre).
 int project(d2c_ctx* c, const void* A, int lda, const void* W, int m, int N, int K, GemmPlan* plan_out,
             size_t* stride_out, hipStream_t st, bool single_split = false, float* dst = nullptr) {
   GemmPlan pl = plan_gemm(c->dims.dtype, m, N, K, single_split);
@@ -137,7 +143,8 @@ int project(d2c_ctx* c, const void* A, int lda, const void* W, int m, int N, int
   float* P = dst ? dst : c->partial;
   if (!dst && stride * pl.splits > c->partial_floats) return fail(c, D2C_ESHAPE, "projection partials exceed workspace");
   D2C_TIMED(c, st, D2C_PROF_GEMM, (double)N * K * tsize(c),
-            launch_gemm(c->dims.dtype, pl, A, lda, W, K, P, N, stride, m, N, K, st));
+            launch_gemm(c->dims.dtype, pl, A, lda, W, c->pre ? pre_chunks(c, K) : K, P, N, stride, m, N, K, st,
+                        c->pre));
   *plan_out = pl;
   *stride_out = stride;
   return D2C_OK;
@@ -293,6 +300,29 @@ int d2c_init(const d2c_dims* dims, const d2c_weights* w, d2c_ctx** out) {
       return bail(fail(c, D2C_EHIP, "hipEventCreateWithFlags failed"));
   if (hipEventCreateWithFlags(&c->side_done, hipEventDisableTiming) != hipSuccess)
     return bail(fail(c, D2C_EHIP, "hipEventCreateWithFlags failed"));
+  if (tunables().gemm_preshuffle) {
+    // library-owned pre-tiled copies of every projection matrix; the caller's matrices are read here only
+    // (whatever stream wrote them must be done: wait for the device once)
+    if (hipDeviceSynchronize() != hipSuccess) return bail(fail(c, D2C_EHIP, "hipDeviceSynchronize failed"));
+    auto retile = [&](const void*& W, int N, int K) -> int {
+      void* dstp = nullptr;
+      int rc2 = ws_alloc(c, &dstp, preshuffled_bytes(N, K, D.dtype));
+      if (rc2) return rc2;
+      hipError_t e = launch_preshuffle(D.dtype, W, K, N, K, dstp, nullptr);
+      if (e != hipSuccess) return fail(c, D2C_EHIP, std::string("preshuffle: ") + hipGetErrorString(e));
+      W = dstp;
+      return D2C_OK;
+    };
+    for (int l = 0; l < D.n_layers && !rc; ++l) {
+      if ((rc = retile(c->wqkv[l], d_q(c) + 2 * d_kv(c), D.d_model)) || (rc = retile(c->wo[l], D.d_model, d_q(c))) ||
+          (rc = retile(c->w_gate_up[l], 2 * D.d_ffn, D.d_model)) || (rc = retile(c->w_down[l], D.d_model, D.d_ffn)))
+        break;
+    }
+    if (!rc) rc = retile(c->lm_head, D.vocab, D.d_model);
+    if (rc) return bail(rc);
+    if (hipStreamSynchronize(nullptr) != hipSuccess) return bail(fail(c, D2C_EHIP, "preshuffle failed"));
+    c->pre = true;
+  }
   hipError_t e2 = launch_rope_table(c->rope_cos, c->rope_sin, D.max_seq, D.head_dim, D.rope_theta, nullptr);
   if (e2 == hipSuccess) e2 = hipStreamSynchronize(nullptr);
   if (e2 != hipSuccess) return bail(fail(c, D2C_EHIP, std::string("rope table: ") + hipGetErrorString(e2)));
@@ -323,7 +353,8 @@ int d2c_set_tunable(const char* name, int32_t value) {
   if (!strcmp(name, "gemm_target_wgs")) t.gemm_target_wgs = value;
   else if (!strcmp(name, "gemm_max_splits")) t.gemm_max_splits = std::max(1, std::min(8, (int)value));
   else if (!strcmp(name, "gemm_nt_big_n")) t.gemm_nt_big_n = value;
-  else if (!strcmp(name, "gemm_waves")) t.gemm_waves = value == 16 ? 16 : value == 8 ? 8 : value == 4 ? 4 : 0;
+  else if (!strcmp(name, "gemm_waves")) t.gemm_waves = value == 8 ? 8 : value == 4 ? 4 : 0;
+  else if (!strcmp(name, "gemm_preshuffle")) t.gemm_preshuffle = value != 0;
   else if (!strcmp(name, "gemm_rot")) t.gemm_rot = value < 0 ? 0 : value;
   else if (!strcmp(name, "attn_tiled_min_m")) t.attn_tiled_min_m = value < 1 ? 1 : value;
   else if (!strcmp(name, "attn_max_splits")) t.attn_max_splits = std::max(1, std::min(8, (int)value));

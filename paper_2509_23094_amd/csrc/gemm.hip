@@ -37,7 +37,7 @@ constexpr int kRowStride = kChunkBytes + 16;     // LDS row pitch: 16-byte skew,
 constexpr int kSteps = 4;                        // matrix-core steps per chunk
 
 // RING = number of weight chunks a wave keeps in registers (one being consumed, RING-1 in flight).
-template <typename T, int MT, int NT, int WAVES>
+template <typename T, int MT, int NT, int WAVES, bool PRE>
 __global__ __launch_bounds__(WAVES * 64) void gemm_rows_kernel(
     const T* __restrict__ A, int lda, const T* __restrict__ W, int ldw, float* __restrict__ P, int ldp,
     size_t split_stride, int m, int N, int K, int k_per_split, int n_blocks, int n_splits, int row_chunks, int rot_mul) {
@@ -65,12 +65,20 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_rows_kernel(
   const int n_base = (bx * WAVES + wave) * (16 * NT);
   const int n_chunks = (k_end - k_begin + KC - 1) / KC;
 
-  // this lane's weight rows (clamped: out-of-range columns are computed on a valid row and dropped)
+  // this lane's weight rows (clamped: out-of-range columns are computed on a valid row and dropped).
+  // PRE: W is the pre-tiled copy (see preshuffle_kernel): [16-row tile][256-byte chunk][step][lane][16 B],
+  // ldw = chunks per tile; wrow then points at this lane's 16 bytes of step 0 of the tile's chunk 0.
+  constexpr int kBlockElems = 16 * KC;           // elements of one 16-row x 256-byte block (4 KB)
   const T* wrow[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
-    int n = min(n_base + nt * 16 + r, N - 1);
-    wrow[nt] = W + (size_t)n * ldw;
+    if (PRE) {
+      const int t16 = min((n_base + nt * 16) / 16, (N + 15) / 16 - 1);
+      wrow[nt] = W + (size_t)t16 * ldw * kBlockElems + lane * E;
+    } else {
+      int n = min(n_base + nt * 16 + r, N - 1);
+      wrow[nt] = W + (size_t)n * ldw;
+    }
   }
 
   Frag<T> areg[2][AI];                 // areg[c & 1]: activation chunk c on its way from global memory to LDS
@@ -116,11 +124,20 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_rows_kernel(
   };
   auto load_b = [&](Frag<T> (&b)[NT][kSteps], int chunk) {
     const int kc = chunk_k(chunk);
+    if (PRE) {
+      // one instruction = 1 KB contiguous: whole cache lines, no clamping (the copy is zero-padded)
+      const size_t off = (size_t)(kc / KC) * kBlockElems;
 #pragma unroll
-    for (int s = 0; s < kSteps; ++s) {
-      const int k = min(kc + s * KS + g * E, k_end - E);
+      for (int s = 0; s < kSteps; ++s)
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) b[nt][s].raw = ld16(wrow[nt] + k);
+        for (int nt = 0; nt < NT; ++nt) b[nt][s].raw = ld16(wrow[nt] + off + s * 64 * E);
+    } else {
+#pragma unroll
+      for (int s = 0; s < kSteps; ++s) {
+        const int k = min(kc + s * KS + g * E, k_end - E);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) b[nt][s].raw = ld16(wrow[nt] + k);
+      }
     }
   };
 
@@ -182,52 +199,63 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_rows_kernel(
     }
 }
 
-template <typename T, int MT, int NT, int WAVES>
+template <typename T, int MT, int NT, int WAVES, bool PRE>
 hipError_t launch_t(const GemmPlan& pl, const void* A, int lda, const void* W, int ldw, float* P, int ldp,
                     size_t split_stride, int m, int N, int K, hipStream_t st) {
   const int cols = 16 * NT * WAVES;
   const int n_blocks = (N + cols - 1) / cols;
   const int groups = (n_blocks * pl.splits + 7) / 8;            // weight tiles are dealt to the XCDs in groups of 8
   dim3 grid(groups * 8 * pl.row_chunks);
-  hipLaunchKernelGGL((gemm_rows_kernel<T, MT, NT, WAVES>), grid, dim3(WAVES * 64), 0, st, (const T*)A, lda,
+  hipLaunchKernelGGL((gemm_rows_kernel<T, MT, NT, WAVES, PRE>), grid, dim3(WAVES * 64), 0, st, (const T*)A, lda,
                      (const T*)W, ldw, P, ldp, split_stride, m, N, K, pl.k_per_split, n_blocks, pl.splits,
                      pl.row_chunks, pl.rot);
   return hipGetLastError();
 }
 
-template <typename T, int NT, int WAVES>
+template <typename T, int NT, int WAVES, bool PRE>
 hipError_t launch_mt(const GemmPlan& pl, const void* A, int lda, const void* W, int ldw, float* P, int ldp,
                      size_t ss, int m, int N, int K, hipStream_t st) {
   switch (pl.mt) {
-    case 1: return launch_t<T, 1, NT, WAVES>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 2: return launch_t<T, 2, NT, WAVES>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 3: return launch_t<T, 3, NT, WAVES>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 4: return launch_t<T, 4, NT, WAVES>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    case 1: return launch_t<T, 1, NT, WAVES, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    case 2: return launch_t<T, 2, NT, WAVES, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    case 3: return launch_t<T, 3, NT, WAVES, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    case 4: return launch_t<T, 4, NT, WAVES, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    case 5: return launch_t<T, 5, NT, WAVES, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    case 6: return launch_t<T, 6, NT, WAVES, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    case 7: return launch_t<T, 7, NT, WAVES, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    case 8: return launch_t<T, 8, NT, WAVES, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
     default: break;
-  }
-  if constexpr (WAVES <= 8) {      // 16 waves leave 128 registers per lane: not enough for more row tiles
-    switch (pl.mt) {
-      case 5: return launch_t<T, 5, NT, WAVES>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-      case 6: return launch_t<T, 6, NT, WAVES>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-      case 7: return launch_t<T, 7, NT, WAVES>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-      case 8: return launch_t<T, 8, NT, WAVES>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-      default: break;
-    }
   }
   return hipErrorInvalidValue;
 }
 
-template <typename T>
+template <typename T, bool PRE>
 hipError_t launch_nt(const GemmPlan& pl, const void* A, int lda, const void* W, int ldw, float* P, int ldp,
                      size_t ss, int m, int N, int K, hipStream_t st) {
   if (pl.nt == 1) {
-    if (pl.waves == 16) return launch_mt<T, 1, 16>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    if (pl.waves == 8) return launch_mt<T, 1, 8>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    return launch_mt<T, 1, 4>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    if (pl.waves == 8) return launch_mt<T, 1, 8, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    return launch_mt<T, 1, 4, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
   }
-  if (pl.waves == 16) return launch_mt<T, 2, 16>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-  if (pl.waves == 8) return launch_mt<T, 2, 8>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-  return launch_mt<T, 2, 4>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+  if (pl.waves == 8) return launch_mt<T, 2, 8, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+  return launch_mt<T, 2, 4, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+}
+
+// One 16-byte fragment per thread: dst block (tile t, chunk c) slot (step s, lane) <- src row t*16 + lane%16,
+// bytes c*256 + s*64 + (lane/16)*16; rows >= N and bytes >= the row length read as zero.
+__global__ __launch_bounds__(256) void preshuffle_kernel(const unsigned char* __restrict__ src, size_t src_pitch_bytes,
+                                                         int N, size_t row_bytes, int chunks,
+                                                         unsigned char* __restrict__ dst, size_t n_frags) {
+  const size_t f = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (f >= n_frags) return;
+  const int lane = (int)(f & 63), s = (int)((f >> 6) & 3);
+  const size_t block = f >> 8;
+  const int c = (int)(block % chunks);
+  const size_t t = block / chunks;
+  const size_t row = t * 16 + (lane & 15);
+  const size_t byte = (size_t)c * 256 + s * 64 + (lane >> 4) * 16;
+  u32x4 v = {0u, 0u, 0u, 0u};
+  if (row < (size_t)N && byte + 16 <= row_bytes) v = ld16(src + row * src_pitch_bytes + byte);
+  *reinterpret_cast<u32x4*>(dst + f * 16) = v;
 }
 
 }  // namespace
@@ -241,8 +269,7 @@ GemmPlan plan_gemm(int dtype, int m, int N, int K, bool single_split) {
   pl.nt = N > t.gemm_nt_big_n ? 2 : 1;
   pl.rot = t.gemm_rot;
   // narrow outputs with a deep k split gain from 8 waves sharing one activation chunk; wide ones from more workgroups
-  pl.waves = t.gemm_waves == 16 ? 16 : t.gemm_waves == 8 ? 8 : t.gemm_waves == 4 ? 4 : (N <= 8192 ? 8 : 4);
-  if (pl.waves == 16 && pl.mt > 4) pl.waves = 8;
+  pl.waves = t.gemm_waves == 8 ? 8 : t.gemm_waves == 4 ? 4 : (N <= 8192 ? 8 : 4);
   const int kc = dtype == kBF16 ? 128 : 64;                       // elements per 256-byte chunk
   const int n_blocks = (N + 16 * pl.nt * pl.waves - 1) / (16 * pl.nt * pl.waves);
   const int chunks = (K + kc - 1) / kc;
@@ -257,15 +284,38 @@ GemmPlan plan_gemm(int dtype, int m, int N, int K, bool single_split) {
 }
 
 hipError_t launch_gemm(int dtype, const GemmPlan& pl, const void* A, int lda, const void* W, int ldw, float* P,
-                       int ldp, size_t split_stride, int m, int N, int K, hipStream_t st) {
+                       int ldp, size_t split_stride, int m, int N, int K, hipStream_t st, bool pre) {
   if (m <= 0 || N <= 0 || K <= 0) return hipErrorInvalidValue;
   const int e = dtype == kBF16 ? 8 : 4;
   // 16-byte fragments: the contraction length and both pitches must be whole fragments
-  if (K % e || lda % e || ldw % e) return hipErrorInvalidValue;
+  if (K % e || lda % e || (!pre && ldw % e)) return hipErrorInvalidValue;
   if (pl.mt * 16 * pl.row_chunks < m || (size_t)pl.k_per_split * pl.splits < (size_t)K) return hipErrorInvalidValue;
   if (split_stride < (size_t)m * ldp || ldp < N) return hipErrorInvalidValue;
-  if (dtype == kBF16) return launch_nt<bf16>(pl, A, lda, W, ldw, P, ldp, split_stride, m, N, K, st);
-  return launch_nt<float>(pl, A, lda, W, ldw, P, ldp, split_stride, m, N, K, st);
+  if (pre) {
+    // ldw = chunks per tile of the pre-tiled copy; every split must start on a chunk boundary
+    const int kc = dtype == kBF16 ? 128 : 64;
+    if (ldw != (K + kc - 1) / kc || pl.k_per_split % kc) return hipErrorInvalidValue;
+    if (dtype == kBF16) return launch_nt<bf16, true>(pl, A, lda, W, ldw, P, ldp, split_stride, m, N, K, st);
+    return launch_nt<float, true>(pl, A, lda, W, ldw, P, ldp, split_stride, m, N, K, st);
+  }
+  if (dtype == kBF16) return launch_nt<bf16, false>(pl, A, lda, W, ldw, P, ldp, split_stride, m, N, K, st);
+  return launch_nt<float, false>(pl, A, lda, W, ldw, P, ldp, split_stride, m, N, K, st);
+}
+
+size_t preshuffled_bytes(int N, int K, int dtype) {
+  const size_t row_bytes = (size_t)K * dtype_size(dtype);
+  return (size_t)((N + 15) / 16) * ((row_bytes + 255) / 256) * 4096;
+}
+
+hipError_t launch_preshuffle(int dtype, const void* W, int ldw, int N, int K, void* dst, hipStream_t st) {
+  if (N <= 0 || K <= 0 || ldw < K) return hipErrorInvalidValue;
+  const size_t ts = dtype_size(dtype);
+  if ((size_t)K * ts % 16 || (size_t)ldw * ts % 16) return hipErrorInvalidValue;
+  const size_t n_frags = preshuffled_bytes(N, K, dtype) / 16;
+  const int chunks = (int)(((size_t)K * ts + 255) / 256);
+  hipLaunchKernelGGL(preshuffle_kernel, dim3((unsigned)((n_frags + 255) / 256)), dim3(256), 0, st,
+                     (const unsigned char*)W, (size_t)ldw * ts, N, (size_t)K * ts, chunks, (unsigned char*)dst, n_frags);
+  return hipGetLastError();
 }
 
 }  // namespace d2c

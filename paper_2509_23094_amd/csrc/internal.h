@@ -15,7 +15,8 @@ struct Tunables {
   int gemm_target_wgs = 512;   // aim for at least this many groups of 4 waves per GEMM
   int gemm_max_splits = 8;
   int gemm_nt_big_n = 16384;   // N above this uses two column tiles per wave
-  int gemm_waves = 0;          // waves per workgroup sharing one activation chunk in LDS: 4, 8, 16; 0 = by shape
+  int gemm_waves = 0;          // waves per workgroup sharing one activation chunk in LDS: 4, 8; 0 = by shape
+  bool gemm_preshuffle = true; // d2c_init keeps pre-tiled copies of the projection matrices (costs their size again)
   int gemm_rot = 0;            // start chunk of a workgroup's k walk = (column block * this) % chunks
   int attn_tiled_min_m = 64;   // bf16 attention: from this many query rows on, the LDS-tiled kernels
   int attn_max_splits = 8;     // key-range splits of one attention launch (1..8)
@@ -37,8 +38,14 @@ struct GemmPlan {
 };
 GemmPlan plan_gemm(int dtype, int m, int N, int K, bool single_split = false);
 // P must hold plan.splits * split_stride floats; split_stride >= m * ldp.
+// pre = W is a pre-tiled copy made by launch_preshuffle (then ldw = 256-byte chunks per row).
 hipError_t launch_gemm(int dtype, const GemmPlan& plan, const void* A, int lda, const void* W, int ldw,
-                       float* P, int ldp, size_t split_stride, int m, int N, int K, hipStream_t st);
+                       float* P, int ldp, size_t split_stride, int m, int N, int K, hipStream_t st,
+                       bool pre = false);
+// Pre-tiled weight copy: 16-row x 256-byte blocks, each stored as the 4 x 1 KB wave loads of the
+// projection kernel ([tile][chunk][step][lane][16 B]); rows and row tails are zero-padded.
+size_t preshuffled_bytes(int N, int K, int dtype);
+hipError_t launch_preshuffle(int dtype, const void* W, int ldw, int N, int K, void* dst, hipStream_t st);
 
 // ---- row-wise kernels
 // h[r,:] = emb[tokens[idx[r]],:];  a[r,:] = T(rmsnorm(h[r,:]) * gain)
