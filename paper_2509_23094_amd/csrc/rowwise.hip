@@ -73,47 +73,35 @@ __device__ __forceinline__ void store4(bf16* dst, const f32x4& v) {
   *reinterpret_cast<bf16x4*>(dst) = o;
 }
 
-// Same as add_norm_kernel for d <= NI*1024, d % 4 == 0: the row stays in registers and every
-// access is a 16-byte vector, all of a thread's loads independent of each other.
-template <typename T, int NI>
-__global__ __launch_bounds__(kThreads) void add_norm_vec_kernel(float* __restrict__ h, const float* __restrict__ P,
-                                                                int n_splits, size_t split_stride, int ldp, int d,
-                                                                const float* __restrict__ gain, float eps,
-                                                                T* __restrict__ a) {
-  __shared__ float red[kThreads / 64];
+// Same as add_norm_kernel for d <= 4*THREADS, d % 4 == 0: one 16-byte piece of the row per thread, kept in
+// registers; a thread's loads (the row piece and one piece per split) are all independent, and a
+// 4096-wide row is spread over 16 waves, so the kernel is about one memory latency long.
+template <typename T, int THREADS>
+__global__ __launch_bounds__(THREADS) void add_norm_vec_kernel(float* __restrict__ h, const float* __restrict__ P,
+                                                               int n_splits, size_t split_stride, int ldp, int d,
+                                                               const float* __restrict__ gain, float eps,
+                                                               T* __restrict__ a) {
+  __shared__ float red[THREADS / 64];
   const int r = blockIdx.x;
+  const int c = threadIdx.x * 4;
+  const bool live = c < d;
   float* hr = h + (size_t)r * d;
   const float* pr = P + (size_t)r * ldp;
-  f32x4 v[NI];
-#pragma unroll
-  for (int i = 0; i < NI; ++i) {
-    const int c = (threadIdx.x + i * kThreads) * 4;
-    v[i] = c < d ? *reinterpret_cast<const f32x4*>(hr + c) : f32x4{0.f, 0.f, 0.f, 0.f};
-  }
-  if (n_splits > 0) {
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const int c = (threadIdx.x + i * kThreads) * 4;
-      if (c < d) {
-        f32x4 add = {0.f, 0.f, 0.f, 0.f};
+  f32x4 v = {0.f, 0.f, 0.f, 0.f};
+  if (live) {
+    v = *reinterpret_cast<const f32x4*>(hr + c);
+    if (n_splits > 0) {
+      f32x4 add = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 8
-        for (int s = 0; s < n_splits; ++s) add += *reinterpret_cast<const f32x4*>(pr + (size_t)s * split_stride + c);
-        v[i] += add;
-        store4(hr + c, v[i]);
-      }
+      for (int s = 0; s < n_splits; ++s) add += *reinterpret_cast<const f32x4*>(pr + (size_t)s * split_stride + c);
+      v += add;
+      store4(hr + c, v);
     }
   }
   if (a == nullptr) return;
-  float ss = 0.f;
-#pragma unroll
-  for (int i = 0; i < NI; ++i) ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
+  const float ss = v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
   const float inv = 1.0f / sqrtf(block_sum(ss, red) / (float)d + eps);
-  T* ar = a + (size_t)r * d;
-#pragma unroll
-  for (int i = 0; i < NI; ++i) {
-    const int c = (threadIdx.x + i * kThreads) * 4;
-    if (c < d) store4(ar + c, v[i] * inv * *reinterpret_cast<const f32x4*>(gain + c));
-  }
+  if (live) store4(a + (size_t)r * d + c, v * inv * *reinterpret_cast<const f32x4*>(gain + c));
 }
 
 template <typename T>
@@ -299,11 +287,19 @@ hipError_t launch_add_norm(int dtype, float* h, const float* P, int n_splits, si
                            int d, const float* gain, float eps, void* a, hipStream_t st) {
   if (m <= 0) return hipSuccess;
   if (d % 4 == 0 && d <= 4096 && ldp % 4 == 0 && split_stride % 4 == 0) {
-    D2C_DISPATCH(dtype,
-                 hipLaunchKernelGGL((add_norm_vec_kernel<bf16, 4>), dim3(m), dim3(kThreads), 0, st, h, P, n_splits,
-                                    split_stride, ldp, d, gain, eps, (bf16*)a),
-                 hipLaunchKernelGGL((add_norm_vec_kernel<float, 4>), dim3(m), dim3(kThreads), 0, st, h, P, n_splits,
-                                    split_stride, ldp, d, gain, eps, (float*)a));
+    if (d > 1024) {
+      D2C_DISPATCH(dtype,
+                   hipLaunchKernelGGL((add_norm_vec_kernel<bf16, 1024>), dim3(m), dim3(1024), 0, st, h, P, n_splits,
+                                      split_stride, ldp, d, gain, eps, (bf16*)a),
+                   hipLaunchKernelGGL((add_norm_vec_kernel<float, 1024>), dim3(m), dim3(1024), 0, st, h, P, n_splits,
+                                      split_stride, ldp, d, gain, eps, (float*)a));
+    } else {
+      D2C_DISPATCH(dtype,
+                   hipLaunchKernelGGL((add_norm_vec_kernel<bf16, 256>), dim3(m), dim3(256), 0, st, h, P, n_splits,
+                                      split_stride, ldp, d, gain, eps, (bf16*)a),
+                   hipLaunchKernelGGL((add_norm_vec_kernel<float, 256>), dim3(m), dim3(256), 0, st, h, P, n_splits,
+                                      split_stride, ldp, d, gain, eps, (float*)a));
+    }
     return hipGetLastError();
   }
   D2C_DISPATCH(dtype,
