@@ -228,7 +228,7 @@ int d2c_profile_begin(d2c_ctx* ctx);
 int d2c_profile_end(d2c_ctx* ctx, double* ms, int64_t* launches, double* bytes);
 
 /* Launch-shape tunables, process-wide; set them before d2c_init.  Names:
- * "gemm_target_wgs", "gemm_max_splits" (1..8), "gemm_nt_big_n", "gemm_waves" (4, 8; 0 = chosen by shape), "gemm_rot"
+ * "gemm_target_wgs", "gemm_max_splits" (1..8), "gemm_nt_big_n", "gemm_waves" (4, 8; 0 = chosen by shape), "gemm_preshuffle" (0/1), "gemm_rot"
  * for the projection kernel; "attn_tiled_min_m" (bf16 attention switches to the LDS-tiled kernels from
  * this many query rows on), "attn_max_splits" (1..8, key-range splits of one attention launch); "side_stream" (0/1: whether d2c_step runs the head
  * average and the rollout on a second stream).  Returns D2C_EINVAL for an unknown name. */

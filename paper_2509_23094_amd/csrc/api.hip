@@ -26,6 +26,9 @@ struct d2c_ctx {
   // pre = the projection matrices above (and lm_head) point at library-owned pre-tiled copies made by
   // d2c_init (16-row x 256-byte blocks in the order the projection kernel's waves load them)
   bool pre = false;
+  // fused_swiglu = the pre-tiled gate/up copies alternate gate and up tiles and the projection applies
+  // the SwiGLU in its epilogue (no partials, no separate launch)
+  bool fused_swiglu = false;
   // workspace (device)
   std::vector<void*> allocs;
   int64_t ws_bytes = 0;
@@ -190,8 +193,15 @@ int layer_impl(d2c_ctx* c, int layer, float* hidden, const int32_t* idx, int m, 
   D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
             launch_add_norm(dt, hidden, c->partial, pl.splits, stride, d, m, d, c->ffn_norm[layer], D.rms_eps,
                             c->a_norm, st));
-  if ((rc = project(c, c->a_norm, d, c->w_gate_up[layer], m, 2 * F, d, &pl, &stride, st)) != D2C_OK) return rc;
-  D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0, launch_swiglu(dt, c->partial, pl.splits, stride, 2 * F, m, F, c->act, st));
+  if (c->fused_swiglu) {
+    pl = plan_gemm(dt, m, 2 * F, d, true);
+    D2C_TIMED(c, st, D2C_PROF_GEMM, 2.0 * F * d * tsize(c),
+              launch_gemm_swiglu(dt, pl, c->a_norm, d, c->w_gate_up[layer], pre_chunks(c, d), c->act, F, m, d, st));
+  } else {
+    if ((rc = project(c, c->a_norm, d, c->w_gate_up[layer], m, 2 * F, d, &pl, &stride, st)) != D2C_OK) return rc;
+    D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
+              launch_swiglu(dt, c->partial, pl.splits, stride, 2 * F, m, F, c->act, st));
+  }
   if ((rc = project(c, c->act, F, c->w_down[layer], m, d, F, &pl, &stride, st)) != D2C_OK) return rc;
   D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
             launch_add_norm(dt, hidden, c->partial, pl.splits, stride, d, m, d, next_gain, D.rms_eps,
@@ -304,24 +314,26 @@ int d2c_init(const d2c_dims* dims, const d2c_weights* w, d2c_ctx** out) {
     // library-owned pre-tiled copies of every projection matrix; the caller's matrices are read here only
     // (whatever stream wrote them must be done: wait for the device once)
     if (hipDeviceSynchronize() != hipSuccess) return bail(fail(c, D2C_EHIP, "hipDeviceSynchronize failed"));
-    auto retile = [&](const void*& W, int N, int K) -> int {
+    const bool fuse = D.d_ffn % 16 == 0;
+    auto retile = [&](const void*& W, int N, int K, int half = 0) -> int {
       void* dstp = nullptr;
       int rc2 = ws_alloc(c, &dstp, preshuffled_bytes(N, K, D.dtype));
       if (rc2) return rc2;
-      hipError_t e = launch_preshuffle(D.dtype, W, K, N, K, dstp, nullptr);
+      hipError_t e = launch_preshuffle(D.dtype, W, K, N, K, dstp, nullptr, half);
       if (e != hipSuccess) return fail(c, D2C_EHIP, std::string("preshuffle: ") + hipGetErrorString(e));
       W = dstp;
       return D2C_OK;
     };
     for (int l = 0; l < D.n_layers && !rc; ++l) {
       if ((rc = retile(c->wqkv[l], d_q(c) + 2 * d_kv(c), D.d_model)) || (rc = retile(c->wo[l], D.d_model, d_q(c))) ||
-          (rc = retile(c->w_gate_up[l], 2 * D.d_ffn, D.d_model)) || (rc = retile(c->w_down[l], D.d_model, D.d_ffn)))
+          (rc = retile(c->w_gate_up[l], 2 * D.d_ffn, D.d_model, fuse ? D.d_ffn : 0)) || (rc = retile(c->w_down[l], D.d_model, D.d_ffn)))
         break;
     }
     if (!rc) rc = retile(c->lm_head, D.vocab, D.d_model);
     if (rc) return bail(rc);
     if (hipStreamSynchronize(nullptr) != hipSuccess) return bail(fail(c, D2C_EHIP, "preshuffle failed"));
     c->pre = true;
+    c->fused_swiglu = fuse;
   }
   hipError_t e2 = launch_rope_table(c->rope_cos, c->rope_sin, D.max_seq, D.head_dim, D.rope_theta, nullptr);
   if (e2 == hipSuccess) e2 = hipStreamSynchronize(nullptr);

@@ -37,10 +37,17 @@ constexpr int kRowStride = kChunkBytes + 16;     // LDS row pitch: 16-byte skew,
 constexpr int kSteps = 4;                        // matrix-core steps per chunk
 
 // RING = number of weight chunks a wave keeps in registers (one being consumed, RING-1 in flight).
-template <typename T, int MT, int NT, int WAVES, bool PRE>
+// MODE: 0 = W row-major [N, K]; 1 = W pre-tiled; 2 = W pre-tiled with gate and up tiles interleaved and the
+// SwiGLU applied in the epilogue (single k split, one column tile per wave): act[m, N/2] = T(silu(g) * u).
+enum { kRowMajor = 0, kPre = 1, kPreSwiglu = 2 };
+
+template <typename T, int MT, int NT, int WAVES, int MODE>
 __global__ __launch_bounds__(WAVES * 64) void gemm_rows_kernel(
     const T* __restrict__ A, int lda, const T* __restrict__ W, int ldw, float* __restrict__ P, int ldp,
-    size_t split_stride, int m, int N, int K, int k_per_split, int n_blocks, int n_splits, int row_chunks, int rot_mul) {
+    size_t split_stride, int m, int N, int K, int k_per_split, int n_blocks, int n_splits, int row_chunks, int rot_mul,
+    T* __restrict__ act) {
+  constexpr bool PRE = MODE != kRowMajor;
+  static_assert(MODE != kPreSwiglu || (NT == 1 && WAVES % 2 == 0), "the SwiGLU epilogue pairs neighbouring waves");
   constexpr int RING = 2;
   constexpr int kThreads = WAVES * 64;
   constexpr int kAFrags = MT * 256;                              // 16-byte fragments of one activation chunk
@@ -184,6 +191,33 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_rows_kernel(
     }
   }
 
+  if (MODE == kPreSwiglu) {
+    // Column tiles alternate gate, up, gate, up ..: wave 2p holds the gate values and wave 2p+1 the up
+    // values of the same 16 hidden columns.  The odd wave hands its accumulators over through LDS (the
+    // activation buffers are idle: the loop ended on a barrier), the even wave applies the gate.
+    f32x4* xch = reinterpret_cast<f32x4*>(&lds[0][0]);          // [WAVES/2][MT][64]
+    const int pair = wave >> 1;
+    if (wave & 1) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) xch[(pair * MT + mt) * 64 + lane] = acc[mt][0];
+    }
+    __syncthreads();
+    if (wave & 1) return;
+    const int F = N >> 1;
+    const int col = (n_base >> 5) * 16 + r;                     // n_base = 32 * (hidden tile)
+    if (col >= F) return;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const f32x4 u = xch[(pair * MT + mt) * 64 + lane];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int row = row0 + mt * 16 + g * 4 + j;
+        const float gv = acc[mt][0][j];
+        if (row < m) act[(size_t)row * F + col] = from_f32<T>(gv / (1.0f + expf(-gv)) * u[j]);
+      }
+    }
+    return;
+  }
   float* out = P + (size_t)by * split_stride;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
@@ -199,51 +233,56 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_rows_kernel(
     }
 }
 
-template <typename T, int MT, int NT, int WAVES, bool PRE>
+template <typename T, int MT, int NT, int WAVES, int MODE>
 hipError_t launch_t(const GemmPlan& pl, const void* A, int lda, const void* W, int ldw, float* P, int ldp,
-                    size_t split_stride, int m, int N, int K, hipStream_t st) {
+                    size_t split_stride, int m, int N, int K, hipStream_t st, void* act) {
   const int cols = 16 * NT * WAVES;
   const int n_blocks = (N + cols - 1) / cols;
   const int groups = (n_blocks * pl.splits + 7) / 8;            // weight tiles are dealt to the XCDs in groups of 8
   dim3 grid(groups * 8 * pl.row_chunks);
-  hipLaunchKernelGGL((gemm_rows_kernel<T, MT, NT, WAVES, PRE>), grid, dim3(WAVES * 64), 0, st, (const T*)A, lda,
+  hipLaunchKernelGGL((gemm_rows_kernel<T, MT, NT, WAVES, MODE>), grid, dim3(WAVES * 64), 0, st, (const T*)A, lda,
                      (const T*)W, ldw, P, ldp, split_stride, m, N, K, pl.k_per_split, n_blocks, pl.splits,
-                     pl.row_chunks, pl.rot);
+                     pl.row_chunks, pl.rot, (T*)act);
   return hipGetLastError();
 }
 
-template <typename T, int NT, int WAVES, bool PRE>
+template <typename T, int NT, int WAVES, int MODE>
 hipError_t launch_mt(const GemmPlan& pl, const void* A, int lda, const void* W, int ldw, float* P, int ldp,
-                     size_t ss, int m, int N, int K, hipStream_t st) {
+                     size_t ss, int m, int N, int K, hipStream_t st, void* act) {
   switch (pl.mt) {
-    case 1: return launch_t<T, 1, NT, WAVES, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 2: return launch_t<T, 2, NT, WAVES, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 3: return launch_t<T, 3, NT, WAVES, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 4: return launch_t<T, 4, NT, WAVES, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 5: return launch_t<T, 5, NT, WAVES, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 6: return launch_t<T, 6, NT, WAVES, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 7: return launch_t<T, 7, NT, WAVES, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    case 8: return launch_t<T, 8, NT, WAVES, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    case 1: return launch_t<T, 1, NT, WAVES, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+    case 2: return launch_t<T, 2, NT, WAVES, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+    case 3: return launch_t<T, 3, NT, WAVES, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+    case 4: return launch_t<T, 4, NT, WAVES, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+    case 5: return launch_t<T, 5, NT, WAVES, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+    case 6: return launch_t<T, 6, NT, WAVES, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+    case 7: return launch_t<T, 7, NT, WAVES, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+    case 8: return launch_t<T, 8, NT, WAVES, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
     default: break;
   }
   return hipErrorInvalidValue;
 }
 
-template <typename T, bool PRE>
+template <typename T, int MODE>
 hipError_t launch_nt(const GemmPlan& pl, const void* A, int lda, const void* W, int ldw, float* P, int ldp,
-                     size_t ss, int m, int N, int K, hipStream_t st) {
+                     size_t ss, int m, int N, int K, hipStream_t st, void* act) {
   if (pl.nt == 1) {
-    if (pl.waves == 8) return launch_mt<T, 1, 8, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-    return launch_mt<T, 1, 4, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+    if (pl.waves == 8) return launch_mt<T, 1, 8, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+    return launch_mt<T, 1, 4, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
   }
-  if (pl.waves == 8) return launch_mt<T, 2, 8, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
-  return launch_mt<T, 2, 4, PRE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st);
+  if constexpr (MODE != kPreSwiglu) {
+    if (pl.waves == 8) return launch_mt<T, 2, 8, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+    return launch_mt<T, 2, 4, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+  }
+  return hipErrorInvalidValue;
 }
 
-// One 16-byte fragment per thread: dst block (tile t, chunk c) slot (step s, lane) <- src row t*16 + lane%16,
-// bytes c*256 + s*64 + (lane/16)*16; rows >= N and bytes >= the row length read as zero.
+// One 16-byte fragment per thread: dst block (tile t, chunk c) slot (step s, lane) <- src row
+// row_of(t) + lane%16, bytes c*256 + s*64 + (lane/16)*16; rows >= N and bytes >= the row length read as zero.
+// half > 0 (gate/up interleave, half % 16 == 0): dst tile 2j is src tile j, dst tile 2j+1 is the tile
+// that starts at src row half + 16j.
 __global__ __launch_bounds__(256) void preshuffle_kernel(const unsigned char* __restrict__ src, size_t src_pitch_bytes,
-                                                         int N, size_t row_bytes, int chunks,
+                                                         int N, size_t row_bytes, int chunks, int half,
                                                          unsigned char* __restrict__ dst, size_t n_frags) {
   const size_t f = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (f >= n_frags) return;
@@ -251,7 +290,8 @@ __global__ __launch_bounds__(256) void preshuffle_kernel(const unsigned char* __
   const size_t block = f >> 8;
   const int c = (int)(block % chunks);
   const size_t t = block / chunks;
-  const size_t row = t * 16 + (lane & 15);
+  const size_t row0 = half > 0 ? (t >> 1) * 16 + ((t & 1) ? (size_t)half : 0) : t * 16;
+  const size_t row = row0 + (lane & 15);
   const size_t byte = (size_t)c * 256 + s * 64 + (lane >> 4) * 16;
   u32x4 v = {0u, 0u, 0u, 0u};
   if (row < (size_t)N && byte + 16 <= row_bytes) v = ld16(src + row * src_pitch_bytes + byte);
@@ -296,11 +336,25 @@ hipError_t launch_gemm(int dtype, const GemmPlan& pl, const void* A, int lda, co
     // ldw = chunks per tile of the pre-tiled copy; every split must start on a chunk boundary
     const int kc = dtype == kBF16 ? 128 : 64;
     if (ldw != (K + kc - 1) / kc || pl.k_per_split % kc) return hipErrorInvalidValue;
-    if (dtype == kBF16) return launch_nt<bf16, true>(pl, A, lda, W, ldw, P, ldp, split_stride, m, N, K, st);
-    return launch_nt<float, true>(pl, A, lda, W, ldw, P, ldp, split_stride, m, N, K, st);
+    if (dtype == kBF16)
+      return launch_nt<bf16, kPre>(pl, A, lda, W, ldw, P, ldp, split_stride, m, N, K, st, nullptr);
+    return launch_nt<float, kPre>(pl, A, lda, W, ldw, P, ldp, split_stride, m, N, K, st, nullptr);
   }
-  if (dtype == kBF16) return launch_nt<bf16, false>(pl, A, lda, W, ldw, P, ldp, split_stride, m, N, K, st);
-  return launch_nt<float, false>(pl, A, lda, W, ldw, P, ldp, split_stride, m, N, K, st);
+  if (dtype == kBF16)
+    return launch_nt<bf16, kRowMajor>(pl, A, lda, W, ldw, P, ldp, split_stride, m, N, K, st, nullptr);
+  return launch_nt<float, kRowMajor>(pl, A, lda, W, ldw, P, ldp, split_stride, m, N, K, st, nullptr);
+}
+
+hipError_t launch_gemm_swiglu(int dtype, const GemmPlan& pl, const void* A, int lda, const void* W, int ldw,
+                              void* act, int F, int m, int K, hipStream_t st) {
+  if (m <= 0 || F <= 0 || K <= 0 || F % 16) return hipErrorInvalidValue;
+  const int e = dtype == kBF16 ? 8 : 4, kc = dtype == kBF16 ? 128 : 64;
+  if (K % e || lda % e || ldw != (K + kc - 1) / kc) return hipErrorInvalidValue;
+  if (pl.splits != 1 || pl.nt != 1 || pl.mt * 16 * pl.row_chunks < m || pl.k_per_split < K)
+    return hipErrorInvalidValue;
+  if (dtype == kBF16)
+    return launch_nt<bf16, kPreSwiglu>(pl, A, lda, W, ldw, nullptr, 0, 0, m, 2 * F, K, st, act);
+  return launch_nt<float, kPreSwiglu>(pl, A, lda, W, ldw, nullptr, 0, 0, m, 2 * F, K, st, act);
 }
 
 size_t preshuffled_bytes(int N, int K, int dtype) {
@@ -308,14 +362,18 @@ size_t preshuffled_bytes(int N, int K, int dtype) {
   return (size_t)((N + 15) / 16) * ((row_bytes + 255) / 256) * 4096;
 }
 
-hipError_t launch_preshuffle(int dtype, const void* W, int ldw, int N, int K, void* dst, hipStream_t st) {
+hipError_t launch_preshuffle(int dtype, const void* W, int ldw, int N, int K, void* dst, hipStream_t st,
+                             int interleave_half) {
   if (N <= 0 || K <= 0 || ldw < K) return hipErrorInvalidValue;
+  if (interleave_half < 0 || interleave_half % 16 || (interleave_half && N != 2 * interleave_half))
+    return hipErrorInvalidValue;
   const size_t ts = dtype_size(dtype);
   if ((size_t)K * ts % 16 || (size_t)ldw * ts % 16) return hipErrorInvalidValue;
   const size_t n_frags = preshuffled_bytes(N, K, dtype) / 16;
   const int chunks = (int)(((size_t)K * ts + 255) / 256);
   hipLaunchKernelGGL(preshuffle_kernel, dim3((unsigned)((n_frags + 255) / 256)), dim3(256), 0, st,
-                     (const unsigned char*)W, (size_t)ldw * ts, N, (size_t)K * ts, chunks, (unsigned char*)dst, n_frags);
+                     (const unsigned char*)W, (size_t)ldw * ts, N, (size_t)K * ts, chunks, interleave_half,
+                     (unsigned char*)dst, n_frags);
   return hipGetLastError();
 }
 

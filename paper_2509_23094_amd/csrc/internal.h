@@ -45,7 +45,12 @@ hipError_t launch_gemm(int dtype, const GemmPlan& plan, const void* A, int lda, 
 // Pre-tiled weight copy: 16-row x 256-byte blocks, each stored as the 4 x 1 KB wave loads of the
 // projection kernel ([tile][chunk][step][lane][16 B]); rows and row tails are zero-padded.
 size_t preshuffled_bytes(int N, int K, int dtype);
-hipError_t launch_preshuffle(int dtype, const void* W, int ldw, int N, int K, void* dst, hipStream_t st);
+// interleave_half = F > 0 (N = 2F, F % 16 == 0): 16-row tiles of the two halves alternate (gate, up, gate, ..).
+hipError_t launch_preshuffle(int dtype, const void* W, int ldw, int N, int K, void* dst, hipStream_t st,
+                             int interleave_half = 0);
+// act[m, F] = T(silu(g) * u) with [g | u] = A W^T, W a pre-tiled interleaved copy of [2F, K]; plan: single split
+hipError_t launch_gemm_swiglu(int dtype, const GemmPlan& plan, const void* A, int lda, const void* W, int ldw,
+                              void* act, int F, int m, int K, hipStream_t st);
 
 // ---- row-wise kernels
 // h[r,:] = emb[tokens[idx[r]],:];  a[r,:] = T(rmsnorm(h[r,:]) * gain)

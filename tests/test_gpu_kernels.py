@@ -134,11 +134,30 @@ LAYER_CASES = [
     ("bf16-gqa", W.ModelDims(1, 512, 8, 2, 64, 1024, 64, dtype="bf16"), 300, 150),
     ("C3-width", W.DIMS["C3"], 512, 83),     # one LLaDA-8B-shaped layer at full width
     ("C4-width", W.DIMS["C4"], 768, 100),    # one Dream-7B-shaped layer at full width
+
+
+    ("tiny-f32-odd-ffn", W.ModelDims(1, 64, 4, 4, 16, 72, 64, dtype="f32"), 40, 9),   # FFN width not a multiple of 16
 ]
+# the same block with the caller's row-major weights (no pre-tiled copies, separate SwiGLU launch)
+LAYER_CASES_ROW_MAJOR = ["C1-f32", "bf16-small", "C3-width"]
 
 
 @pytest.mark.parametrize("name,wd,L,m", LAYER_CASES, ids=[c[0] for c in LAYER_CASES])
 def test_refresh_layer_parity(B, name, wd, L, m):
+    _refresh_layer_parity(B, name, wd, L, m)
+
+
+@pytest.mark.parametrize("name", LAYER_CASES_ROW_MAJOR)
+def test_refresh_layer_parity_row_major_weights(B, name):
+    case = [c for c in LAYER_CASES if c[0] == name][0]
+    B.d2c_set_tunable("gemm_preshuffle", 0)
+    try:
+        _refresh_layer_parity(B, *case)
+    finally:
+        B.d2c_set_tunable("gemm_preshuffle", 1)
+
+
+def _refresh_layer_parity(B, name, wd, L, m):
     say(f"refresh_layer {name} L={L} m={m}")
     ctx, dims, mdl = _ctx_for(B, wd, max_seq=L, tiny_vocab=64)
     od = oracle_dims(dims)
