@@ -44,9 +44,13 @@ def device_model(W, dims, seed, torch):
             "layers": layers}
 
 
-def fresh_sequence(B, W, ctx, dims, su, seed):
-    y0, m0 = W.initial_sequence(dims, su, seed)
-    return B.Sequence_(ctx, y0, m0, su.prompt_len)
+def fresh_sequences(B, W, ctx, dims, su, gen):
+    """One batch of independent sequences (different prompts, same lengths)."""
+    seqs = []
+    for b in range(su.batch):
+        y0, m0 = W.initial_sequence(dims, su, gen * su.batch + b)
+        seqs.append(B.Sequence_(ctx, y0, m0, su.prompt_len))
+    return seqs
 
 
 def cpu_baseline(W, dims, su, m_rows, n_logit_rows):
@@ -148,7 +152,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=128)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="C3", choices=["C3", "C4", "C2"],
+    ap.add_argument("--workload", default="C3", choices=["C3", "C4", "C5", "C2"],
                     help="C3 (default, the metric's workload), C4, or C2 = the isolated selective-refresh attention op")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (the result is then not the metric)")
     ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
@@ -196,16 +200,16 @@ def main():
     ctx = B.Context(dims, mdl, su.seq_len, device_weights=True)
     prm = B.make_params(su.sigma, su.k, su.p, su.block_len, su.n_unmask, 0)
 
-    def run_steps(seq, n, collect=None):
+    def run_steps(seqs, n, collect=None):
         for _ in range(n):
             if collect is not None:
-                collect.append((seq.n_s, seq.n_rows))
-            ctx.d2c_step(prm, [seq])
+                collect.append((sum(q.n_s for q in seqs), sum(q.n_rows for q in seqs)))
+            ctx.d2c_step(prm, seqs)
 
     # ---- timed region: exactly K d2Cache steps (in as many generations as needed), after W warm-up steps
     elapsed, done, shapes, gen = 0.0, 0, [], 0
     while done < K:
-        seq = fresh_sequence(B, W, ctx, dims, su, gen)
+        seq = fresh_sequences(B, W, ctx, dims, su, gen)
         run_steps(seq, 1)                                 # step 0: every row, fills the caches (not timed)
         run_steps(seq, Wm if gen == 0 else 0)             # warm-up
         n = min(K - done, per_gen - (Wm if gen == 0 else 0))
@@ -221,7 +225,7 @@ def main():
     mean_rows = float(np.mean([s[1] for s in shapes]))
 
     # ---- roofline pass: the same steps again with an event pair around every launch
-    seq = fresh_sequence(B, W, ctx, dims, su, 0)
+    seq = fresh_sequences(B, W, ctx, dims, su, 0)
     run_steps(seq, 1 + Wm)
     n_prof = min(K, per_gen - Wm)
     torch.cuda.synchronize()
@@ -250,19 +254,19 @@ def main():
     # ---- full recomputation (the paper's Vanilla): the same engine with every row selected
     vanilla = None
     if not args.no_vanilla:
-        seqv = fresh_sequence(B, W, ctx, dims, su, 0)
+        seqv = fresh_sequences(B, W, ctx, dims, su, 0)
         # k >= |M|, p = 1 and a single block select every row at every step
         pv = B.make_params(su.sigma, su.seq_len, 1.0, su.gen_len, su.n_unmask, 0)
         for _ in range(2):
-            ctx.d2c_step(pv, [seqv])
+            ctx.d2c_step(pv, seqv)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         nv = 4
         for _ in range(nv):
-            assert seqv.n_s == su.seq_len
-            ctx.d2c_step(pv, [seqv])
+            assert all(q.n_s == su.seq_len for q in seqv)
+            ctx.d2c_step(pv, seqv)
         torch.cuda.synchronize()
-        vanilla = {"ms_per_step": round(1e3 * (time.perf_counter() - t0) / nv, 3), "rows_per_step": su.seq_len}
+        vanilla = {"ms_per_step": round(1e3 * (time.perf_counter() - t0) / nv, 3), "rows_per_step": su.seq_len * su.batch}
         vanilla["steps_per_sec"] = round(1e3 / vanilla["ms_per_step"], 2)
 
     cpu = None
@@ -276,12 +280,12 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: %s-shaped random-init model, %d layers, d_model %d, %dx%d heads, FFN %d, "
                                "vocab %d; prompt %d + gen %d, block %d, %d token/step, sigma %g k %d p %g"
-                               % (args.workload, {"C3": "LLaDA-8B", "C4": "Dream-7B"}[args.workload], dims.n_layers, dims.d_model, dims.n_heads, dims.head_dim, dims.d_ffn,
+                               % (args.workload, {"C3": "LLaDA-8B", "C4": "Dream-7B", "C5": "LLaDA-8B"}[args.workload], dims.n_layers, dims.d_model, dims.n_heads, dims.head_dim, dims.d_ffn,
                                   dims.vocab, su.prompt_len, su.gen_len, su.block_len, su.n_unmask, su.sigma, su.k,
                                   su.p),
-                   "batch": 1, "seq_len": su.seq_len, "mean_rows_per_step": round(mean_m, 2),
+                   "batch": su.batch, "seq_len": su.seq_len, "mean_rows_per_step": round(mean_m, 2),
                    "mean_logit_rows_per_step": round(mean_rows, 2)},
-        "tokens_per_sec": round(su.n_unmask * K / elapsed, 3),
+        "tokens_per_sec": round(su.batch * su.n_unmask * K / elapsed, 3),
         "algorithmic_gb_per_step": round(step_bytes / 1e9, 3),
         "step_hbm_frac": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "roofline": roofline, "kernel_classes": by_class, "full_recompute": vanilla, "cpu_baseline": cpu,
