@@ -336,8 +336,11 @@ __global__ __launch_bounds__(kThreads) void attn_merge_kernel(const float* __res
   if (c == 0) lse[hr] = mx + __logf(lsum);
 }
 
-// A-bar tile of 64 queries x 16*KA keys: loop over the heads, K block of each head through LDS.
-template <int DH, int KA>
+// A-bar tile of 64*QT queries x 16*KA keys: loop over the heads, K block of each head through LDS,
+// exp2(s*c - lse*log2e) accumulated in registers.  Every iteration streams its Q and K pieces once
+// (no reuse across heads), so the bytes per tile fall with the tile size: the plan takes the largest
+// tile and restores the workgroup count by dealing the heads to several workgroups per tile.
+template <int DH, int KA, int QT>
 __global__ __launch_bounds__(kThreads) void attn_tiled_avg_kernel(const bf16* __restrict__ q,
                                                                   const bf16* __restrict__ k_cache,
                                                                   const float* __restrict__ lse, int m, int L,
@@ -350,22 +353,29 @@ __global__ __launch_bounds__(kThreads) void attn_tiled_avg_kernel(const bf16* __
   __shared__ u32x4 k_lds[2][NF * 64];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 15, g = lane >> 4;
-  const int q0 = blockIdx.x * 64 + wave * 16;
+  const int q0 = blockIdx.x * (64 * QT) + wave * (16 * QT);
   const int key0 = blockIdx.y * (16 * KA);
   const int dq = n_heads * DH;
   const size_t kv_pitch = (size_t)n_kv_heads * DH;
   const int group = n_heads / n_kv_heads;
-  const int row = min(q0 + r, m - 1);
-  const bf16* qrow = q + (size_t)row * dq + g * 8;
+  int row[QT];
+  const bf16* qrow[QT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    row[t] = min(q0 + t * 16 + r, m - 1);
+    qrow[t] = q + (size_t)row[t] * dq + g * 8;
+  }
   // blockIdx.z = head group; with several groups each writes its own [m, L] partial (already divided
   // by the head count) and a separate launch adds the partials in group order
   const int head_lo = blockIdx.z * heads_per_group;
   const int head_hi = min(n_heads, head_lo + heads_per_group);
   attn_avg += (size_t)blockIdx.z * m * L;
+  const float c2 = scale * 1.44269504088896341f;
 
   u32x4 kst[FW];
-  Frag<bf16> qf[2][NS];
-  float e[2];
+  Frag<bf16> qf[2][QT][NS];
+  float e[2][QT];                                // lse of the head in flight / in use (raw: any arithmetic on a
+                                                 // value just loaded would wait for every outstanding load)
   auto load_head = [&](int head, int slot) {
     const int kvh = head / group;
 #pragma unroll
@@ -375,17 +385,22 @@ __global__ __launch_bounds__(kThreads) void attn_tiled_avg_kernel(const bf16* __
       kst[i] = ld16(k_cache + (size_t)key * kv_pitch + kvh * DH + (f % NS) * 32 + g * 8);
     }
 #pragma unroll
-    for (int s = 0; s < NS; ++s) qf[slot][s].raw = ld16(qrow + head * DH + s * 32);
-    e[slot] = lse[(size_t)head * m + row];
+    for (int t = 0; t < QT; ++t) {
+#pragma unroll
+      for (int s = 0; s < NS; ++s) qf[slot][t][s].raw = ld16(qrow[t] + head * DH + s * 32);
+      e[slot][t] = lse[(size_t)head * m + row[t]];
+    }
   };
   auto store_head = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < FW; ++i) k_lds[buf][min(wave + 4 * i, NF - 1) * 64 + lane] = kst[i];
   };
 
-  f32x4 acc[KA];
+  f32x4 acc[KA][QT];
 #pragma unroll
-  for (int a = 0; a < KA; ++a) acc[a] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int a = 0; a < KA; ++a)
+#pragma unroll
+    for (int t = 0; t < QT; ++t) acc[a][t] = f32x4{0.f, 0.f, 0.f, 0.f};
   load_head(head_lo, 0);
   store_head(0);
   __syncthreads();
@@ -397,28 +412,42 @@ __global__ __launch_bounds__(kThreads) void attn_tiled_avg_kernel(const bf16* __
       const float live = head < head_hi ? 1.f : 0.f;
 #pragma unroll
       for (int a = 0; a < KA; ++a) {
-        f32x4 st = {0.f, 0.f, 0.f, 0.f};
+        f32x4 st[QT];
+#pragma unroll
+        for (int t = 0; t < QT; ++t) st[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
           Frag<bf16> kf;
           kf.raw = k_lds[u][(a * NS + s) * 64 + lane];
-          mfma16(st, kf, qf[u][s]);
+#pragma unroll
+          for (int t = 0; t < QT; ++t) mfma16(st[t], kf, qf[u][t][s]);
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[a][j] += live * __expf(st[j] * scale - e[u]);
+        for (int t = 0; t < QT; ++t) {
+          const float ne2 = -1.44269504088896341f * e[u][t];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[a][t][j] += live * __builtin_amdgcn_exp2f(fmaf(st[t][j], c2, ne2));
+        }
       }
       store_head(u ^ 1);
       __syncthreads();
+      // nothing of the next head's arithmetic may move up here: anything that touches a value still in
+      // flight would make this half wait for all of its own prefetch loads
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
-  if (q0 + r >= m) return;
   const float inv_h = 1.0f / (float)n_heads;
 #pragma unroll
-  for (int a = 0; a < KA; ++a) {
-    float* dst = attn_avg + (size_t)(q0 + r) * L + key0 + a * 16 + 4 * g;
+  for (int t = 0; t < QT; ++t) {
+    const int qr = q0 + t * 16 + r;
+    if (qr >= m) continue;
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if (key0 + a * 16 + 4 * g + j < L) dst[j] = acc[a][j] * inv_h;
+    for (int a = 0; a < KA; ++a) {
+      float* dst = attn_avg + (size_t)qr * L + key0 + a * 16 + 4 * g;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (key0 + a * 16 + 4 * g + j < L) dst[j] = acc[a][t][j] * inv_h;
+    }
   }
 }
 
@@ -470,18 +499,19 @@ hipError_t launch_fwd(const void* q, const void* k_cache, const void* v_cache, i
 }
 
 struct AvgPlan {
-  int ka, key_blocks, q_blocks, groups, heads_per_group;
+  int ka, qt, key_blocks, q_blocks, groups, heads_per_group;
 };
 AvgPlan plan_avg(int m, int L, int n_heads) {
   AvgPlan p;
-  p.q_blocks = (m + 63) / 64;
-  // 64 keys per workgroup once that still gives every compute unit a workgroup, else 32
-  p.ka = (size_t)p.q_blocks * ((L + 63) / 64) >= (size_t)kTargetWgs ? 4 : 2;
+  // the largest tile the row and key counts fill: 128 x 128, 64 x 128 (m <= 64) or 64 x 32 (L <= 32)
+  p.qt = m > 64 ? 2 : 1;
+  p.ka = L > 32 ? 8 : 2;
+  p.q_blocks = (m + 64 * p.qt - 1) / (64 * p.qt);
   p.key_blocks = (L + 16 * p.ka - 1) / (16 * p.ka);
   // The loop over the heads is a chain of dependent load latencies: when the tile grid alone leaves
   // most of the chip idle, the heads are dealt to several workgroups per tile.
   int groups = 1;
-  while (groups < 8 && groups * 2 <= n_heads && (size_t)p.q_blocks * p.key_blocks * groups < 4 * kTargetWgs) groups *= 2;
+  while (groups < 8 && groups * 2 <= n_heads && (size_t)p.q_blocks * p.key_blocks * groups < 2 * kTargetWgs) groups *= 2;
   p.heads_per_group = (n_heads + groups - 1) / groups;
   p.groups = (n_heads + p.heads_per_group - 1) / p.heads_per_group;
   return p;
@@ -495,12 +525,14 @@ hipError_t launch_avg(const void* q, const void* k_cache, const float* lse, int 
   if (p.groups > 1 && (!scratch || (size_t)p.groups * m * L > scratch_floats)) return hipErrorInvalidValue;
   float* dst = p.groups > 1 ? scratch : attn_avg;
   const dim3 grid(p.q_blocks, p.key_blocks, p.groups);
-  if (p.ka == 4)
-    hipLaunchKernelGGL((attn_tiled_avg_kernel<DH, 4>), grid, dim3(kThreads), 0, st, (const bf16*)q,
-                       (const bf16*)k_cache, lse, m, L, n_heads, n_kv_heads, scale, p.heads_per_group, dst);
-  else
-    hipLaunchKernelGGL((attn_tiled_avg_kernel<DH, 2>), grid, dim3(kThreads), 0, st, (const bf16*)q,
-                       (const bf16*)k_cache, lse, m, L, n_heads, n_kv_heads, scale, p.heads_per_group, dst);
+#define D2C_AVG(KA_, QT_)                                                                                      \
+  hipLaunchKernelGGL((attn_tiled_avg_kernel<DH, KA_, QT_>), grid, dim3(kThreads), 0, st, (const bf16*)q,       \
+                     (const bf16*)k_cache, lse, m, L, n_heads, n_kv_heads, scale, p.heads_per_group, dst)
+  if (p.ka == 8 && p.qt == 2) D2C_AVG(8, 2);
+  else if (p.ka == 8) D2C_AVG(8, 1);
+  else if (p.qt == 2) D2C_AVG(2, 2);
+  else D2C_AVG(2, 1);
+#undef D2C_AVG
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || p.groups == 1) return e;
   return launch_sum_splits(attn_avg, scratch, p.groups, (size_t)m * L, (size_t)m * L, st);
