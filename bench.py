@@ -197,7 +197,7 @@ def main():
     assert Wm < per_gen, "warmup must be shorter than one generation"
 
     mdl = device_model(W, dims, 0, torch)
-    ctx = B.Context(dims, mdl, su.seq_len, device_weights=True)
+    ctx = B.Context(dims, mdl, su.seq_len, device_weights=True, max_batch=su.batch)
     prm = B.make_params(su.sigma, su.k, su.p, su.block_len, su.n_unmask, 0)
 
     def run_steps(seqs, n, collect=None):

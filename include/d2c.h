@@ -56,6 +56,9 @@ typedef struct {
   float   rms_eps;
   float   rope_theta;
   int32_t mask_id;      /* id of the [MASK] token (Sec. 3.1)                      */
+  int32_t max_batch;    /* sequences whose selected rows one d2c_step projects together
+                           (the weights are then streamed once per group, not once per
+                           sequence); the row-sized workspace grows with it; 0 = 1     */
 } d2c_dims;
 
 /* Borrowed device pointers.  The per-layer members are HOST arrays of n_layers
@@ -204,7 +207,9 @@ int d2c_influence(d2c_ctx* ctx, const float* rollout, const int32_t* idx, int32_
 /* One whole denoising step for `batch` independent sequences: partial forward
  * over S_t through all layers with rollout, LM head and Eq. 1 on the masked rows
  * of S_t, selection and unmasking; leaves S_{t+1} in the state and refreshes the
- * host mirrors.  A sequence with n_masked == 0 is skipped. */
+ * host mirrors.  A sequence with n_masked == 0 is skipped.  The sequences are independent (own
+ * caches, sets, rollout); they are taken in groups of up to max_batch whose rows share the
+ * projection launches, every other kernel runs per sequence. */
 int d2c_step(d2c_ctx* ctx, const d2c_params* params, d2c_seq_state* seqs, int32_t batch,
              void* stream);
 

@@ -31,7 +31,7 @@ class D2CError(RuntimeError):
 class d2c_dims(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "n_kv_heads", "head_dim", "d_ffn",
                                           "vocab", "max_seq", "dtype")] + \
-               [("rms_eps", C.c_float), ("rope_theta", C.c_float), ("mask_id", C.c_int32)]
+               [("rms_eps", C.c_float), ("rope_theta", C.c_float), ("mask_id", C.c_int32), ("max_batch", C.c_int32)]
 
 
 class d2c_weights(C.Structure):
@@ -126,7 +126,7 @@ def make_params(sigma=10.0, k=32, p=0.1, block_len=32, n_unmask=1, cand_mode=0, 
 class Context:
     """Owns a d2c_ctx and keeps the borrowed weight tensors alive."""
 
-    def __init__(self, dims, weights: Dict, max_seq: int, device_weights: bool = False):
+    def __init__(self, dims, weights: Dict, max_seq: int, device_weights: bool = False, max_batch: int = 1):
         """dims: workloads.ModelDims; weights: {tok_emb, final_norm, lm_head, layers: [{...}]} as numpy
         float32 arrays, or (device_weights=True) as device tensors already in the storage type."""
         self.dims = dims
@@ -172,7 +172,7 @@ class Context:
         w.bqkv = arr(bias) if has_bias else None
         d = d2c_dims(n_layers, dims.d_model, dims.n_heads, dims.n_kv_heads, dims.head_dim, dims.d_ffn, dims.vocab,
                      self.max_seq, D2C_BF16 if self.dtype == "bf16" else D2C_F32, dims.rms_eps, dims.rope_theta,
-                     dims.mask_id)
+                     dims.mask_id, int(max_batch))
         self.n_layers = n_layers
         self.handle = C.c_void_p()
         rc = _lib.d2c_init(C.byref(d), C.byref(w), C.byref(self.handle))

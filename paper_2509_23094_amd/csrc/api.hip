@@ -32,7 +32,7 @@ struct d2c_ctx {
   // workspace (device)
   std::vector<void*> allocs;
   int64_t ws_bytes = 0;
-  float* hidden = nullptr;      // [max_seq, d]
+  float* hidden = nullptr;      // [max_rows, d]
   void* a_norm = nullptr;       // T [max_seq, d]
   void* q = nullptr;            // T [n_layers, max_seq, d_q]: one slot per layer (read later by the side stream)
   void* attn_o = nullptr;       // T [max_seq, d_q]
@@ -44,7 +44,9 @@ struct d2c_ctx {
   float* partial = nullptr;     // split partials of the current projection
   size_t partial_floats = 0;
   float* abar = nullptr;        // [max_seq, max_seq]
-  float* roll[2] = {nullptr, nullptr};
+  std::vector<float*> roll;     // 2 per batch slot (ping-pong over the layers), each [max_seq, max_seq]
+  int max_batch = 1;            // sequences whose rows d2c_step projects together
+  size_t max_rows = 0;          // max_seq * max_batch: rows the row-count-sized buffers hold
   void* head_a = nullptr;       // T [head_rows, d]
   float* logits = nullptr;      // [head_rows, vocab]
   float* conf_part = nullptr;   // per-chunk (max, argmax, sum) triples of Eq. 1 for up to max_seq rows
@@ -153,59 +155,85 @@ int project(d2c_ctx* c, const void* A, int lda, const void* W, int m, int N, int
   return D2C_OK;
 }
 
-// One block on m compact rows.  a_ready: ctx->a_norm already holds RMSNorm(hidden) * attn_norm[layer].
-// next_gain: when non-null the last kernel also leaves RMSNorm(hidden) * next_gain in ctx->a_norm.
+// One sequence's share of a block: its m selected rows sit at rows off .. off+m of the compact buffers.
+struct Seg {
+  const int32_t* idx;
+  int m, off;
+  void *k_cache, *v_cache;      // this layer's cache of the sequence
+  int L;
+  const float* roll_in;         // rollout block before this layer (ignored at layer 0)
+  float* roll_out;              // rollout block after it; null = no rollout update
+};
+
+// One block on the M = sum of m compact rows of n_seg sequences.  The projections run once over all M rows
+// (the weights are streamed once for the whole batch); RoPE + cache update, attention, the head average and
+// the rollout run per sequence on its slice.  a_ready: ctx->a_norm already holds RMSNorm(hidden) *
+// attn_norm[layer].  next_gain: when non-null the last kernel also leaves RMSNorm(hidden) * next_gain in
+// ctx->a_norm.  abar: scratch [m, L] for the head average of one sequence at a time (null = none wanted).
 // side: the stream the head average and the rollout update run on; when it differs from st they are
 // ordered after this layer's attention by ctx->fwd_done[layer] and the caller joins them later.
-int layer_impl(d2c_ctx* c, int layer, float* hidden, const int32_t* idx, int m, void* k_cache, void* v_cache, int L,
-               float* abar, const float* roll_in, float* roll_out, bool a_ready, const float* next_gain,
-               hipStream_t st, hipStream_t side) {
+int layer_impl(d2c_ctx* c, int layer, float* hidden, const Seg* segs, int n_seg, int M, float* abar, bool a_ready,
+               const float* next_gain, hipStream_t st, hipStream_t side) {
   const d2c_dims& D = c->dims;
   const int dt = D.dtype, d = D.d_model, dq = d_q(c), dkv = d_kv(c), F = D.d_ffn;
-  void* q = (char*)c->q + (size_t)layer * D.max_seq * dq * tsize(c);
-  float* lse = c->lse + (size_t)layer * D.n_heads * D.max_seq;
+  const size_t ts = tsize(c);
+  char* q = (char*)c->q + (size_t)layer * c->max_rows * dq * ts;
+  float* lse = c->lse + (size_t)layer * D.n_heads * c->max_rows;
   GemmPlan pl;
   size_t stride;
   int rc;
   if (!a_ready)
     D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
-              launch_add_norm(dt, hidden, nullptr, 0, 0, d, m, d, c->attn_norm[layer], D.rms_eps, c->a_norm, st));
-  if ((rc = project(c, c->a_norm, d, c->wqkv[layer], m, dq + 2 * dkv, d, &pl, &stride, st)) != D2C_OK) return rc;
-  D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
-            launch_qkv_rope_scatter(dt, c->partial, pl.splits, stride, dq + 2 * dkv,
-                                    c->bqkv.empty() ? nullptr : c->bqkv[layer], idx, m, D.n_heads, D.n_kv_heads,
-                                    D.head_dim, c->rope_cos, c->rope_sin, q, k_cache, v_cache, st));
-  D2C_TIMED(c, st, D2C_PROF_ATTENTION, 2.0 * L * dkv * tsize(c),
-            launch_attention_fwd(dt, q, k_cache, v_cache, m, L, D.n_heads, D.n_kv_heads, D.head_dim, c->attn_o, lse,
-                                 c->attn_part, c->attn_part_floats, st));
+              launch_add_norm(dt, hidden, nullptr, 0, 0, d, M, d, c->attn_norm[layer], D.rms_eps, c->a_norm, st));
+  if ((rc = project(c, c->a_norm, d, c->wqkv[layer], M, dq + 2 * dkv, d, &pl, &stride, st)) != D2C_OK) return rc;
+  for (int b = 0; b < n_seg; ++b) {
+    const Seg& g = segs[b];
+    if (g.m <= 0) continue;
+    void* qb = q + (size_t)g.off * dq * ts;
+    D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
+              launch_qkv_rope_scatter(dt, c->partial + (size_t)g.off * (dq + 2 * dkv), pl.splits, stride,
+                                      dq + 2 * dkv, c->bqkv.empty() ? nullptr : c->bqkv[layer], g.idx, g.m,
+                                      D.n_heads, D.n_kv_heads, D.head_dim, c->rope_cos, c->rope_sin, qb, g.k_cache,
+                                      g.v_cache, st));
+    D2C_TIMED(c, st, D2C_PROF_ATTENTION, 2.0 * g.L * dkv * ts,
+              launch_attention_fwd(dt, qb, g.k_cache, g.v_cache, g.m, g.L, D.n_heads, D.n_kv_heads, D.head_dim,
+                                   (char*)c->attn_o + (size_t)g.off * dq * ts, lse + (size_t)D.n_heads * g.off,
+                                   c->attn_part, c->attn_part_floats, st));
+  }
   if (abar) {
     if (side != st) {
       D2C_HIP(c, hipEventRecord(c->fwd_done[layer], st));
       D2C_HIP(c, hipStreamWaitEvent(side, c->fwd_done[layer], 0));
     }
-    D2C_TIMED(c, side, D2C_PROF_ATTN_AVG, 0.0,
-              launch_attention_avg(dt, q, k_cache, lse, m, L, D.n_heads, D.n_kv_heads, D.head_dim, abar, c->avg_part,
-                                   c->avg_part_floats, side));
-    if (roll_out)
-      D2C_TIMED(c, side, D2C_PROF_ROLLOUT, 0.0, launch_rollout(abar, roll_in, roll_out, idx, m, L, layer == 0, side));
+    for (int b = 0; b < n_seg; ++b) {
+      const Seg& g = segs[b];
+      if (g.m <= 0) continue;
+      D2C_TIMED(c, side, D2C_PROF_ATTN_AVG, 0.0,
+                launch_attention_avg(dt, q + (size_t)g.off * dq * ts, g.k_cache, lse + (size_t)D.n_heads * g.off, g.m,
+                                     g.L, D.n_heads, D.n_kv_heads, D.head_dim, abar, c->avg_part, c->avg_part_floats,
+                                     side));
+      if (g.roll_out)
+        D2C_TIMED(c, side, D2C_PROF_ROLLOUT, 0.0,
+                  launch_rollout(abar, g.roll_in, g.roll_out, g.idx, g.m, g.L, layer == 0, side));
+    }
   }
-  if ((rc = project(c, c->attn_o, dq, c->wo[layer], m, d, dq, &pl, &stride, st)) != D2C_OK) return rc;
+  if ((rc = project(c, c->attn_o, dq, c->wo[layer], M, d, dq, &pl, &stride, st)) != D2C_OK) return rc;
   D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
-            launch_add_norm(dt, hidden, c->partial, pl.splits, stride, d, m, d, c->ffn_norm[layer], D.rms_eps,
+            launch_add_norm(dt, hidden, c->partial, pl.splits, stride, d, M, d, c->ffn_norm[layer], D.rms_eps,
                             c->a_norm, st));
   if (c->fused_swiglu) {
-    pl = plan_gemm(dt, m, 2 * F, d, true);
+    pl = plan_gemm(dt, M, 2 * F, d, true);
     pl.nt = 1;                                   // the gated epilogue pairs waves, one column tile each
     D2C_TIMED(c, st, D2C_PROF_GEMM, 2.0 * F * d * tsize(c),
-              launch_gemm_swiglu(dt, pl, c->a_norm, d, c->w_gate_up[layer], pre_chunks(c, d), c->act, F, m, d, st));
+              launch_gemm_swiglu(dt, pl, c->a_norm, d, c->w_gate_up[layer], pre_chunks(c, d), c->act, F, M, d, st));
   } else {
-    if ((rc = project(c, c->a_norm, d, c->w_gate_up[layer], m, 2 * F, d, &pl, &stride, st)) != D2C_OK) return rc;
+    if ((rc = project(c, c->a_norm, d, c->w_gate_up[layer], M, 2 * F, d, &pl, &stride, st)) != D2C_OK) return rc;
     D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
-              launch_swiglu(dt, c->partial, pl.splits, stride, 2 * F, m, F, c->act, st));
+              launch_swiglu(dt, c->partial, pl.splits, stride, 2 * F, M, F, c->act, st));
   }
-  if ((rc = project(c, c->act, F, c->w_down[layer], m, d, F, &pl, &stride, st)) != D2C_OK) return rc;
+  if ((rc = project(c, c->act, F, c->w_down[layer], M, d, F, &pl, &stride, st)) != D2C_OK) return rc;
   D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
-            launch_add_norm(dt, hidden, c->partial, pl.splits, stride, d, m, d, next_gain, D.rms_eps,
+            launch_add_norm(dt, hidden, c->partial, pl.splits, stride, d, M, d, next_gain, D.rms_eps,
                             next_gain ? c->a_norm : nullptr, st));
   return D2C_OK;
 }
@@ -249,6 +277,7 @@ int d2c_init(const d2c_dims* dims, const d2c_weights* w, d2c_ctx** out) {
   if (D.d_model % e || D.d_ffn % e || (D.n_heads * D.head_dim) % e)
     return fail(nullptr, D2C_ESHAPE, "d_model, d_ffn and n_heads*head_dim must be multiples of 16 bytes of T");
   if (D.max_seq > select_max_len()) return fail(nullptr, D2C_ESHAPE, "max_seq exceeds the selection kernel's limit");
+  if (D.max_batch < 0 || D.max_batch > 64) return fail(nullptr, D2C_EINVAL, "max_batch must be in [0, 64]");
   if (D.mask_id < 0 || D.mask_id >= D.vocab) return fail(nullptr, D2C_EINVAL, "mask_id outside the vocabulary");
   if (!w->tok_emb || !w->final_norm || !w->lm_head || !w->attn_norm || !w->wqkv || !w->wo || !w->ffn_norm ||
       !w->w_gate_up || !w->w_down)
@@ -271,12 +300,15 @@ int d2c_init(const d2c_dims* dims, const d2c_weights* w, d2c_ctx** out) {
   auto bail = [&](int code) { std::string m = c->err; d2c_destroy(c); g_init_err = m; return code; };
   if (hipGetDevice(&c->device) != hipSuccess) return bail(fail(c, D2C_EHIP, "hipGetDevice failed"));
 
-  const size_t ts = tsize(c), Lm = (size_t)D.max_seq, d = (size_t)D.d_model, dq = (size_t)d_q(c), F = (size_t)D.d_ffn;
+  c->max_batch = std::max(1, (int)D.max_batch);
+  c->max_rows = (size_t)D.max_seq * c->max_batch;
+  const size_t ts = tsize(c), Lm = (size_t)D.max_seq, Lr = c->max_rows, d = (size_t)D.d_model, dq = (size_t)d_q(c),
+               F = (size_t)D.d_ffn;
   // largest split-partial footprint over every row count the context can see
   const int shapes[4][2] = {{d_q(c) + 2 * d_kv(c), D.d_model}, {D.d_model, d_q(c)}, {2 * D.d_ffn, D.d_model},
                             {D.d_model, D.d_ffn}};
   size_t pf = 0;
-  for (int m = 1; m <= D.max_seq; ++m)
+  for (int m = 1; m <= (int)Lr; ++m)
     for (auto& s : shapes) {
       // up to 128 rows leave room for the largest split count; beyond that the planner's choice is taken
       GemmPlan pl = plan_gemm(D.dtype, m, s[0], s[1]);
@@ -286,14 +318,16 @@ int d2c_init(const d2c_dims* dims, const d2c_weights* w, d2c_ctx** out) {
   c->head_rows = (int)std::min<size_t>(Lm, 256);
   c->attn_part_floats = attention_scratch_floats(D.dtype, D.max_seq, D.max_seq, D.n_heads, D.head_dim);
   c->avg_part_floats = attention_avg_scratch_floats(D.dtype, D.max_seq, D.max_seq, D.n_heads);
-  if ((rc = ws_alloc(c, &c->hidden, Lm * d * 4)) || (rc = ws_alloc(c, &c->a_norm, Lm * d * ts)) ||
-      (rc = ws_alloc(c, &c->q, (size_t)D.n_layers * Lm * dq * ts)) || (rc = ws_alloc(c, &c->attn_o, Lm * dq * ts)) ||
-      (rc = ws_alloc(c, &c->act, Lm * F * ts)) ||
-      (rc = ws_alloc(c, &c->lse, (size_t)D.n_layers * D.n_heads * Lm * 4)) ||
+  c->roll.assign(2 * (size_t)c->max_batch, nullptr);
+  for (auto& rp : c->roll)
+    if ((rc = ws_alloc(c, &rp, Lm * Lm * 4))) return bail(rc);
+  if ((rc = ws_alloc(c, &c->hidden, Lr * d * 4)) || (rc = ws_alloc(c, &c->a_norm, Lr * d * ts)) ||
+      (rc = ws_alloc(c, &c->q, (size_t)D.n_layers * Lr * dq * ts)) || (rc = ws_alloc(c, &c->attn_o, Lr * dq * ts)) ||
+      (rc = ws_alloc(c, &c->act, Lr * F * ts)) ||
+      (rc = ws_alloc(c, &c->lse, (size_t)D.n_layers * D.n_heads * Lr * 4)) ||
       (rc = ws_alloc(c, &c->attn_part, std::max<size_t>(1, c->attn_part_floats) * 4)) ||
       (rc = ws_alloc(c, &c->avg_part, std::max<size_t>(1, c->avg_part_floats) * 4)) ||
       (rc = ws_alloc(c, &c->partial, pf * 4)) || (rc = ws_alloc(c, &c->abar, Lm * Lm * 4)) ||
-      (rc = ws_alloc(c, &c->roll[0], Lm * Lm * 4)) || (rc = ws_alloc(c, &c->roll[1], Lm * Lm * 4)) ||
       (rc = ws_alloc(c, &c->head_a, (size_t)c->head_rows * d * ts)) ||
       (rc = ws_alloc(c, &c->logits, (size_t)c->head_rows * D.vocab * 4)) ||
       (rc = ws_alloc(c, &c->conf_part, confidence_scratch_floats(D.max_seq) * 4)) ||
@@ -456,8 +490,8 @@ int d2c_refresh_layer(d2c_ctx* c, int32_t layer, float* hidden, const int32_t* i
   if ((attn_avg == nullptr) != (rollout == nullptr))
     return fail(c, D2C_EINVAL, "attn_avg and rollout must both be given or both be null");
   hipStream_t st = (hipStream_t)stream;
-  rc = layer_impl(c, layer, hidden, idx, m, k_cache, v_cache, L, attn_avg, rollout, rollout ? c->roll[0] : nullptr,
-                  false, nullptr, st, st);
+  const Seg seg{idx, m, 0, k_cache, v_cache, L, rollout, rollout ? c->roll[0] : nullptr};
+  rc = layer_impl(c, layer, hidden, &seg, 1, m, attn_avg, false, nullptr, st, st);
   if (rc) return rc;
   if (rollout) D2C_HIP(c, launch_copy_f32(rollout, c->roll[0], (size_t)m * L, st));
   return D2C_OK;
@@ -536,55 +570,118 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
   hipStream_t side = tunables().side_stream ? c->side : st;
   const int dt = D.dtype, d = D.d_model;
   const size_t ts = tsize(c), cache_layer = (size_t)d_kv(c) * ts;
-  for (int b = 0; b < batch; ++b) {
-    d2c_seq_state& s = seqs[b];
-    int32_t* ch = c->counts_host + (size_t)b * D2C_N_COUNTS;
-    if (s.n_masked == 0) { ch[D2C_CNT_S] = -1; continue; }
-    const int m = s.n_s, L = s.L;
-    float* roll_final = nullptr;
-    if (m > 0) {
-      D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
-                launch_embed_norm(dt, c->tok_emb, s.tokens, s.s_idx, m, d, c->attn_norm[0], D.rms_eps, c->hidden,
-                                  c->a_norm, st));
-      const int roll_layers = p->rollout_layers > 0 ? std::min(p->rollout_layers, D.n_layers) : D.n_layers;
+  const int roll_layers = p->rollout_layers > 0 ? std::min(p->rollout_layers, D.n_layers) : D.n_layers;
+  // sequences are taken in groups of up to max_batch; the rows of a group are projected together
+  std::vector<int> group;                       // indices into seqs
+  std::vector<Seg> segs;
+  for (int b0 = 0; b0 < batch;) {
+    group.clear();
+    int M = 0;
+    while (b0 < batch && (int)group.size() < c->max_batch) {
+      d2c_seq_state& s = seqs[b0];
+      if (s.n_masked == 0) {
+        c->counts_host[(size_t)b0 * D2C_N_COUNTS + D2C_CNT_S] = -1;      // finished: skipped
+      } else {
+        group.push_back(b0);
+        M += s.n_s;
+      }
+      ++b0;
+    }
+    if (group.empty()) continue;
+    const int n_seg = (int)group.size();
+    segs.assign(n_seg, Seg{});
+    for (int i = 0, off = 0; i < n_seg; ++i) {
+      const d2c_seq_state& s = seqs[group[i]];
+      segs[i].idx = s.s_idx;
+      segs[i].m = s.n_s;
+      segs[i].off = off;
+      segs[i].L = s.L;
+      off += s.n_s;
+    }
+    if (M > 0) {
+      for (int i = 0; i < n_seg; ++i) {
+        const d2c_seq_state& s = seqs[group[i]];
+        if (segs[i].m > 0)
+          D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
+                    launch_embed_norm(dt, c->tok_emb, s.tokens, s.s_idx, segs[i].m, d, c->attn_norm[0], D.rms_eps,
+                                      c->hidden + (size_t)segs[i].off * d,
+                                      (char*)c->a_norm + (size_t)segs[i].off * d * ts, st));
+      }
       for (int l = 0; l < D.n_layers; ++l) {
-        char* kc = (char*)s.k_cache + (size_t)l * L * cache_layer;
-        char* vc = (char*)s.v_cache + (size_t)l * L * cache_layer;
         const bool in_rollout = l < roll_layers;     // later layers skip the head average altogether
-        rc = layer_impl(c, l, c->hidden, s.s_idx, m, kc, vc, L, in_rollout ? c->abar : nullptr, c->roll[l & 1],
-                        in_rollout ? c->roll[(l + 1) & 1] : nullptr, true,
+        for (int i = 0; i < n_seg; ++i) {
+          const d2c_seq_state& s = seqs[group[i]];
+          segs[i].k_cache = (char*)s.k_cache + (size_t)l * s.L * cache_layer;
+          segs[i].v_cache = (char*)s.v_cache + (size_t)l * s.L * cache_layer;
+          segs[i].roll_in = c->roll[2 * i + (l & 1)];
+          segs[i].roll_out = in_rollout ? c->roll[2 * i + ((l + 1) & 1)] : nullptr;
+        }
+        rc = layer_impl(c, l, c->hidden, segs.data(), n_seg, M, in_rollout ? c->abar : nullptr, true,
                         l + 1 < D.n_layers ? c->attn_norm[l + 1] : nullptr, st, side);
         if (rc) return rc;
       }
-      roll_final = c->roll[roll_layers & 1];
       if (side != st) {                       // join: the influence scores need the last rollout update
         D2C_HIP(c, hipEventRecord(c->side_done, side));
         D2C_HIP(c, hipStreamWaitEvent(st, c->side_done, 0));
       }
-      if (s.hidden_out)
-        D2C_HIP(c, hipMemcpyAsync(s.hidden_out, c->hidden, (size_t)m * d * 4, hipMemcpyDeviceToDevice, st));
     }
-    D2C_TIMED(c, st, D2C_PROF_ROLLOUT, 0.0, launch_influence(roll_final, s.s_idx, m, L, s.influence, st));
-    // Eq. 1 on the rows of S_t that are still masked, head_rows rows at a time
-    for (int r0 = 0; r0 < s.n_rows; r0 += c->head_rows) {
-      const int nr = std::min(c->head_rows, s.n_rows - r0);
-      D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
-                launch_gather_norm(dt, c->hidden, s.s_rows + r0, nr, d, c->final_norm, D.rms_eps, c->head_a, st));
+    for (int i = 0; i < n_seg; ++i) {
+      d2c_seq_state& s = seqs[group[i]];
+      const float* hid = c->hidden + (size_t)segs[i].off * d;
+      if (segs[i].m > 0 && s.hidden_out)
+        D2C_HIP(c, hipMemcpyAsync(s.hidden_out, hid, (size_t)segs[i].m * d * 4, hipMemcpyDeviceToDevice, st));
+      D2C_TIMED(c, st, D2C_PROF_ROLLOUT, 0.0,
+                launch_influence(segs[i].m > 0 ? c->roll[2 * i + (roll_layers & 1)] : nullptr, s.s_idx, segs[i].m,
+                                 s.L, s.influence, st));
+    }
+    // Eq. 1 on the rows of S_t that are still masked: the masked rows of the whole group go through the
+    // LM head together, head_rows rows at a time; a piece = rows [r0, r0 + nr) of one sequence's list
+    struct Piece { int seg, r0, nr, at; };
+    std::vector<Piece> pieces;
+    int fill = 0;
+    auto flush = [&]() -> int {
+      if (fill == 0) return D2C_OK;
       GemmPlan pl;
       size_t stride;
-      if ((rc = project(c, c->head_a, d, c->lm_head, nr, D.vocab, d, &pl, &stride, st, true, c->logits))) return rc;
-      D2C_TIMED(c, st, D2C_PROF_SELECT, 0.0,
-                launch_confidence(c->logits, s.s_rows + r0, s.s_idx, nr, D.vocab, s.conf, s.pred, c->conf_part, st));
-      if (s.logits_out)
-        D2C_HIP(c, hipMemcpyAsync(s.logits_out + (size_t)r0 * D.vocab, c->logits, (size_t)nr * D.vocab * 4,
-                                  hipMemcpyDeviceToDevice, st));
+      int rc2 = project(c, c->head_a, d, c->lm_head, fill, D.vocab, d, &pl, &stride, st, true, c->logits);
+      if (rc2) return rc2;
+      for (const Piece& pc : pieces) {
+        d2c_seq_state& s = seqs[group[pc.seg]];
+        const float* lg = c->logits + (size_t)pc.at * D.vocab;
+        D2C_TIMED(c, st, D2C_PROF_SELECT, 0.0,
+                  launch_confidence(lg, s.s_rows + pc.r0, s.s_idx, pc.nr, D.vocab, s.conf, s.pred, c->conf_part, st));
+        if (s.logits_out)
+          D2C_HIP(c, hipMemcpyAsync(s.logits_out + (size_t)pc.r0 * D.vocab, lg, (size_t)pc.nr * D.vocab * 4,
+                                    hipMemcpyDeviceToDevice, st));
+      }
+      pieces.clear();
+      fill = 0;
+      return D2C_OK;
+    };
+    for (int i = 0; i < n_seg; ++i) {
+      const d2c_seq_state& s = seqs[group[i]];
+      for (int r0 = 0; r0 < s.n_rows;) {
+        const int nr = std::min(c->head_rows - fill, s.n_rows - r0);
+        D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
+                  launch_gather_norm(dt, c->hidden + (size_t)segs[i].off * d, s.s_rows + r0, nr, d, c->final_norm,
+                                     D.rms_eps, (char*)c->head_a + (size_t)fill * d * ts, st));
+        pieces.push_back(Piece{i, r0, nr, fill});
+        fill += nr;
+        r0 += nr;
+        if (fill == c->head_rows && (rc = flush())) return rc;
+      }
     }
-    SelectArgs a{p->sigma, p->k, p->p, p->block_len, p->n_unmask, p->cand_mode, p->threshold, p->conf_decode,
-                 s.tokens, s.is_masked, L,
-                 s.prompt_len, s.conf, s.pred, s.influence, s.mstar, s.u_set, s.decode_idx, s.s_idx, s.s_rows,
-                 s.counts, s.score};
-    D2C_TIMED(c, st, D2C_PROF_SELECT, 0.0, launch_select(a, st));
-    D2C_HIP(c, hipMemcpyAsync(ch, s.counts, sizeof(int32_t) * D2C_N_COUNTS, hipMemcpyDeviceToHost, st));
+    if ((rc = flush())) return rc;
+    for (int i = 0; i < n_seg; ++i) {
+      d2c_seq_state& s = seqs[group[i]];
+      SelectArgs a{p->sigma, p->k, p->p, p->block_len, p->n_unmask, p->cand_mode, p->threshold, p->conf_decode,
+                   s.tokens, s.is_masked, s.L,
+                   s.prompt_len, s.conf, s.pred, s.influence, s.mstar, s.u_set, s.decode_idx, s.s_idx, s.s_rows,
+                   s.counts, s.score};
+      D2C_TIMED(c, st, D2C_PROF_SELECT, 0.0, launch_select(a, st));
+      D2C_HIP(c, hipMemcpyAsync(c->counts_host + (size_t)group[i] * D2C_N_COUNTS, s.counts,
+                                sizeof(int32_t) * D2C_N_COUNTS, hipMemcpyDeviceToHost, st));
+    }
   }
   D2C_HIP(c, hipStreamSynchronize(st));
   for (int b = 0; b < batch; ++b) {

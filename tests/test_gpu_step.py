@@ -246,6 +246,41 @@ def test_step_batch_of_ragged_sequences(B):
     ctx.close()
 
 
+def test_step_grouped_projections_match_separate_calls(B):
+    """max_batch = 3: the rows of three ragged sequences share the projection launches.  The split plan of
+    a projection depends on the row count, so the floats may differ from separate calls in the last bits:
+    sets must be identical (fp32 model with widened weights: no near-ties), floats within the fp32 bar."""
+    wd = W.DIMS["C1"]
+    mdl = W.model_weights(wd, 3)
+    for lw in mdl["layers"]:
+        for name in ("wqkv", "wo", "w_gate_up", "w_down"):
+            lw[name] = lw[name] * np.float32(4.0)
+    sus = [W.DecodeSetup(24, 32, 16, 1, k=8, p=0.5), W.DecodeSetup(64, 48, 16, 1, k=8, p=0.5),
+           W.DecodeSetup(40, 16, 16, 1, k=8, p=0.5)]
+    gp = B.make_params(10.0, 8, 0.5, 16, 1, 0)
+    ctx_g = B.Context(wd, mdl, 112, max_batch=3)
+    ctx_1 = B.Context(wd, mdl, 112)
+    grouped, single = [], []
+    for b, su in enumerate(sus):
+        y0, m0 = W.initial_sequence(wd, su, 11, seq=b)
+        grouped.append(B.Sequence_(ctx_g, y0, m0, su.prompt_len))
+        single.append(B.Sequence_(ctx_1, y0, m0, su.prompt_len))
+    for t in range(10):
+        say(f"grouped d2c_step t={t}")
+        ctx_g.d2c_step(gp, grouped)
+        for q in single:
+            ctx_1.d2c_step(gp, [q])
+        for a, b in zip(grouped, single):
+            assert (a.n_s, a.n_rows, a.n_masked) == (b.n_s, b.n_rows, b.n_masked)
+            assert torch.equal(a.s_idx[: a.n_s], b.s_idx[: b.n_s])
+            assert torch.equal(a.tokens, b.tokens) and torch.equal(a.is_masked, b.is_masked)
+            assert torch.equal(a.pred, b.pred)
+            for name in ("k_cache", "v_cache", "conf", "influence"):
+                assert rel_l2(host(getattr(a, name)), host(getattr(b, name))) < TOL["f32"], name
+    ctx_g.close()
+    ctx_1.close()
+
+
 def test_step_llada_shape_reduced_depth(B):
     """LLaDA-8B geometry at full width and full vocabulary, 2 of the 32 layers: step 0 (all 512 rows)
     and two d2Cache steps, teacher-forced."""
