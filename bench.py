@@ -7,7 +7,11 @@ A "step" is one d2c_step: partial forward of the selected rows through all 32
 layers with rollout, LM head + Eq. 1 on the masked rows, two-stage selection and
 unmasking.  Step 0 (all 512 rows) fills the caches before the clock starts.
 
-Prints one JSON line; see the design doc for how each field is measured.
+Prints one JSON line.  value = timed steps / wall time between two device synchronisations;
+roofline = algorithmic weight bytes of the projection launches / their HIP-event durations
+(a second pass over the same steps with an event pair around every launch), against 8 TB/s;
+full_recompute = the same engine with every row selected; cpu_baseline = the CPU oracle on a
+bounded sample of the same workload.  --workload C4 / C5 / C2 run the other configurations.
 """
 import argparse
 import json
@@ -164,8 +168,9 @@ def main():
     ap.add_argument("--no-vanilla", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus %d is not supported (the path shards by sequence, "
-              "see DESIGN.md)" % args.gpus, file=sys.stderr)
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported (sequences are independent, so "
+              "the path would shard by sequence with replicated weights and no exchange)" % args.gpus,
+              file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
