@@ -278,3 +278,33 @@ def test_rollout_over_first_layers_only():
     first2 = O.rollout(abars[:2], S, L)
     assert not np.allclose(full, first2)
     np.testing.assert_allclose(first2.sum(axis=1), 1.0, atol=1e-14)
+
+
+def _paper_defaults():
+    import os
+    vals = {}
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_defaults.txt")
+    for line in open(path):
+        line = line.split("#", 1)[0].split()
+        if len(line) == 2:
+            vals[line[0]] = float(line[1])
+    return vals
+
+
+def test_defaults_are_the_values_the_paper_states():
+    """sigma, k, p, block size and the parallel-decoding threshold as the paper's text gives them
+    (tests/golden/paper_defaults.txt, each with its passage): the oracle's defaults and the two
+    model-shaped benchmark workloads use exactly these."""
+    from paper_2509_23094_amd import workloads as W
+    g = _paper_defaults()
+    assert set(g) == {"sigma", "k", "p", "block_len", "threshold"}
+    d = O.Params()
+    assert (d.sigma, d.k, d.p, d.block_len) == (g["sigma"], g["k"], g["p"], g["block_len"])
+    for name in ("C3", "C4"):
+        su = W.SETUP[name]
+        assert (su.sigma, su.k, su.p, su.block_len) == (g["sigma"], g["k"], g["p"], g["block_len"])
+    assert (W.SETUP["C5"].sigma, W.SETUP["C5"].k, W.SETUP["C5"].p) == (g["sigma"], g["k"], g["p"])
+    # the threshold only enters through Params.threshold: parallel decoding at the paper's value unmasks
+    # exactly the candidates whose confidence exceeds it
+    conf = np.array([0.95, 0.5, 0.91, 0.9, 0.2], np.float32)
+    assert np.array_equal(np.flatnonzero(conf > np.float32(g["threshold"])), [0, 2])
