@@ -542,11 +542,17 @@ hipError_t launch_avg(const void* q, const void* k_cache, const float* lse, int 
 
 }  // namespace
 
-size_t attention_tiled_scratch_floats(int max_m, int L, int n_heads, int head_dim) {
+// Worst case over every (m <= max_m, L <= max_L): the split count depends on the number of 64-key blocks
+// and shorter sequences can be split as often as longer ones, so both are scanned (L at block boundaries).
+size_t attention_tiled_scratch_floats(int max_m, int max_L, int n_heads, int head_dim) {
   size_t worst = 0;
-  for (int m = 1; m <= max_m; ++m) {
-    const FwdPlan p = plan_fwd(m, L, n_heads);
-    if (p.n_splits > 1) worst = std::max(worst, (size_t)p.n_splits * n_heads * m * (head_dim + 2));
+  for (int L = kBlockKeys;; L += kBlockKeys) {
+    const int Lc = std::min(L, max_L);
+    for (int m = 1; m <= max_m; ++m) {
+      const FwdPlan p = plan_fwd(m, Lc, n_heads);
+      if (p.n_splits > 1) worst = std::max(worst, (size_t)p.n_splits * n_heads * m * (head_dim + 2));
+    }
+    if (L >= max_L) break;
   }
   return worst;
 }
@@ -561,11 +567,17 @@ hipError_t launch_attention_tiled_fwd(const void* q, const void* k_cache, const 
   return hipErrorInvalidValue;
 }
 
-size_t attention_tiled_avg_scratch_floats(int max_m, int L, int n_heads) {
+// Worst case over every (m <= max_m, L <= max_L): a short sequence has few key tiles and therefore more
+// head groups, so the product groups * m * L does not peak at max_L; L is scanned at tile boundaries.
+size_t attention_tiled_avg_scratch_floats(int max_m, int max_L, int n_heads) {
   size_t worst = 0;
-  for (int m = 1; m <= max_m; ++m) {
-    const AvgPlan p = plan_avg(m, L, n_heads);
-    if (p.groups > 1) worst = std::max(worst, (size_t)p.groups * m * L);
+  for (int L = 32;; L += 32) {
+    const int Lc = std::min(L, max_L);
+    for (int m = 1; m <= max_m; ++m) {
+      const AvgPlan p = plan_avg(m, Lc, n_heads);
+      if (p.groups > 1) worst = std::max(worst, (size_t)p.groups * m * Lc);
+    }
+    if (L >= max_L) break;
   }
   return worst;
 }

@@ -96,11 +96,11 @@ hipError_t launch_attention_avg(int dtype, const void* q, const void* k_cache, c
                                 size_t scratch_floats, hipStream_t st);
 
 // the bf16 kernels for many query rows (K/V blocks staged through LDS, optional key split + merge)
-size_t attention_tiled_scratch_floats(int max_m, int L, int n_heads, int head_dim);
+size_t attention_tiled_scratch_floats(int max_m, int max_L, int n_heads, int head_dim);
 hipError_t launch_attention_tiled_fwd(const void* q, const void* k_cache, const void* v_cache, int m, int L,
                                       int n_heads, int n_kv_heads, int head_dim, void* out, float* lse,
                                       float* scratch, size_t scratch_floats, hipStream_t st);
-size_t attention_tiled_avg_scratch_floats(int max_m, int L, int n_heads);
+size_t attention_tiled_avg_scratch_floats(int max_m, int max_L, int n_heads);
 hipError_t launch_attention_tiled_avg(const void* q, const void* k_cache, const float* lse, int m, int L,
                                       int n_heads, int n_kv_heads, int head_dim, float* attn_avg, float* scratch,
                                       size_t scratch_floats, hipStream_t st);

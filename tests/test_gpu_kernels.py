@@ -89,9 +89,20 @@ def test_attention_parity(B, dtype, H, Hkv, dh, L, m, kernels):
 ATTN_TILED_MIN_M_DEFAULT = 64
 
 
-def _attention_parity(B, dtype, H, Hkv, dh, L, m):
+def test_attention_short_sequence_in_a_long_context(B):
+    """A context sized for 2048 positions serving L = 256: the short sequence is split into more head groups
+    and key ranges than the longest one, so the scratch buffers must be sized over every L, not max_seq."""
+    say("attention L=256 m=200 in a max_seq=2048 context")
+    B.d2c_set_tunable("attn_tiled_min_m", 1)
+    try:
+        _attention_parity(B, "bf16", 8, 8, 128, 256, 200, max_seq=2048)
+    finally:
+        B.d2c_set_tunable("attn_tiled_min_m", ATTN_TILED_MIN_M_DEFAULT)
+
+
+def _attention_parity(B, dtype, H, Hkv, dh, L, m, max_seq=None):
     wd = W.ModelDims(1, H * dh, H, Hkv, dh, 64, 64, dtype=dtype)
-    ctx, dims, _ = _ctx_for(B, wd, max_seq=L)
+    ctx, dims, _ = _ctx_for(B, wd, max_seq=max_seq or L)
     case = W.attention_case(1, H, Hkv, dh, L, m, dtype=dtype)
     tdt = B.torch_dtype(dtype)
     q = B.to_device(case["q"], dtype)
