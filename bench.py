@@ -164,6 +164,9 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run five plain 256 MiB device copies (known size, for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE) and exit")
+    ap.add_argument("--rollout-layers", type=int, default=0,
+                    help="attention rollout over the first R layers only (the paper's lightweight variant, "
+                         "R = 5 there); 0 = all layers, the metric's setting")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-vanilla", action="store_true")
     args = ap.parse_args()
@@ -203,7 +206,7 @@ def main():
 
     mdl = device_model(W, dims, 0, torch)
     ctx = B.Context(dims, mdl, su.seq_len, device_weights=True, max_batch=su.batch)
-    prm = B.make_params(su.sigma, su.k, su.p, su.block_len, su.n_unmask, 0)
+    prm = B.make_params(su.sigma, su.k, su.p, su.block_len, su.n_unmask, 0, rollout_layers=args.rollout_layers)
 
     def run_steps(seqs, n, collect=None):
         for _ in range(n):

@@ -43,8 +43,14 @@ struct d2c_ctx {
   float* avg_part = nullptr;    // per-head-group partials of the head average (used on the side stream)
   float* partial = nullptr;     // split partials of the current projection
   size_t partial_floats = 0;
-  float* abar = nullptr;        // [max_seq, max_seq]
-  std::vector<float*> roll;     // 2 per batch slot (ping-pong over the layers), each [max_seq, max_seq]
+  float* roll = nullptr;        // d2c_refresh_layer: the rollout block after the layer, [max_seq, max_seq]
+  // d2c_step keeps every layer's head average (per batch slot: [n_layers][max_seq * max_seq]) and turns
+  // them into the influence scores by a row-vector chain after the last layer
+  float* abar_all = nullptr;
+  // per-head attention rows of the few-row attention launches, [max_batch][n_layers][probs_floats]
+  float* probs_all = nullptr;
+  float* chain_u = nullptr;     // [n_layers, max_seq]: the chain's per-layer vectors (one sequence at a time)
+  size_t probs_floats = 0;
   int max_batch = 1;            // sequences whose rows d2c_step projects together
   size_t max_rows = 0;          // max_seq * max_batch: rows the row-count-sized buffers hold
   void* head_a = nullptr;       // T [head_rows, d]
@@ -161,6 +167,9 @@ struct Seg {
   int m, off;
   void *k_cache, *v_cache;      // this layer's cache of the sequence
   int L;
+  float* abar;                  // [m, L] out: head average of this layer (null = not wanted)
+  float* probs;                 // [H, m, L] out: per-head attention rows written by the attention launch
+                                // itself (null = not wanted; only where attention_fwd_emits_probs)
   const float* roll_in;         // rollout block before this layer (ignored at layer 0)
   float* roll_out;              // rollout block after it; null = no rollout update
 };
@@ -169,11 +178,11 @@ struct Seg {
 // (the weights are streamed once for the whole batch); RoPE + cache update, attention, the head average and
 // the rollout run per sequence on its slice.  a_ready: ctx->a_norm already holds RMSNorm(hidden) *
 // attn_norm[layer].  next_gain: when non-null the last kernel also leaves RMSNorm(hidden) * next_gain in
-// ctx->a_norm.  abar: scratch [m, L] for the head average of one sequence at a time (null = none wanted).
+// ctx->a_norm.
 // side: the stream the head average and the rollout update run on; when it differs from st they are
 // ordered after this layer's attention by ctx->fwd_done[layer] and the caller joins them later.
-int layer_impl(d2c_ctx* c, int layer, float* hidden, const Seg* segs, int n_seg, int M, float* abar, bool a_ready,
-               const float* next_gain, hipStream_t st, hipStream_t side) {
+int layer_impl(d2c_ctx* c, int layer, float* hidden, const Seg* segs, int n_seg, int M, bool a_ready,
+               const float* next_gain, hipStream_t st, hipStream_t side, bool record_fwd = false) {
   const d2c_dims& D = c->dims;
   const int dt = D.dtype, d = D.d_model, dq = d_q(c), dkv = d_kv(c), F = D.d_ffn;
   const size_t ts = tsize(c);
@@ -198,23 +207,26 @@ int layer_impl(d2c_ctx* c, int layer, float* hidden, const Seg* segs, int n_seg,
     D2C_TIMED(c, st, D2C_PROF_ATTENTION, 2.0 * g.L * dkv * ts,
               launch_attention_fwd(dt, qb, g.k_cache, g.v_cache, g.m, g.L, D.n_heads, D.n_kv_heads, D.head_dim,
                                    (char*)c->attn_o + (size_t)g.off * dq * ts, lse + (size_t)D.n_heads * g.off,
-                                   c->attn_part, c->attn_part_floats, st));
+                                   c->attn_part, c->attn_part_floats, st, g.probs));
   }
-  if (abar) {
+  bool any_abar = false;
+  for (int b = 0; b < n_seg; ++b) any_abar = any_abar || (segs[b].m > 0 && segs[b].abar);
+  if (record_fwd && !any_abar && side != st) D2C_HIP(c, hipEventRecord(c->fwd_done[layer], st));
+  if (any_abar) {
     if (side != st) {
       D2C_HIP(c, hipEventRecord(c->fwd_done[layer], st));
       D2C_HIP(c, hipStreamWaitEvent(side, c->fwd_done[layer], 0));
     }
     for (int b = 0; b < n_seg; ++b) {
       const Seg& g = segs[b];
-      if (g.m <= 0) continue;
+      if (g.m <= 0 || !g.abar) continue;
       D2C_TIMED(c, side, D2C_PROF_ATTN_AVG, 0.0,
                 launch_attention_avg(dt, q + (size_t)g.off * dq * ts, g.k_cache, lse + (size_t)D.n_heads * g.off, g.m,
-                                     g.L, D.n_heads, D.n_kv_heads, D.head_dim, abar, c->avg_part, c->avg_part_floats,
-                                     side));
+                                     g.L, D.n_heads, D.n_kv_heads, D.head_dim, g.abar, c->avg_part,
+                                     c->avg_part_floats, side));
       if (g.roll_out)
         D2C_TIMED(c, side, D2C_PROF_ROLLOUT, 0.0,
-                  launch_rollout(abar, g.roll_in, g.roll_out, g.idx, g.m, g.L, layer == 0, side));
+                  launch_rollout(g.abar, g.roll_in, g.roll_out, g.idx, g.m, g.L, layer == 0, side));
     }
   }
   if ((rc = project(c, c->attn_o, dq, c->wo[layer], M, d, dq, &pl, &stride, st)) != D2C_OK) return rc;
@@ -318,16 +330,20 @@ int d2c_init(const d2c_dims* dims, const d2c_weights* w, d2c_ctx** out) {
   c->head_rows = (int)std::min<size_t>(Lm, 256);
   c->attn_part_floats = attention_scratch_floats(D.dtype, D.max_seq, D.max_seq, D.n_heads, D.head_dim);
   c->avg_part_floats = attention_avg_scratch_floats(D.dtype, D.max_seq, D.max_seq, D.n_heads);
-  c->roll.assign(2 * (size_t)c->max_batch, nullptr);
-  for (auto& rp : c->roll)
-    if ((rc = ws_alloc(c, &rp, Lm * Lm * 4))) return bail(rc);
+  if ((rc = ws_alloc(c, &c->roll, Lm * Lm * 4)) ||
+      (rc = ws_alloc(c, &c->abar_all, (size_t)c->max_batch * D.n_layers * Lm * Lm * 4)))
+    return bail(rc);
+  c->probs_floats = attention_probs_floats(D.dtype, D.n_heads, D.max_seq);
+  if ((rc = ws_alloc(c, &c->probs_all, (size_t)c->max_batch * D.n_layers * c->probs_floats * 4)) ||
+      (rc = ws_alloc(c, &c->chain_u, (size_t)D.n_layers * Lm * 4)))
+    return bail(rc);
   if ((rc = ws_alloc(c, &c->hidden, Lr * d * 4)) || (rc = ws_alloc(c, &c->a_norm, Lr * d * ts)) ||
       (rc = ws_alloc(c, &c->q, (size_t)D.n_layers * Lr * dq * ts)) || (rc = ws_alloc(c, &c->attn_o, Lr * dq * ts)) ||
       (rc = ws_alloc(c, &c->act, Lr * F * ts)) ||
       (rc = ws_alloc(c, &c->lse, (size_t)D.n_layers * D.n_heads * Lr * 4)) ||
       (rc = ws_alloc(c, &c->attn_part, std::max<size_t>(1, c->attn_part_floats) * 4)) ||
       (rc = ws_alloc(c, &c->avg_part, std::max<size_t>(1, c->avg_part_floats) * 4)) ||
-      (rc = ws_alloc(c, &c->partial, pf * 4)) || (rc = ws_alloc(c, &c->abar, Lm * Lm * 4)) ||
+      (rc = ws_alloc(c, &c->partial, pf * 4)) ||
       (rc = ws_alloc(c, &c->head_a, (size_t)c->head_rows * d * ts)) ||
       (rc = ws_alloc(c, &c->logits, (size_t)c->head_rows * D.vocab * 4)) ||
       (rc = ws_alloc(c, &c->conf_part, confidence_scratch_floats(D.max_seq) * 4)) ||
@@ -490,10 +506,10 @@ int d2c_refresh_layer(d2c_ctx* c, int32_t layer, float* hidden, const int32_t* i
   if ((attn_avg == nullptr) != (rollout == nullptr))
     return fail(c, D2C_EINVAL, "attn_avg and rollout must both be given or both be null");
   hipStream_t st = (hipStream_t)stream;
-  const Seg seg{idx, m, 0, k_cache, v_cache, L, rollout, rollout ? c->roll[0] : nullptr};
-  rc = layer_impl(c, layer, hidden, &seg, 1, m, attn_avg, false, nullptr, st, st);
+  const Seg seg{idx, m, 0, k_cache, v_cache, L, attn_avg, nullptr, rollout, rollout ? c->roll : nullptr};
+  rc = layer_impl(c, layer, hidden, &seg, 1, m, false, nullptr, st, st);
   if (rc) return rc;
-  if (rollout) D2C_HIP(c, launch_copy_f32(rollout, c->roll[0], (size_t)m * L, st));
+  if (rollout) D2C_HIP(c, launch_copy_f32(rollout, c->roll, (size_t)m * L, st));
   return D2C_OK;
 }
 
@@ -571,6 +587,11 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
   const int dt = D.dtype, d = D.d_model;
   const size_t ts = tsize(c), cache_layer = (size_t)d_kv(c) * ts;
   const int roll_layers = p->rollout_layers > 0 ? std::min(p->rollout_layers, D.n_layers) : D.n_layers;
+  const size_t abar_stride = (size_t)D.max_seq * D.max_seq;
+  auto abar_slot = [&](int slot, int layer) { return c->abar_all + ((size_t)slot * D.n_layers + layer) * abar_stride; };
+  auto probs_slot = [&](int slot, int layer) {
+    return c->probs_all + ((size_t)slot * D.n_layers + layer) * c->probs_floats;
+  };
   // sequences are taken in groups of up to max_batch; the rows of a group are projected together
   std::vector<int> group;                       // indices into seqs
   std::vector<Seg> segs;
@@ -613,26 +634,41 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
           const d2c_seq_state& s = seqs[group[i]];
           segs[i].k_cache = (char*)s.k_cache + (size_t)l * s.L * cache_layer;
           segs[i].v_cache = (char*)s.v_cache + (size_t)l * s.L * cache_layer;
-          segs[i].roll_in = c->roll[2 * i + (l & 1)];
-          segs[i].roll_out = in_rollout ? c->roll[2 * i + ((l + 1) & 1)] : nullptr;
+          // few rows: the attention launch writes the per-head rows itself and the head means of all layers
+          // are taken in one launch after the last layer; otherwise a second pass per layer on the side stream
+          const bool emits = attention_fwd_emits_probs(dt, segs[i].m, s.L);
+          segs[i].probs = in_rollout && emits ? probs_slot(i, l) : nullptr;
+          segs[i].abar = in_rollout && !emits ? abar_slot(i, l) : nullptr;
+          segs[i].roll_in = nullptr;               // no rollout block here: Eq. 9 comes from the chain below
+          segs[i].roll_out = nullptr;
         }
-        rc = layer_impl(c, l, c->hidden, segs.data(), n_seg, M, in_rollout ? c->abar : nullptr, true,
-                        l + 1 < D.n_layers ? c->attn_norm[l + 1] : nullptr, st, side);
+        rc = layer_impl(c, l, c->hidden, segs.data(), n_seg, M, true,
+                        l + 1 < D.n_layers ? c->attn_norm[l + 1] : nullptr, st, side, l == roll_layers - 1);
         if (rc) return rc;
       }
-      if (side != st) {                       // join: the influence scores need the last rollout update
-        D2C_HIP(c, hipEventRecord(c->side_done, side));
-        D2C_HIP(c, hipStreamWaitEvent(st, c->side_done, 0));
-      }
+      if (side != st) D2C_HIP(c, hipStreamWaitEvent(side, c->fwd_done[roll_layers - 1], 0));
+    }
+    // Eq. 9 per sequence on the side stream, behind the last head average: v = ones, then the layers in
+    // reverse order, one launch per sequence.  It runs beside the last layer's FFN and the LM head.
+    for (int i = 0; i < n_seg; ++i) {
+      d2c_seq_state& s = seqs[group[i]];
+      if (attention_fwd_emits_probs(dt, segs[i].m, s.L))
+        D2C_TIMED(c, side, D2C_PROF_ATTN_AVG, 0.0,
+                  launch_head_mean(probs_slot(i, 0), c->probs_floats, abar_slot(i, 0), abar_stride, roll_layers,
+                                   D.n_heads, segs[i].m, s.L, side));
+      D2C_TIMED(c, side, D2C_PROF_ROLLOUT, 0.0,
+                launch_influence_chain(abar_slot(i, 0), abar_stride, roll_layers, s.s_idx, segs[i].m, s.L,
+                                       c->chain_u, s.influence, side));
+    }
+    if (side != st) {                         // join: the selection needs the influence scores
+      D2C_HIP(c, hipEventRecord(c->side_done, side));
+      D2C_HIP(c, hipStreamWaitEvent(st, c->side_done, 0));
     }
     for (int i = 0; i < n_seg; ++i) {
       d2c_seq_state& s = seqs[group[i]];
       const float* hid = c->hidden + (size_t)segs[i].off * d;
       if (segs[i].m > 0 && s.hidden_out)
         D2C_HIP(c, hipMemcpyAsync(s.hidden_out, hid, (size_t)segs[i].m * d * 4, hipMemcpyDeviceToDevice, st));
-      D2C_TIMED(c, st, D2C_PROF_ROLLOUT, 0.0,
-                launch_influence(segs[i].m > 0 ? c->roll[2 * i + (roll_layers & 1)] : nullptr, s.s_idx, segs[i].m,
-                                 s.L, s.influence, st));
     }
     // Eq. 1 on the rows of S_t that are still masked: the masked rows of the whole group go through the
     // LM head together, head_rows rows at a time; a piece = rows [r0, r0 + nr) of one sequence's list

@@ -18,6 +18,8 @@
 //           heads, recompute S^T and accumulate exp(s - lse) in registers, then add
 //           their partial sums in a fixed order through LDS.
 // fp32 path (small test model only): the same two passes, one workgroup per query row, plain FMA.
+#include <algorithm>
+
 #include "common.cuh"
 #include "internal.h"
 
@@ -58,14 +60,19 @@ __device__ __forceinline__ void load_kv_tile(KvTile<DH>& t, const bf16* __restri
 constexpr int kFwdWaves = 8;
 constexpr int kFwdThreads = kFwdWaves * 64;
 
-template <int DH>
+// KEEP > 0: the wave also keeps the scaled scores of its first 4*KEEP key tiles (all of them when
+// L <= 512*KEEP) and, once the workgroup knows the rows' log-sum-exp, writes the normalised probabilities
+// of this head to probs [H, m, L]: the head average then needs no second pass over Q and K.
+template <int DH, int KEEP>
 __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
     const bf16* __restrict__ q, const bf16* __restrict__ k_cache, const bf16* __restrict__ v_cache, int m, int L,
-    int n_heads, int n_kv_heads, float scale, bf16* __restrict__ out, float* __restrict__ lse) {
+    int n_heads, int n_kv_heads, float scale, bf16* __restrict__ out, float* __restrict__ lse,
+    float* __restrict__ probs) {
   constexpr int NS = DH / 32;     // contraction steps of Q K^T
   constexpr int NB = DH / 64;     // 64-wide head-dim blocks of the output
   __shared__ float o_lds[kFwdWaves][16][DH + 1];
   __shared__ float m_lds[kFwdWaves][16], l_lds[kFwdWaves][16];
+  __shared__ float lse_lds[16];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 15, g = lane >> 4;
@@ -92,7 +99,7 @@ __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
 #pragma unroll
     for (int i = 0; i < 4; ++i) acc[b][i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  auto consume = [&](const KvTile<DH>& t, int key0) {
+  auto consume = [&](const KvTile<DH>& t, int key0, f32x4* keep) {
     f32x4 st = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < NS; ++s) mfma16(st, t.k[s], qf[s]);
@@ -103,6 +110,7 @@ __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
       x[j] = (key0 + 4 * g + j < L) ? st[j] * scale : -INFINITY;
       tmax = fmaxf(tmax, x[j]);
     }
+    if (keep) *keep = f32x4{x[0], x[1], x[2], x[3]};
     tmax = fmaxf(tmax, __shfl_xor(tmax, 16, kWave));
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
     const float m_new = fmaxf(m_run, tmax);
@@ -144,14 +152,30 @@ __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
     const int t = wave + u * kFwdWaves;
     if (t < n_tiles) load_kv_tile<DH>(ring[u], kbase, vbase, kv_pitch, t * 16, L, r, g);
   }
-  for (int t0 = wave; t0 < n_tiles; t0 += 4 * kFwdWaves) {
+  f32x4 kept[KEEP > 0 ? 4 * KEEP : 1];
+  if constexpr (KEEP > 0) {
+    // all of the wave's tiles in 4*KEEP statically indexed slots (the launcher guarantees L <= 512*KEEP)
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int t = t0 + u * kFwdWaves;
-      if (t >= n_tiles) break;
-      consume(ring[u], t * 16);
-      const int tn = t + 4 * kFwdWaves;
-      if (tn < n_tiles) load_kv_tile<DH>(ring[u], kbase, vbase, kv_pitch, tn * 16, L, r, g);
+    for (int it = 0; it < KEEP; ++it)
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int t = wave + (it * 4 + u) * kFwdWaves;
+        if (t < n_tiles) {
+          consume(ring[u], t * 16, &kept[it * 4 + u]);
+          const int tn = t + 4 * kFwdWaves;
+          if (tn < n_tiles) load_kv_tile<DH>(ring[u], kbase, vbase, kv_pitch, tn * 16, L, r, g);
+        }
+      }
+  } else {
+    for (int t0 = wave; t0 < n_tiles; t0 += 4 * kFwdWaves) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int t = t0 + u * kFwdWaves;
+        if (t >= n_tiles) break;
+        consume(ring[u], t * 16, nullptr);
+        const int tn = t + 4 * kFwdWaves;
+        if (tn < n_tiles) load_kv_tile<DH>(ring[u], kbase, vbase, kv_pitch, tn * 16, L, r, g);
+      }
     }
   }
 
@@ -182,11 +206,43 @@ __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
       lsum += l_lds[w][qi] * f;
       osum += o_lds[w][qi][dcol] * f;
     }
+    if (dcol == 0) lse_lds[qi] = mx + __logf(lsum);
     if (q0 + qi < m) {
       out[(size_t)(q0 + qi) * dq + head * DH + dcol] = (bf16)(osum / lsum);
       if (dcol == 0) lse[(size_t)head * m + q0 + qi] = mx + __logf(lsum);
     }
   }
+  if constexpr (KEEP > 0) {
+    __syncthreads();
+    if (q0 + r >= m) return;
+    const float e = lse_lds[r];
+    float* prow = probs + ((size_t)head * m + q0 + r) * L;
+#pragma unroll
+    for (int o = 0; o < 4 * KEEP; ++o) {
+      const int key0 = (wave + o * kFwdWaves) * 16 + 4 * g;
+      if ((L & 3) == 0) {                       // rows start 16-byte aligned: one store per tile
+        if (key0 < L)
+          *reinterpret_cast<f32x4*>(prow + key0) = f32x4{__expf(kept[o][0] - e), __expf(kept[o][1] - e),
+                                                         __expf(kept[o][2] - e), __expf(kept[o][3] - e)};
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (key0 + j < L) prow[key0 + j] = __expf(kept[o][j] - e);    // masked scores are -inf: never stored
+      }
+    }
+  }
+}
+
+// abar[l][i, j] = mean over the heads of probs[l][h][i, j], heads added in order (one thread per element)
+__global__ __launch_bounds__(kThreads) void head_mean_kernel(const float* __restrict__ probs, size_t probs_layer_stride,
+                                                             float* __restrict__ abar, size_t abar_layer_stride,
+                                                             int n_heads, size_t n_elems) {
+  const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= n_elems) return;
+  const float* p = probs + (size_t)blockIdx.y * probs_layer_stride + i;
+  float sum = 0.f;
+  for (int h = 0; h < n_heads; ++h) sum += p[(size_t)h * n_elems];
+  abar[(size_t)blockIdx.y * abar_layer_stride + i] = sum * (1.0f / (float)n_heads);
 }
 
 // Pass 2: one workgroup per (16-query tile, 16-key tile); its 4 waves split the heads (wave w takes
@@ -330,10 +386,18 @@ __global__ __launch_bounds__(kThreads) void attn_avg_f32_kernel(const float* __r
 
 template <int DH>
 hipError_t launch_fwd_bf16(const void* q, const void* k_cache, const void* v_cache, int m, int L, int n_heads,
-                           int n_kv_heads, void* out, float* lse, hipStream_t st) {
+                           int n_kv_heads, void* out, float* lse, float* probs, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)DH);
-  hipLaunchKernelGGL(attn_fwd_bf16_kernel<DH>, dim3((m + 15) / 16, n_heads), dim3(kFwdThreads), 0, st, (const bf16*)q,
-                     (const bf16*)k_cache, (const bf16*)v_cache, m, L, n_heads, n_kv_heads, scale, (bf16*)out, lse);
+  const dim3 grid((m + 15) / 16, n_heads);
+#define D2C_FWD(KEEP_)                                                                                          \
+  hipLaunchKernelGGL((attn_fwd_bf16_kernel<DH, KEEP_>), grid, dim3(kFwdThreads), 0, st, (const bf16*)q,         \
+                     (const bf16*)k_cache, (const bf16*)v_cache, m, L, n_heads, n_kv_heads, scale, (bf16*)out, \
+                     lse, probs)
+  if (!probs) D2C_FWD(0);
+  else if (L <= 512) D2C_FWD(1);
+  else if (L <= 1024) D2C_FWD(2);
+  else return hipErrorInvalidValue;
+#undef D2C_FWD
   return hipGetLastError();
 }
 
@@ -349,21 +413,42 @@ hipError_t launch_avg_bf16(const void* q, const void* k_cache, const float* lse,
 
 }  // namespace
 
+constexpr int kProbsMaxM = 64, kProbsMaxL = 1024;
+
+bool attention_fwd_emits_probs(int dtype, int m, int L) {
+  return dtype == kBF16 && m > 0 && m < tunables().attn_tiled_min_m && m <= kProbsMaxM && L <= kProbsMaxL;
+}
+
+size_t attention_probs_floats(int dtype, int n_heads, int max_L) {
+  return dtype == kBF16 ? (size_t)n_heads * kProbsMaxM * std::min(max_L, kProbsMaxL) : 0;
+}
+
+hipError_t launch_head_mean(const float* probs, size_t probs_layer_stride, float* abar, size_t abar_layer_stride,
+                            int n_layers, int n_heads, int m, int L, hipStream_t st) {
+  if (n_layers <= 0 || m <= 0) return hipSuccess;
+  const size_t n = (size_t)m * L;
+  hipLaunchKernelGGL(head_mean_kernel, dim3((unsigned)((n + kThreads - 1) / kThreads), n_layers), dim3(kThreads), 0, st,
+                     probs, probs_layer_stride, abar, abar_layer_stride, n_heads, n);
+  return hipGetLastError();
+}
+
 size_t attention_scratch_floats(int dtype, int max_m, int max_L, int n_heads, int head_dim) {
   return dtype == kBF16 ? attention_tiled_scratch_floats(max_m, max_L, n_heads, head_dim) : 0;
 }
 
 hipError_t launch_attention_fwd(int dtype, const void* q, const void* k_cache, const void* v_cache, int m, int L,
                                 int n_heads, int n_kv_heads, int head_dim, void* out, float* lse, float* scratch,
-                                size_t scratch_floats, hipStream_t st) {
+                                size_t scratch_floats, hipStream_t st, float* probs) {
   if (m <= 0) return hipSuccess;
   if (L <= 0 || n_heads % n_kv_heads) return hipErrorInvalidValue;
+  if (probs && !attention_fwd_emits_probs(dtype, m, L)) return hipErrorInvalidValue;
   if (dtype == kBF16) {
     if (m >= tunables().attn_tiled_min_m)
       return launch_attention_tiled_fwd(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, head_dim, out, lse, scratch,
                                         scratch_floats, st);
-    if (head_dim == 128) return launch_fwd_bf16<128>(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, st);
-    if (head_dim == 64) return launch_fwd_bf16<64>(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, st);
+    if (head_dim == 128)
+      return launch_fwd_bf16<128>(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, probs, st);
+    if (head_dim == 64) return launch_fwd_bf16<64>(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, probs, st);
     return hipErrorInvalidValue;
   }
   const size_t smem = ((size_t)L + 8) * sizeof(float);

@@ -85,9 +85,16 @@ hipError_t launch_rope_table(float* cos_t, float* sin_t, int max_pos, int head_d
 // fwd: out T [m, H*dh] and the log-sum-exp per (head, row), lse float [H, m]
 // scratch: attention_scratch_floats(...) floats (partials of a split key range), may be null for fp32
 size_t attention_scratch_floats(int dtype, int max_m, int max_L, int n_heads, int head_dim);
+// probs (optional, only where attention_fwd_emits_probs): float [H, m, L], the normalised attention rows of
+// every head, written by the same launch; launch_head_mean turns them into the head average.
+bool attention_fwd_emits_probs(int dtype, int m, int L);
+size_t attention_probs_floats(int dtype, int n_heads, int max_L);      // capacity one (layer, sequence) needs
 hipError_t launch_attention_fwd(int dtype, const void* q, const void* k_cache, const void* v_cache, int m, int L,
                                 int n_heads, int n_kv_heads, int head_dim, void* out, float* lse, float* scratch,
-                                size_t scratch_floats, hipStream_t st);
+                                size_t scratch_floats, hipStream_t st, float* probs = nullptr);
+// abar[l] (at abar + l * abar_layer_stride, [m, L]) = mean over heads of probs[l] (at probs + l * stride, [H, m, L])
+hipError_t launch_head_mean(const float* probs, size_t probs_layer_stride, float* abar, size_t abar_layer_stride,
+                            int n_layers, int n_heads, int m, int L, hipStream_t st);
 // avg: attn_avg float [m, L] = mean over heads of exp(q k / sqrt(dh) - lse); needs fwd's lse
 // scratch: attention_avg_scratch_floats(...) floats (per-head-group partials), may be null for fp32
 size_t attention_avg_scratch_floats(int dtype, int max_m, int max_L, int n_heads);
@@ -110,6 +117,13 @@ hipError_t launch_rollout(const float* attn_avg, const float* c_in, float* c_out
                           bool first, hipStream_t st);
 hipError_t launch_influence(const float* c_block, const int32_t* idx, int m, int L, float* influence,
                             hipStream_t st);
+
+// ---- Eq. 9 as a row-vector chain: c = 1^T W^(n_layers) ... W^(1) with W^(l) built from abar_l (Eq. 6-7).
+// abar: layer l at abar + l * layer_stride, [m, L] floats.  u_scratch: n_layers * m floats.  Two launches (a
+// sequential m x m part in one workgroup, then all columns in parallel); L <= the selection kernel's limit.
+// m == 0 or n_layers == 0: all ones.
+hipError_t launch_influence_chain(const float* abar, size_t layer_stride, int n_layers, const int32_t* idx, int m,
+                                  int L, float* u_scratch, float* influence, hipStream_t st);
 
 // ---- selection
 // Eq. 1 per logits row; the row's position is via ? via[pos[row]] : pos[row]

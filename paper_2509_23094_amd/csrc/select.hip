@@ -151,6 +151,113 @@ __global__ void influence_kernel(const float* __restrict__ c_block, const int32_
   influence[col] = s;
 }
 
+// ------------------------------------------------------------------ Eq. 9 without the rollout matrix
+// c = 1^T C^(N) = 1^T W^(N) W^(N-1) ... W^(1) (Eq. 8-9): multiplying from the LEFT keeps a length-L row
+// vector v instead of the |S| x L block, O(m L) work per layer instead of O(m^2 L), at the price of needing
+// the layers in reverse order, i.e. every layer's A-bar kept until the last one is done.  With rows outside
+// S of W equal to unit vectors and rows i in S equal to (A-bar_i + e_i)/2 (Eq. 6-7):
+//   (v W)_j = ( sum_{i in S} v_i A-bar_ij + ([j not in S] + 1) v_j ) / 2.
+// Only the m entries u = v[S] feed back into later products; a column j outside S just accumulates:
+//   u^(N) = ones;  u^(l-1)_k = ( sum_i u^(l)_i A-bar^(l)[i, S_k] + u^(l)_k ) / 2      (sequential, m x m per layer)
+//   c_j = 1 + sum_l sum_i u^(l)_i A-bar^(l)[i, j] / 2   for j outside S,   c_{S_k} = u^(0)_k  (parallel)
+// so the sequential part touches m^2 numbers per layer and the m L part is one fully parallel launch.
+constexpr int kChainThreads = 1024;
+constexpr int kChainMaxLen = 4096;           // = the selection kernel's length limit
+
+// Sequential part, one workgroup: u through the layers in reverse order; writes U[l][i] = u^(l)_i (the
+// vector entering layer l) for the parallel part and c at the positions of S.  Items of 64 entries of S x
+// one of RG row groups keep all 16 waves busy for short S; fixed summation order.
+__global__ __launch_bounds__(kChainThreads) void chain_rows_kernel(const float* __restrict__ abar,
+                                                                   size_t layer_stride, int n_layers,
+                                                                   const int32_t* __restrict__ idx, int m, int L,
+                                                                   float* __restrict__ U,
+                                                                   float* __restrict__ influence) {
+  __shared__ float u[2][kChainMaxLen];
+  __shared__ float part[kChainMaxLen];                 // [RG][padded m], RG * padded m <= max(padded m, 1024)
+  __shared__ int32_t s_idx[kChainMaxLen];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  for (int i = tid; i < m; i += kChainThreads) {
+    u[0][i] = 1.f;
+    s_idx[i] = idx[i];
+  }
+  __syncthreads();
+  const int n_cb = (m + 63) / 64, mp = n_cb * 64;
+  const int RG = mp < kChainThreads ? kChainThreads / mp : 1;
+  const int n_items = n_cb * RG;
+  int cur = 0;
+  for (int l = n_layers - 1; l >= 0; --l) {
+    const float* a = abar + (size_t)l * layer_stride;
+    const float* uin = u[cur];
+    float* uout = u[cur ^ 1];
+    for (int i = tid; i < m; i += kChainThreads) U[(size_t)l * m + i] = uin[i];
+    for (int item = wave; item < n_items; item += kChainThreads / 64) {
+      const int cb = item % n_cb, rg = item / n_cb;
+      const int k = cb * 64 + lane;
+      const float* acol = a + s_idx[min(k, m - 1)];
+      float acc = 0.f;
+      int i = rg;
+      for (; i + 7 * RG < m; i += 8 * RG) {
+        float x[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) x[t] = acol[(size_t)(i + t * RG) * L];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc = fmaf(uin[i + t * RG], x[t], acc);
+      }
+      for (; i < m; i += RG) acc = fmaf(uin[i], acol[(size_t)i * L], acc);
+      part[rg * mp + k] = acc;
+    }
+    __syncthreads();
+    for (int k = tid; k < m; k += kChainThreads) {
+      float sum = 0.f;
+      for (int rg = 0; rg < RG; ++rg) sum += part[rg * mp + k];
+      uout[k] = 0.5f * (sum + uin[k]);
+    }
+    __syncthreads();
+    cur ^= 1;
+  }
+  for (int k = tid; k < m; k += kChainThreads) influence[s_idx[k]] = u[cur][k];
+}
+
+// Parallel part: 64 columns per workgroup, its 16 waves take the layers round-robin (wave w: layers w,
+// w + 16, ..), a lane owns one column and adds u^(l)_i A-bar^(l)[i, j] over the rows in order with eight
+// loads in flight; the waves' sums are added in wave order.  Columns inside S are left alone.
+__global__ __launch_bounds__(kChainThreads) void chain_cols_kernel(const float* __restrict__ abar,
+                                                                   size_t layer_stride, int n_layers,
+                                                                   const int32_t* __restrict__ idx, int m, int L,
+                                                                   const float* __restrict__ U,
+                                                                   float* __restrict__ influence) {
+  __shared__ float red[kChainThreads / 64][64];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int col = blockIdx.x * 64 + lane;
+  const float* acol = abar + min(col, L - 1);
+  float acc = 0.f;
+  for (int l = wave; l < n_layers; l += kChainThreads / 64) {
+    const float* a = acol + (size_t)l * layer_stride;
+    const float* ul = U + (size_t)l * m;
+    int i = 0;
+    for (; i + 8 <= m; i += 8) {
+      float x[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) x[t] = a[(size_t)(i + t) * L];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) acc = fmaf(ul[i + t], x[t], acc);
+    }
+    for (; i < m; ++i) acc = fmaf(ul[i], a[(size_t)i * L], acc);
+  }
+  red[wave][lane] = acc;
+  __syncthreads();
+  if (wave != 0 || col >= L || find_sorted(idx, m, col) >= 0) return;
+  float sum = 0.f;
+#pragma unroll
+  for (int w = 0; w < kChainThreads / 64; ++w) sum += red[w][lane];
+  influence[col] = 1.f + 0.5f * sum;
+}
+
+__global__ void ones_kernel(float* __restrict__ x, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) x[i] = 1.f;
+}
+
 // ------------------------------------------------------------------ two-stage selection, one workgroup
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
@@ -448,6 +555,22 @@ hipError_t launch_influence(const float* c_block, const int32_t* idx, int m, int
                             hipStream_t st) {
   if (L <= 0) return hipErrorInvalidValue;
   hipLaunchKernelGGL(influence_kernel, dim3((L + 255) / 256), dim3(256), 0, st, c_block, idx, m, L, influence);
+  return hipGetLastError();
+}
+
+hipError_t launch_influence_chain(const float* abar, size_t layer_stride, int n_layers, const int32_t* idx, int m,
+                                  int L, float* u_scratch, float* influence, hipStream_t st) {
+  if (L <= 0 || L > kChainMaxLen || m < 0 || m > L || n_layers < 0) return hipErrorInvalidValue;
+  if (m == 0 || n_layers == 0) {           // nothing was refreshed: C = I, every c_j = 1
+    hipLaunchKernelGGL(ones_kernel, dim3((L + 255) / 256), dim3(256), 0, st, influence, L);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL(chain_rows_kernel, dim3(1), dim3(kChainThreads), 0, st, abar, layer_stride, n_layers, idx, m, L,
+                     u_scratch, influence);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(chain_cols_kernel, dim3((L + 63) / 64), dim3(kChainThreads), 0, st, abar, layer_stride, n_layers,
+                     idx, m, L, u_scratch, influence);
   return hipGetLastError();
 }
 
