@@ -50,6 +50,7 @@ struct d2c_ctx {
   // per-head attention rows of the few-row attention launches, [max_batch][n_layers][probs_floats]
   float* probs_all = nullptr;
   float* chain_u = nullptr;     // [n_layers, max_seq]: the chain's per-layer vectors (one sequence at a time)
+  float* chain_g = nullptr;     // [n_layers, max_seq * max_seq]: the dense m x m blocks of the chain
   size_t probs_floats = 0;
   int max_batch = 1;            // sequences whose rows d2c_step projects together
   size_t max_rows = 0;          // max_seq * max_batch: rows the row-count-sized buffers hold
@@ -335,7 +336,8 @@ int d2c_init(const d2c_dims* dims, const d2c_weights* w, d2c_ctx** out) {
     return bail(rc);
   c->probs_floats = attention_probs_floats(D.dtype, D.n_heads, D.max_seq);
   if ((rc = ws_alloc(c, &c->probs_all, (size_t)c->max_batch * D.n_layers * c->probs_floats * 4)) ||
-      (rc = ws_alloc(c, &c->chain_u, (size_t)D.n_layers * Lm * 4)))
+      (rc = ws_alloc(c, &c->chain_u, (size_t)D.n_layers * Lm * 4)) ||
+      (rc = ws_alloc(c, &c->chain_g, (size_t)D.n_layers * Lm * Lm * 4)))
     return bail(rc);
   if ((rc = ws_alloc(c, &c->hidden, Lr * d * 4)) || (rc = ws_alloc(c, &c->a_norm, Lr * d * ts)) ||
       (rc = ws_alloc(c, &c->q, (size_t)D.n_layers * Lr * dq * ts)) || (rc = ws_alloc(c, &c->attn_o, Lr * dq * ts)) ||
@@ -658,7 +660,7 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
                                    D.n_heads, segs[i].m, s.L, side));
       D2C_TIMED(c, side, D2C_PROF_ROLLOUT, 0.0,
                 launch_influence_chain(abar_slot(i, 0), abar_stride, roll_layers, s.s_idx, segs[i].m, s.L,
-                                       c->chain_u, s.influence, side));
+                                       c->chain_u, c->chain_g, s.influence, side));
     }
     if (side != st) {                         // join: the selection needs the influence scores
       D2C_HIP(c, hipEventRecord(c->side_done, side));

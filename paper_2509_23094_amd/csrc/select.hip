@@ -164,12 +164,23 @@ __global__ void influence_kernel(const float* __restrict__ c_block, const int32_
 constexpr int kChainThreads = 1024;
 constexpr int kChainMaxLen = 4096;           // = the selection kernel's length limit
 
+// G[l][i, k] = abar[l][i, S_k]: the m x m blocks the sequential part reads, made dense first (all layers in
+// one launch) so that the one workgroup that walks the layers reads consecutive floats.
+__global__ __launch_bounds__(256) void chain_gather_kernel(const float* __restrict__ abar, size_t layer_stride,
+                                                           const int32_t* __restrict__ idx, int m, int L,
+                                                           float* __restrict__ G) {
+  const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t mm = (size_t)m * m;
+  if (e >= mm) return;
+  const int i = (int)(e / m), k = (int)(e - (size_t)i * m);
+  G[(size_t)blockIdx.y * mm + e] = abar[(size_t)blockIdx.y * layer_stride + (size_t)i * L + idx[k]];
+}
+
 // Sequential part, one workgroup: u through the layers in reverse order; writes U[l][i] = u^(l)_i (the
 // vector entering layer l) for the parallel part and c at the positions of S.  Items of 64 entries of S x
 // one of RG row groups keep all 16 waves busy for short S; fixed summation order.
-__global__ __launch_bounds__(kChainThreads) void chain_rows_kernel(const float* __restrict__ abar,
-                                                                   size_t layer_stride, int n_layers,
-                                                                   const int32_t* __restrict__ idx, int m, int L,
+__global__ __launch_bounds__(kChainThreads) void chain_rows_kernel(const float* __restrict__ G, int n_layers,
+                                                                   const int32_t* __restrict__ idx, int m,
                                                                    float* __restrict__ U,
                                                                    float* __restrict__ influence) {
   __shared__ float u[2][kChainMaxLen];
@@ -186,24 +197,24 @@ __global__ __launch_bounds__(kChainThreads) void chain_rows_kernel(const float* 
   const int n_items = n_cb * RG;
   int cur = 0;
   for (int l = n_layers - 1; l >= 0; --l) {
-    const float* a = abar + (size_t)l * layer_stride;
+    const float* a = G + (size_t)l * m * m;
     const float* uin = u[cur];
     float* uout = u[cur ^ 1];
     for (int i = tid; i < m; i += kChainThreads) U[(size_t)l * m + i] = uin[i];
     for (int item = wave; item < n_items; item += kChainThreads / 64) {
       const int cb = item % n_cb, rg = item / n_cb;
       const int k = cb * 64 + lane;
-      const float* acol = a + s_idx[min(k, m - 1)];
+      const float* acol = a + min(k, m - 1);
       float acc = 0.f;
       int i = rg;
       for (; i + 7 * RG < m; i += 8 * RG) {
         float x[8];
 #pragma unroll
-        for (int t = 0; t < 8; ++t) x[t] = acol[(size_t)(i + t * RG) * L];
+        for (int t = 0; t < 8; ++t) x[t] = acol[(size_t)(i + t * RG) * m];
 #pragma unroll
         for (int t = 0; t < 8; ++t) acc = fmaf(uin[i + t * RG], x[t], acc);
       }
-      for (; i < m; i += RG) acc = fmaf(uin[i], acol[(size_t)i * L], acc);
+      for (; i < m; i += RG) acc = fmaf(uin[i], acol[(size_t)i * m], acc);
       part[rg * mp + k] = acc;
     }
     __syncthreads();
@@ -559,15 +570,20 @@ hipError_t launch_influence(const float* c_block, const int32_t* idx, int m, int
 }
 
 hipError_t launch_influence_chain(const float* abar, size_t layer_stride, int n_layers, const int32_t* idx, int m,
-                                  int L, float* u_scratch, float* influence, hipStream_t st) {
+                                  int L, float* u_scratch, float* g_scratch, float* influence, hipStream_t st) {
   if (L <= 0 || L > kChainMaxLen || m < 0 || m > L || n_layers < 0) return hipErrorInvalidValue;
   if (m == 0 || n_layers == 0) {           // nothing was refreshed: C = I, every c_j = 1
     hipLaunchKernelGGL(ones_kernel, dim3((L + 255) / 256), dim3(256), 0, st, influence, L);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL(chain_rows_kernel, dim3(1), dim3(kChainThreads), 0, st, abar, layer_stride, n_layers, idx, m, L,
-                     u_scratch, influence);
+  const size_t mm = (size_t)m * m;
+  hipLaunchKernelGGL(chain_gather_kernel, dim3((unsigned)((mm + 255) / 256), n_layers), dim3(256), 0, st, abar,
+                     layer_stride, idx, m, L, g_scratch);
   hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(chain_rows_kernel, dim3(1), dim3(kChainThreads), 0, st, g_scratch, n_layers, idx, m, u_scratch,
+                     influence);
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(chain_cols_kernel, dim3((L + 63) / 64), dim3(kChainThreads), 0, st, abar, layer_stride, n_layers,
                      idx, m, L, u_scratch, influence);
