@@ -413,7 +413,7 @@ hipError_t launch_avg_bf16(const void* q, const void* k_cache, const float* lse,
 
 }  // namespace
 
-constexpr int kProbsMaxM = 64, kProbsMaxL = 1024;
+constexpr int kProbsMaxM = 128, kProbsMaxL = 1024;
 
 bool attention_fwd_emits_probs(int dtype, int m, int L) {
   return dtype == kBF16 && m > 0 && m < tunables().attn_tiled_min_m && m <= kProbsMaxM && L <= kProbsMaxL;

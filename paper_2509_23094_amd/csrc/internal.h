@@ -18,7 +18,7 @@ struct Tunables {
   int gemm_waves = 0;          // waves per workgroup sharing one activation chunk in LDS: 4, 8; 0 = by shape
   bool gemm_preshuffle = true; // d2c_init keeps pre-tiled copies of the projection matrices (costs their size again)
   int gemm_rot = 0;            // start chunk of a workgroup's k walk = (column block * this) % chunks
-  int attn_tiled_min_m = 64;   // bf16 attention: from this many query rows on, the LDS-tiled kernels
+  int attn_tiled_min_m = 96;   // bf16 attention: from this many query rows on, the LDS-tiled kernels
   int attn_max_splits = 8;     // key-range splits of one attention launch (1..8)
   int attn_qt = 0;             // 16-row query tiles per wave in the tiled forward kernel: 1, 2; 0 = by m
   int attn_target_wgs = 256;   // split the key range until the forward grid has this many workgroups

@@ -86,7 +86,7 @@ def test_attention_parity(B, dtype, H, Hkv, dh, L, m, kernels):
         B.d2c_set_tunable("attn_tiled_min_m", ATTN_TILED_MIN_M_DEFAULT)
 
 
-ATTN_TILED_MIN_M_DEFAULT = 64
+ATTN_TILED_MIN_M_DEFAULT = 96
 
 
 def test_attention_short_sequence_in_a_long_context(B):
