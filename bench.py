@@ -57,10 +57,12 @@ def fresh_sequences(B, W, ctx, dims, su, gen):
     return seqs
 
 
-def cpu_baseline(W, dims, su, m_rows, n_logit_rows):
-    """The oracle on this machine's host cores, on a bounded sample of the same workload: one full-width
-    layer on m_rows selected rows, the LM head + Eq. 1 on n_logit_rows rows, rollout and both
-    selections at L = 512; the layer time is scaled by n_layers to a whole step."""
+def cpu_baseline(W, dims, su, m_rows, n_logit_rows, n_steps=2):
+    """The oracle on this machine's host cores, on a bounded sample of the same workload: n_steps whole d2Cache
+    steps at the mean shapes of the timed run (m_rows selected rows, n_logit_rows masked rows), each step =
+    n_layers x (one full-width block on the selected rows + its L x L rollout update) + LM head + Eq. 1 +
+    both selections.  The weights of one layer are reused for every layer (the cost is the same per
+    layer; 16 GB of fp32 weights per layer set would not fit the sample's time), nothing is scaled."""
     import numpy as np
     from oracle import d2cache_oracle as O
     try:
@@ -72,32 +74,39 @@ def cpu_baseline(W, dims, su, m_rows, n_logit_rows):
                 dims.rms_eps, dims.rope_theta)
     L = su.seq_len
     lw = W.layer_weights(dims, 0, 0)
-    head = W.lm_head(dims, 0)
+    head = {"final_norm": np.ones(dims.d_model), "lm_head": W.lm_head(dims, 0)}
     S = W.distinct_sorted_rows(0, L, m_rows)
-    h = W.hidden_rows(0, m_rows, dims.d_model, std=0.5)
+    h0 = W.hidden_rows(0, m_rows, dims.d_model, std=0.5)
     kc = W.round_bf16(W.hidden_rows(1, L, dims.d_kv)).astype(np.float64)
     vc = W.round_bf16(W.hidden_rows(2, L, dims.d_kv)).astype(np.float64)
-    t0 = time.perf_counter()
-    h2, abar = O.refresh_layer(od, lw, h, S, kc, vc)
-    t_layer = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    C = O.rollout([abar], S, L)
-    t_roll = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    logits = O.lm_logits(od, {"final_norm": np.ones(dims.d_model), "lm_head": head}, h2[:n_logit_rows])
-    s, xh = O.confidence(logits)
-    t_head = time.perf_counter() - t0
     is_masked = W.random_mask(0, L, su.prompt_len, 0.3).astype(bool)
     conf = W.random_scores(0, L)
-    t0 = time.perf_counter()
-    O.select(O.Params(sigma=su.sigma, k=su.k, p=su.p, block_len=su.block_len, n_unmask=su.n_unmask), is_masked,
-             su.prompt_len, conf, O.influence(C).astype(np.float32))
-    t_sel = time.perf_counter() - t0
-    step_s = dims.n_layers * (t_layer + t_roll) + t_head + t_sel
-    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
-            "sample": ("1 of %d full-width layers on %d rows (%.2f s) + its L x L rollout update (%.2f s), scaled x%d; "
-                       "LM head + Eq. 1 on %d rows (%.2f s); selection at L=%d (%.3f s)"
-                       % (dims.n_layers, m_rows, t_layer, t_roll, dims.n_layers, n_logit_rows, t_head, L, t_sel))}
+    prm = O.Params(sigma=su.sigma, k=su.k, p=su.p, block_len=su.block_len, n_unmask=su.n_unmask)
+    t_layers = t_roll = t_head = t_sel = 0.0
+    t_all = time.perf_counter()
+    for _ in range(n_steps):
+        h, abars = h0, []
+        t0 = time.perf_counter()
+        for _l in range(dims.n_layers):
+            h, abar = O.refresh_layer(od, lw, h, S, kc, vc)
+            abars.append(abar)
+            h = h0                                    # the same, well-scaled input for every layer
+        t_layers += time.perf_counter() - t0
+        t0 = time.perf_counter()
+        C = O.rollout(abars, S, L)
+        t_roll += time.perf_counter() - t0
+        t0 = time.perf_counter()
+        s, xh = O.confidence(O.lm_logits(od, head, h[:n_logit_rows]))
+        t_head += time.perf_counter() - t0
+        t0 = time.perf_counter()
+        O.select(prm, is_masked, su.prompt_len, conf, O.influence(C).astype(np.float32))
+        t_sel += time.perf_counter() - t0
+    total = time.perf_counter() - t_all
+    return {"value": n_steps / total, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+            "sample": ("%d whole steps at the run's mean shapes (%d selected rows, %d masked rows, L = %d), %.1f s: "
+                       "%d x (full-width block + rollout update) with one layer's weights reused %.1f s + %.1f s, "
+                       "LM head + Eq. 1 %.1f s, selection %.2f s"
+                       % (n_steps, m_rows, n_logit_rows, L, total, dims.n_layers, t_layers, t_roll, t_head, t_sel))}
 
 
 def bench_attention_op(args, B, W, torch, np):
