@@ -236,7 +236,6 @@ int layer_impl(d2c_ctx* c, int layer, float* hidden, const Seg* segs, int n_seg,
                             c->a_norm, st));
   if (c->fused_swiglu) {
     pl = plan_gemm(dt, M, 2 * F, d, true);
-    pl.nt = 1;                                   // the gated epilogue pairs waves, one column tile each
     D2C_TIMED(c, st, D2C_PROF_GEMM, 2.0 * F * d * tsize(c),
               launch_gemm_swiglu(dt, pl, c->a_norm, d, c->w_gate_up[layer], pre_chunks(c, d), c->act, F, M, d, st));
   } else {

@@ -47,7 +47,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_rows_kernel(
     size_t split_stride, int m, int N, int K, int k_per_split, int n_blocks, int n_splits, int row_chunks, int rot_mul,
     T* __restrict__ act) {
   constexpr bool PRE = MODE != kRowMajor;
-  static_assert(MODE != kPreSwiglu || (NT == 1 && WAVES % 2 == 0), "the SwiGLU epilogue pairs neighbouring waves");
+  static_assert(MODE != kPreSwiglu || NT == 2 || WAVES % 2 == 0, "the SwiGLU epilogue pairs neighbouring waves");
   constexpr int RING = 2;
   constexpr int kThreads = WAVES * 64;
   constexpr int kAFrags = MT * 256;                              // 16-byte fragments of one activation chunk
@@ -191,6 +191,21 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_rows_kernel(
     }
   }
 
+  if (MODE == kPreSwiglu && NT == 2) {
+    // Column tiles alternate gate, up, gate, up ..: with two tiles per wave the pair sits in one wave
+    const int F = N >> 1;
+    const int col = (n_base >> 5) * 16 + r;                     // n_base = 32 * (hidden tile)
+    if (col >= F) return;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int row = row0 + mt * 16 + g * 4 + j;
+        const float gv = acc[mt][0][j];
+        if (row < m) act[(size_t)row * F + col] = from_f32<T>(gv / (1.0f + expf(-gv)) * acc[mt][NT - 1][j]);
+      }
+    return;
+  }
   if (MODE == kPreSwiglu) {
     // Column tiles alternate gate, up, gate, up ..: wave 2p holds the gate values and wave 2p+1 the up
     // values of the same 16 hidden columns.  The odd wave hands its accumulators over through LDS (the
@@ -270,11 +285,8 @@ hipError_t launch_nt(const GemmPlan& pl, const void* A, int lda, const void* W, 
     if (pl.waves == 8) return launch_mt<T, 1, 8, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
     return launch_mt<T, 1, 4, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
   }
-  if constexpr (MODE != kPreSwiglu) {
-    if (pl.waves == 8) return launch_mt<T, 2, 8, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
-    return launch_mt<T, 2, 4, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
-  }
-  return hipErrorInvalidValue;
+  if (pl.waves == 8) return launch_mt<T, 2, 8, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+  return launch_mt<T, 2, 4, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
 }
 
 // One 16-byte fragment per thread: dst block (tile t, chunk c) slot (step s, lane) <- src row
@@ -306,7 +318,9 @@ GemmPlan plan_gemm(int dtype, int m, int N, int K, bool single_split) {
   const int tiles = (m + 15) / 16;
   pl.mt = tiles <= 8 ? (tiles < 1 ? 1 : tiles) : 8;
   pl.row_chunks = tiles <= 8 ? 1 : (tiles + 7) / 8;
-  pl.nt = N > t.gemm_nt_big_n ? 2 : 1;
+  // two column tiles per wave halve the LDS reads per matrix-core step: a gain once there are several
+  // row chunks (the kernel is LDS- and L2-bound there), a loss for a handful of rows (fewer waves in flight)
+  pl.nt = (N > t.gemm_nt_big_n || tiles > 8) ? 2 : 1;
   pl.rot = t.gemm_rot;
   // 8 waves share one activation chunk in LDS: fewer, fatter workgroups (about 1.5 per compute unit) with
   // fewer k splits measured faster than 4-wave groups at every projection shape of the two models
@@ -350,7 +364,7 @@ hipError_t launch_gemm_swiglu(int dtype, const GemmPlan& pl, const void* A, int 
   if (m <= 0 || F <= 0 || K <= 0 || F % 16) return hipErrorInvalidValue;
   const int e = dtype == kBF16 ? 8 : 4, kc = dtype == kBF16 ? 128 : 64;
   if (K % e || lda % e || ldw != (K + kc - 1) / kc) return hipErrorInvalidValue;
-  if (pl.splits != 1 || pl.nt != 1 || pl.mt * 16 * pl.row_chunks < m || pl.k_per_split < K)
+  if (pl.splits != 1 || pl.mt * 16 * pl.row_chunks < m || pl.k_per_split < K)
     return hipErrorInvalidValue;
   if (dtype == kBF16)
     return launch_nt<bf16, kPreSwiglu>(pl, A, lda, W, ldw, nullptr, 0, 0, m, 2 * F, K, st, act);

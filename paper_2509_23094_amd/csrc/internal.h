@@ -14,7 +14,8 @@ inline size_t dtype_size(int dt) { return dt == kBF16 ? 2 : 4; }
 struct Tunables {
   int gemm_target_wgs = 384;   // aim for at least this many groups of 4 waves per GEMM
   int gemm_max_splits = 8;
-  int gemm_nt_big_n = 1 << 30; // N above this uses two column tiles per wave (measured slower at every model shape)
+  int gemm_nt_big_n = 1 << 30; // N above this uses two column tiles per wave even for few rows (measured slower);
+                               // more than 128 rows always do
   int gemm_waves = 0;          // waves per workgroup sharing one activation chunk in LDS: 4, 8; 0 = by shape
   bool gemm_preshuffle = true; // d2c_init keeps pre-tiled copies of the projection matrices (costs their size again)
   int gemm_rot = 0;            // start chunk of a workgroup's k walk = (column block * this) % chunks
