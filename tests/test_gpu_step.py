@@ -221,6 +221,28 @@ def test_step_bf16_small_teacher_forced(B):
     _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=24)
 
 
+def test_step_bf16_small_on_one_stream(B):
+    """The same narrow bf16 model with the second stream switched off: head means, chain and selection
+    all queue behind the projections on the caller's stream."""
+    wd = W.ModelDims(3, 512, 8, 2, 64, 1408, 2048, dtype="bf16")
+    su = W.DecodeSetup(40, 24, 12, 1, k=6, p=0.3)
+    mdl = W.model_weights(wd, 3)
+    B.d2c_set_tunable("side_stream", 0)
+    try:
+        _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=8)
+    finally:
+        B.d2c_set_tunable("side_stream", 1)
+
+
+def test_step_bf16_many_rows_per_step(B):
+    """A bf16 model whose steps select more than 96 rows (k = 64 masked + half the known tokens): the
+    LDS-tiled attention kernels and the per-layer head average on the second stream inside d2c_step."""
+    wd = W.ModelDims(2, 512, 4, 4, 128, 1408, 2048, dtype="bf16")
+    su = W.DecodeSetup(160, 96, 96, 2, k=64, p=0.6)
+    mdl = W.model_weights(wd, 5)
+    _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=6)
+
+
 def test_step_batch_of_ragged_sequences(B):
     """Two independent sequences of different length in one d2c_step call equal two separate calls."""
     wd = W.ModelDims(2, 256, 4, 4, 64, 688, 512, dtype="bf16")
