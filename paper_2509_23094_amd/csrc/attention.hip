@@ -4,15 +4,17 @@
 // heads, Sec. 4.2 of the d2Cache paper), which the rollout (Eq. 6-8) consumes.
 //
 // bf16 path, two launches, no atomics (bit-reproducible):
-//   pass 1  one workgroup per (16-query tile, head); its 8 waves take key tiles
-//           round-robin (next tile's loads in flight while one is consumed), run an
-//           online softmax each and merge through LDS.  Scores are
+//   pass 1  one workgroup per (16-query tile, head), placed so that the readers of
+//           one kv head share an L2; its 8 waves take 32-key pairs of tiles
+//           round-robin (the next pair's loads in flight while one is consumed), run
+//           an online softmax each and merge through LDS.  Scores are
 //           computed transposed, S^T = K Q^T, so that the 16x16 accumulator layout
-//           (4 consecutive keys per lane for one query) IS the B operand of the
-//           16x16x16 matrix-core step of O^T = V^T P^T: P never leaves registers.
+//           (4 consecutive keys per lane for one query), taken for both tiles of a
+//           pair, IS the B operand of the 16x16x32 matrix-core step of
+//           O^T = V^T P^T: P never leaves registers.
 //           V rows are read straight from global memory (8 bytes = 4 head-dim
-//           values per lane and key) and a 4x4 in-register transpose turns them
-//           into the A operand (4 keys per lane for one head-dim value).
+//           values per lane and key) and 4x4 in-register transposes turn them
+//           into the A operand (4+4 keys per lane for one head-dim value).
 //           Writes O (bf16) and the log-sum-exp per (head, row).
 //   pass 2  one workgroup per (16-query tile, 16-key tile); its 4 waves split the
 //           heads, recompute S^T and accumulate exp(s - lse) in registers, then add
@@ -32,35 +34,93 @@ constexpr int kWaves = 4;
 __device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
 __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
 
-// Operands of one 16-key tile, loaded ahead of their use: K rows for S^T (DH/32 fragments) and,
-// per 64-wide head-dim block, four keys x four head-dim values of V.
+// Operands of one pair of 16-key tiles (32 keys), loaded ahead of their use: per tile the K rows for S^T
+// (DH/32 fragments) and, per 64-wide head-dim block, four keys x four head-dim values of V.
 template <int DH>
-struct KvTile {
-  Frag<bf16> k[DH / 32];
-  u32x2 v[DH / 64][4];
+struct KvPair {
+  Frag<bf16> k[2][DH / 32];
+  u32x2 v[2][DH / 64][4];
 };
 
+// Unconditional: rows past the end are clamped to the last key (their scores are masked by the consumer).
 template <int DH>
-__device__ __forceinline__ void load_kv_tile(KvTile<DH>& t, const bf16* __restrict__ kbase,
+__device__ __forceinline__ void load_kv_pair(KvPair<DH>& t, const bf16* __restrict__ kbase,
                                              const bf16* __restrict__ vbase, size_t pitch, int key0, int L, int r,
                                              int g) {
-  const int key = min(key0 + r, L - 1);
-  const bf16* krow = kbase + (size_t)key * pitch + g * 8;
 #pragma unroll
-  for (int s = 0; s < DH / 32; ++s) t.k[s].raw = ld16(krow + s * 32);
+  for (int a = 0; a < 2; ++a) {
+    const int key = min(key0 + a * 16 + r, L - 1);
+    const bf16* krow = kbase + (size_t)key * pitch + g * 8;
 #pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const int vkey = min(key0 + 4 * g + e, L - 1);
-    const bf16* vrow = vbase + (size_t)vkey * pitch + 4 * r;
-#pragma unroll
-    for (int b = 0; b < DH / 64; ++b) t.v[b][e] = ld8(vrow + b * 64);
+    for (int s = 0; s < DH / 32; ++s) t.k[a][s].raw = ld16(krow + s * 32);
   }
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int vkey = min(key0 + a * 16 + 4 * g + e, L - 1);
+      const bf16* vrow = vbase + (size_t)vkey * pitch + 4 * r;
+#pragma unroll
+      for (int b = 0; b < DH / 64; ++b) t.v[a][b][e] = ld8(vrow + b * 64);
+    }
 }
 
 constexpr int kFwdWaves = 8;
 constexpr int kFwdThreads = kFwdWaves * 64;
+constexpr int kXcds = 8;          // workgroup i of a launch runs on XCD i % 8 (each XCD has its own L2)
 
-// KEEP > 0: the wave also keeps the scaled scores of its first 4*KEEP key tiles (all of them when
+// Which (query tile, head) a workgroup takes.  All workgroups that read the K/V of one kv head are placed
+// on one XCD (or, with fewer than 8 kv heads, on 8 / n_kv_heads of them), so the rows of a kv head come
+// from HBM once (resp. 8 / n_kv_heads times) and the other readers hit that XCD's L2.
+struct FwdMap {
+  int mode;          // 0: plain, 1: n_kv_heads % 8 == 0, 2: 8 % n_kv_heads == 0
+  int n_qt, group;   // query tiles, query heads per kv head
+  int n_wgs;
+};
+__host__ __device__ inline FwdMap fwd_map(int m, int n_heads, int n_kv_heads) {
+  FwdMap f;
+  f.n_qt = (m + 15) / 16;
+  f.group = n_heads / n_kv_heads;
+  const int items = f.group * f.n_qt;                 // workgroups per kv head
+  if (n_kv_heads % kXcds == 0) {
+    f.mode = 1;
+    f.n_wgs = n_kv_heads * items;
+  } else if (kXcds % n_kv_heads == 0) {
+    f.mode = 2;
+    const int share = kXcds / n_kv_heads;             // XCDs per kv head
+    f.n_wgs = kXcds * ((items + share - 1) / share);
+  } else {
+    f.mode = 0;
+    f.n_wgs = n_kv_heads * items;
+  }
+  return f;
+}
+// false: this workgroup has nothing to do (padding of mode 2)
+__device__ __forceinline__ bool fwd_map_decode(const FwdMap& f, int n_kv_heads, int wg, int& head, int& qt) {
+  int kvh, item;
+  const int items = f.group * f.n_qt;
+  if (f.mode == 1) {
+    const int xcd = wg % kXcds, j = wg / kXcds;
+    kvh = xcd + kXcds * (j / items);
+    item = j % items;
+  } else if (f.mode == 2) {
+    const int share = kXcds / n_kv_heads;
+    const int xcd = wg % kXcds, j = wg / kXcds;
+    kvh = xcd / share;
+    item = xcd % share + share * j;
+    if (item >= items) return false;
+  } else {
+    kvh = wg / items;
+    item = wg % items;
+  }
+  head = kvh * f.group + item / f.n_qt;
+  qt = item % f.n_qt;
+  return true;
+}
+
+// One workgroup per (16-query tile, head).  Its 8 waves take 32-key pairs of tiles round-robin, run an
+// online softmax each and merge through LDS.
+// KEEP > 0: the wave also keeps the scaled scores of its first 2*KEEP pairs (all of them when
 // L <= 512*KEEP) and, once the workgroup knows the rows' log-sum-exp, writes the normalised probabilities
 // of this head to probs [H, m, L]: the head average then needs no second pass over Q and K.
 template <int DH, int KEEP>
@@ -71,13 +131,14 @@ __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
   constexpr int NS = DH / 32;     // contraction steps of Q K^T
   constexpr int NB = DH / 64;     // 64-wide head-dim blocks of the output
   __shared__ float o_lds[kFwdWaves][16][DH + 1];
-  __shared__ float m_lds[kFwdWaves][16], l_lds[kFwdWaves][16];
+  __shared__ float m_lds[kFwdWaves][16], l_lds[kFwdWaves][16], f_lds[kFwdWaves][16];
   __shared__ float lse_lds[16];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 15, g = lane >> 4;
-  const int q0 = blockIdx.x * 16;
-  const int head = blockIdx.y;
+  int head, qt;
+  if (!fwd_map_decode(fwd_map(m, n_heads, n_kv_heads), n_kv_heads, blockIdx.x, head, qt)) return;
+  const int q0 = qt * 16;
   const int kvh = head / (n_heads / n_kv_heads);
   const int dq = n_heads * DH;
   const size_t kv_pitch = (size_t)n_kv_heads * DH;
@@ -99,91 +160,100 @@ __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
 #pragma unroll
     for (int i = 0; i < 4; ++i) acc[b][i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  auto consume = [&](const KvTile<DH>& t, int key0, f32x4* keep) {
-    f32x4 st = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int s = 0; s < NS; ++s) mfma16(st, t.k[s], qf[s]);
-    float x[4];
+  // S^T of both tiles, one online-softmax update for the 32 keys, then O^T += V^T P^T with K = 32:
+  // contraction slot (g, j) of the matrix-core step stands for key 16*(j/4) + 4g + j%4 of the pair, which
+  // is how the two accumulators of S^T hold the probabilities, so P never leaves registers.
+  auto consume = [&](const KvPair<DH>& t, int key0, f32x4* keep) {
+    float x[2][4];
     float tmax = -INFINITY;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      x[j] = (key0 + 4 * g + j < L) ? st[j] * scale : -INFINITY;
-      tmax = fmaxf(tmax, x[j]);
+    for (int a = 0; a < 2; ++a) {
+      f32x4 st = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < NS; ++s) mfma16(st, t.k[a][s], qf[s]);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        x[a][j] = (key0 + a * 16 + 4 * g + j < L) ? st[j] * scale : -INFINITY;
+        tmax = fmaxf(tmax, x[a][j]);
+      }
+      if (keep) keep[a] = f32x4{x[a][0], x[a][1], x[a][2], x[a][3]};
     }
-    if (keep) *keep = f32x4{x[0], x[1], x[2], x[3]};
     tmax = fmaxf(tmax, __shfl_xor(tmax, 16, kWave));
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
-    const float m_new = fmaxf(m_run, tmax);
+    const float m_new = fmaxf(m_run, tmax);          // finite: a pair holds at least one key below L
     const float alpha = __expf(m_run - m_new);
-    float p[4];
+    float p[2][4];
     float psum = 0.f;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      p[j] = __expf(x[j] - m_new);
-      psum += p[j];
-    }
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        p[a][j] = __expf(x[a][j] - m_new);
+        psum += p[a][j];
+      }
     l_run = l_run * alpha + psum;
     m_run = m_new;
-    bf16x4 pb = {(bf16)p[0], (bf16)p[1], (bf16)p[2], (bf16)p[3]};
-    const s16x4 pfrag = __builtin_bit_cast(s16x4, pb);
+    Frag<bf16> pf;
+    {
+      bf16x4 p0 = {(bf16)p[0][0], (bf16)p[0][1], (bf16)p[0][2], (bf16)p[0][3]};
+      bf16x4 p1 = {(bf16)p[1][0], (bf16)p[1][1], (bf16)p[1][2], (bf16)p[1][3]};
+      const u32x2 a0 = __builtin_bit_cast(u32x2, p0), a1 = __builtin_bit_cast(u32x2, p1);
+      pf.raw = u32x4{a0.x, a0.y, a1.x, a1.y};
+    }
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-      // in-register 4x4 transpose: operand i holds keys 4g..4g+3 of head-dim value b*64 + 4r + i
-      u32x2 op[4];
-      op[0] = u32x2{pack_lo(t.v[b][0].x, t.v[b][1].x), pack_lo(t.v[b][2].x, t.v[b][3].x)};
-      op[1] = u32x2{pack_hi(t.v[b][0].x, t.v[b][1].x), pack_hi(t.v[b][2].x, t.v[b][3].x)};
-      op[2] = u32x2{pack_lo(t.v[b][0].y, t.v[b][1].y), pack_lo(t.v[b][2].y, t.v[b][3].y)};
-      op[3] = u32x2{pack_hi(t.v[b][0].y, t.v[b][1].y), pack_hi(t.v[b][2].y, t.v[b][3].y)};
+      // in-register 4x4 transposes: operand i holds keys 4g..4g+3 of both tiles for head-dim value b*64 + 4r + i
+      Frag<bf16> op[4];
+      op[0].raw = u32x4{pack_lo(t.v[0][b][0].x, t.v[0][b][1].x), pack_lo(t.v[0][b][2].x, t.v[0][b][3].x),
+                        pack_lo(t.v[1][b][0].x, t.v[1][b][1].x), pack_lo(t.v[1][b][2].x, t.v[1][b][3].x)};
+      op[1].raw = u32x4{pack_hi(t.v[0][b][0].x, t.v[0][b][1].x), pack_hi(t.v[0][b][2].x, t.v[0][b][3].x),
+                        pack_hi(t.v[1][b][0].x, t.v[1][b][1].x), pack_hi(t.v[1][b][2].x, t.v[1][b][3].x)};
+      op[2].raw = u32x4{pack_lo(t.v[0][b][0].y, t.v[0][b][1].y), pack_lo(t.v[0][b][2].y, t.v[0][b][3].y),
+                        pack_lo(t.v[1][b][0].y, t.v[1][b][1].y), pack_lo(t.v[1][b][2].y, t.v[1][b][3].y)};
+      op[3].raw = u32x4{pack_hi(t.v[0][b][0].y, t.v[0][b][1].y), pack_hi(t.v[0][b][2].y, t.v[0][b][3].y),
+                        pack_hi(t.v[1][b][0].y, t.v[1][b][1].y), pack_hi(t.v[1][b][2].y, t.v[1][b][3].y)};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         acc[b][i] *= alpha;
-        acc[b][i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, op[i]), pfrag, acc[b][i], 0,
-                                                              0, 0);
+        mfma16(acc[b][i], op[i], pf);
       }
     }
   };
 
-  // waves take key tiles round-robin; up to four tiles of a wave are in flight: a slot is refilled
-  // with the tile four strides ahead as soon as it has been consumed
-  const int n_tiles = (L + 15) / 16;
-  KvTile<DH> ring[4];
+  // waves take pairs round-robin; two pairs of a wave are in flight: a slot is refilled with the pair two
+  // strides ahead as soon as it has been consumed.  Loads are unconditional (a pair past the end reads the
+  // last key again and is never consumed), so no wait separates them.
+  const int n_pairs = (L + 31) / 32;
+  KvPair<DH> ring[2];
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const int t = wave + u * kFwdWaves;
-    if (t < n_tiles) load_kv_tile<DH>(ring[u], kbase, vbase, kv_pitch, t * 16, L, r, g);
-  }
+  for (int u = 0; u < 2; ++u) load_kv_pair<DH>(ring[u], kbase, vbase, kv_pitch, (wave + u * kFwdWaves) * 32, L, r, g);
   f32x4 kept[KEEP > 0 ? 4 * KEEP : 1];
   if constexpr (KEEP > 0) {
-    // all of the wave's tiles in 4*KEEP statically indexed slots (the launcher guarantees L <= 512*KEEP)
+    // all of the wave's pairs in 2*KEEP statically indexed slots (the launcher guarantees L <= 512*KEEP)
 #pragma unroll
     for (int it = 0; it < KEEP; ++it)
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int t = wave + (it * 4 + u) * kFwdWaves;
-        if (t < n_tiles) {
-          consume(ring[u], t * 16, &kept[it * 4 + u]);
-          const int tn = t + 4 * kFwdWaves;
-          if (tn < n_tiles) load_kv_tile<DH>(ring[u], kbase, vbase, kv_pitch, tn * 16, L, r, g);
-        }
+      for (int u = 0; u < 2; ++u) {
+        const int t = wave + (it * 2 + u) * kFwdWaves;
+        if (t < n_pairs) consume(ring[u], t * 32, &kept[(it * 2 + u) * 2]);
+        if (it + 1 < KEEP) load_kv_pair<DH>(ring[u], kbase, vbase, kv_pitch, (t + 2 * kFwdWaves) * 32, L, r, g);
       }
   } else {
-    for (int t0 = wave; t0 < n_tiles; t0 += 4 * kFwdWaves) {
+    for (int t0 = wave; t0 < n_pairs; t0 += 2 * kFwdWaves) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < 2; ++u) {
         const int t = t0 + u * kFwdWaves;
-        if (t >= n_tiles) break;
-        consume(ring[u], t * 16, nullptr);
-        const int tn = t + 4 * kFwdWaves;
-        if (tn < n_tiles) load_kv_tile<DH>(ring[u], kbase, vbase, kv_pitch, tn * 16, L, r, g);
+        if (t < n_pairs) consume(ring[u], t * 32, nullptr);
+        load_kv_pair<DH>(ring[u], kbase, vbase, kv_pitch, (t + 2 * kFwdWaves) * 32, L, r, g);
       }
     }
   }
 
-  // merge the waves' partial softmaxes
+  // merge the waves' partial softmaxes: the weights of the 8 partial results of a row first, then the sums
   l_run += __shfl_xor(l_run, 16, kWave);
   l_run += __shfl_xor(l_run, 32, kWave);
   if (g == 0) {
-    m_lds[wave][r] = m_run;
+    m_lds[wave][r] = m_run;              // -inf, l = 0 for a wave that had no pair
     l_lds[wave][r] = l_run;
   }
 #pragma unroll
@@ -193,33 +263,36 @@ __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
 #pragma unroll
       for (int j = 0; j < 4; ++j) o_lds[wave][r][b * 64 + 16 * g + 4 * j + i] = acc[b][i][j];
   __syncthreads();
-
-  for (int o = tid; o < 16 * DH; o += kFwdThreads) {
-    const int qi = o / DH, dcol = o - qi * DH;
+  if (tid < kFwdWaves * 16) {
+    const int w = tid >> 4, qi = tid & 15;
     float mx = m_lds[0][qi];
 #pragma unroll
-    for (int w = 1; w < kFwdWaves; ++w) mx = fmaxf(mx, m_lds[w][qi]);
-    float lsum = 0.f, osum = 0.f;
+    for (int u = 1; u < kFwdWaves; ++u) mx = fmaxf(mx, m_lds[u][qi]);
+    float lsum = 0.f;
 #pragma unroll
-    for (int w = 0; w < kFwdWaves; ++w) {
-      const float f = __expf(m_lds[w][qi] - mx);
-      lsum += l_lds[w][qi] * f;
-      osum += o_lds[w][qi][dcol] * f;
-    }
-    if (dcol == 0) lse_lds[qi] = mx + __logf(lsum);
-    if (q0 + qi < m) {
-      out[(size_t)(q0 + qi) * dq + head * DH + dcol] = (bf16)(osum / lsum);
-      if (dcol == 0) lse[(size_t)head * m + q0 + qi] = mx + __logf(lsum);
+    for (int u = 0; u < kFwdWaves; ++u) lsum += l_lds[u][qi] * __expf(m_lds[u][qi] - mx);
+    f_lds[w][qi] = __expf(m_lds[w][qi] - mx) / lsum;
+    if (w == 0) {
+      const float e = mx + __logf(lsum);
+      lse_lds[qi] = e;
+      if (q0 + qi < m) lse[(size_t)head * m + q0 + qi] = e;
     }
   }
+  __syncthreads();
+  for (int o = tid; o < 16 * DH; o += kFwdThreads) {
+    const int qi = o / DH, dcol = o - qi * DH;
+    float osum = 0.f;
+#pragma unroll
+    for (int w = 0; w < kFwdWaves; ++w) osum += o_lds[w][qi][dcol] * f_lds[w][qi];
+    if (q0 + qi < m) out[(size_t)(q0 + qi) * dq + head * DH + dcol] = (bf16)osum;
+  }
   if constexpr (KEEP > 0) {
-    __syncthreads();
     if (q0 + r >= m) return;
     const float e = lse_lds[r];
     float* prow = probs + ((size_t)head * m + q0 + r) * L;
 #pragma unroll
     for (int o = 0; o < 4 * KEEP; ++o) {
-      const int key0 = (wave + o * kFwdWaves) * 16 + 4 * g;
+      const int key0 = (wave + (o >> 1) * kFwdWaves) * 32 + (o & 1) * 16 + 4 * g;
       if ((L & 3) == 0) {                       // rows start 16-byte aligned: one store per tile
         if (key0 < L)
           *reinterpret_cast<f32x4*>(prow + key0) = f32x4{__expf(kept[o][0] - e), __expf(kept[o][1] - e),
@@ -388,7 +461,7 @@ template <int DH>
 hipError_t launch_fwd_bf16(const void* q, const void* k_cache, const void* v_cache, int m, int L, int n_heads,
                            int n_kv_heads, void* out, float* lse, float* probs, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)DH);
-  const dim3 grid((m + 15) / 16, n_heads);
+  const dim3 grid(fwd_map(m, n_heads, n_kv_heads).n_wgs);
 #define D2C_FWD(KEEP_)                                                                                          \
   hipLaunchKernelGGL((attn_fwd_bf16_kernel<DH, KEEP_>), grid, dim3(kFwdThreads), 0, st, (const bf16*)q,         \
                      (const bf16*)k_cache, (const bf16*)v_cache, m, L, n_heads, n_kv_heads, scale, (bf16*)out, \

@@ -92,14 +92,14 @@ __global__ __launch_bounds__(kThreads) void attn_tiled_fwd_kernel(
     for (int s = 0; s < NS; ++s) qf[t][s].raw = ld16(qrow + s * 32);
   }
 
-  // staging registers of K/V blocks on their way from global memory to LDS, two sets: a block is
-  // requested two iterations before it is needed in LDS.  Wave w brings key tile w of K (its NS
-  // fragments) and one 8-key x 4-value unit of V per lane (unit = 32-key step ks, 64-wide block b).
+  // staging registers of the K/V block on its way from global memory to LDS: requested at the top of an
+  // iteration, stored behind its arithmetic.  Wave w brings key tile w of K (its NS fragments) and one
+  // 8-key x 4-value unit of V per lane (unit = 32-key step ks, 64-wide block b).
   struct Stage {
     u32x4 k[NS];
     u32x2 v[2][4];
   };
-  Stage stg[2];
+  Stage stg;
   const int v_b = wave % NB, v_ks = wave / NB;          // v_ks < 2 only for the waves that stage V
   const bool stages_v = NB == 2 || v_ks < 2;            // with two 64-wide blocks all four waves stage V
   const int last_block = n_blocks - 1;
@@ -161,9 +161,12 @@ __global__ __launch_bounds__(kThreads) void attn_tiled_fwd_kernel(
 
   // Online softmax in the base-2 domain: p = 2^(s*c - ref) with c = scale*log2(e).  ref is a per-row
   // reference, not necessarily the running maximum: it is only raised (and O, l rescaled) when a block's
-  // maximum exceeds it by more than kRaise, so p stays below 2^kRaise and the rescaling of the
-  // accumulators, the most expensive vector work of the loop, is skipped for almost every block.  The
-  // result is the same softmax (shift invariance); the decision depends on the data only.
+  // maximum exceeds it by more than kRaise, so p stays below 2^kRaise.  The result is the same softmax
+  // (shift invariance); the decision depends on the data only.  The raise is rare after the first block,
+  // and it is the only vector arithmetic on the O accumulators: it lives OUTSIDE the hot loop (the loop
+  // leaves through a break, the raise is applied, the block is finished, the loop is entered again), so
+  // inside the hot loop the accumulators are touched by matrix-core instructions only and never have to
+  // be copied between the accumulator and the vector register files.
   constexpr float kRaise = 8.f;
   const float c2 = scale * 1.44269504088896341f;
   float ref[QT], l_run[QT];
@@ -175,31 +178,19 @@ __global__ __launch_bounds__(kThreads) void attn_tiled_fwd_kernel(
 #pragma unroll
     for (int d = 0; d < ND; ++d) acc[d][t] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
+  constexpr int FB = QT == 1 ? 8 : 16;         // LDS fragments read per batch (one latency per batch)
+  f32x4 st[4][QT];
+  float tmax2[QT];
 
-  // prologue: block 0 reaches LDS, block 1 is in flight in set 1
-  load_block(stg[0], 0);
-  load_block(stg[1], 1);
-  store_block(stg[0], 0);
-  __syncthreads();
-  for (int blk0 = 0; blk0 < n_blocks; blk0 += 2) {
-#pragma unroll
-   for (int u = 0; u < 2; ++u) {
-    const int blk = blk0 + u;
-    if (blk >= n_blocks) break;          // uniform over the workgroup
-    const int buf = u;
-    // block blk+2 is requested into the set block blk arrived in (stored to LDS one iteration ago)
-    load_block(stg[u], blk + 2);
-    __builtin_amdgcn_sched_barrier(0);
+  // scores of block blk (S^T = K Q^T, masked past key_hi) and their scaled row maxima; returns whether any
+  // row of the wave needs its reference raised
+  auto scores = [&](int blk) -> bool {
+    const int buf = blk & 1;
     const int key0 = key_lo + blk * kBlockKeys;
-
-    f32x4 st[4][QT];
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
       for (int t = 0; t < QT; ++t) st[a][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    // K fragments are read from LDS in batches of FB (one latency per batch instead of one per
-    // fragment pair), each followed by its matrix-core steps.
-    constexpr int FB = QT == 1 ? 8 : 16;         // fragments per batch
 #pragma unroll
     for (int b0 = 0; b0 < 4 * NS; b0 += FB) {
       Frag<bf16> kf[FB];
@@ -212,7 +203,6 @@ __global__ __launch_bounds__(kThreads) void attn_tiled_fwd_kernel(
         for (int t = 0; t < QT; ++t) mfma16(st[(b0 + i) / NS][t], kf[i], qf[t][(b0 + i) % NS]);
       __builtin_amdgcn_sched_barrier(0);
     }
-
     if (key0 + kBlockKeys > key_hi) {    // ragged last block of the range: keys past the end score -inf
 #pragma unroll
       for (int a = 0; a < 4; ++a)
@@ -223,8 +213,7 @@ __global__ __launch_bounds__(kThreads) void attn_tiled_fwd_kernel(
             for (int t = 0; t < QT; ++t) st[a][t][j] = -INFINITY;
           }
     }
-
-    Frag<bf16> pf[2][QT];
+    bool need = false;
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
       float tmax = fmaxf(fmaxf(st[0][t][0], st[0][t][1]), fmaxf(st[0][t][2], st[0][t][3]));
@@ -233,15 +222,18 @@ __global__ __launch_bounds__(kThreads) void attn_tiled_fwd_kernel(
         tmax = fmaxf(tmax, fmaxf(fmaxf(st[a][t][0], st[a][t][1]), fmaxf(st[a][t][2], st[a][t][3])));
       tmax = fmaxf(tmax, __shfl_xor(tmax, 16, kWave));
       tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
-      const float tmax2 = tmax * c2;                   // finite: every block holds at least one key
-      if (__builtin_amdgcn_ballot_w64(tmax2 > ref[t] + kRaise) != 0) {
-        const float ref_new = fmaxf(ref[t], tmax2);
-        const float alpha = __builtin_amdgcn_exp2f(ref[t] - ref_new);      // 0 on the first block
-        l_run[t] *= alpha;
+      tmax2[t] = tmax * c2;                            // finite: every block holds at least one key
+      need = need || tmax2[t] > ref[t] + kRaise;
+    }
+    return __builtin_amdgcn_ballot_w64(need) != 0;
+  };
+  // probabilities of the block against the current references, O^T += V^T P^T, then the block that was
+  // requested at the top of the iteration goes to the other LDS buffer
+  auto finish = [&](int blk) {
+    const int buf = blk & 1;
+    Frag<bf16> pf[2][QT];
 #pragma unroll
-        for (int d = 0; d < ND; ++d) acc[d][t] *= alpha;
-        ref[t] = ref_new;
-      }
+    for (int t = 0; t < QT; ++t) {
       const float nref = -ref[t];
       float psum = 0.f;
       float x[4][4];
@@ -259,7 +251,6 @@ __global__ __launch_bounds__(kThreads) void attn_tiled_fwd_kernel(
                               pack_bf16(x[2 * ks + 1][0], x[2 * ks + 1][1]),
                               pack_bf16(x[2 * ks + 1][2], x[2 * ks + 1][3])};
     }
-
 #pragma unroll
     for (int b0 = 0; b0 < ND * 2; b0 += FB) {
       Frag<bf16> vf[FB];
@@ -272,12 +263,35 @@ __global__ __launch_bounds__(kThreads) void attn_tiled_fwd_kernel(
         for (int t = 0; t < QT; ++t) mfma16(acc[(b0 + i) / 2][t], vf[i], pf[(b0 + i) % 2][t]);
       __builtin_amdgcn_sched_barrier(0);
     }
-
-    // block blk+1 (requested one iteration ago) goes to the other buffer, which was last read one
-    // iteration ago, before the barrier every wave has passed
-    store_block(stg[u ^ 1], buf ^ 1);
+    // the other buffer was last read one iteration ago, before the barrier every wave has passed
+    store_block(stg, buf ^ 1);
     __syncthreads();
-   }
+  };
+
+  load_block(stg, 0);
+  store_block(stg, 0);
+  __syncthreads();
+  int blk = 0;
+  for (;;) {
+    for (; blk < n_blocks; ++blk) {                    // hot loop
+      load_block(stg, blk + 1);                        // flies during this block's arithmetic
+      __builtin_amdgcn_sched_barrier(0);
+      if (scores(blk)) break;
+      finish(blk);
+    }
+    if (blk >= n_blocks) break;
+    // a row's reference must go up: rescale its sums, then finish the block as usual
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+      const float ref_new = fmaxf(ref[t], tmax2[t] > ref[t] + kRaise ? tmax2[t] : ref[t]);
+      const float alpha = __builtin_amdgcn_exp2f(ref[t] - ref_new);        // 0 on the first block, 1 if unchanged
+      l_run[t] *= alpha;
+#pragma unroll
+      for (int d = 0; d < ND; ++d) acc[d][t] *= alpha;
+      ref[t] = ref_new;
+    }
+    finish(blk);
+    ++blk;
   }
 
 #pragma unroll
