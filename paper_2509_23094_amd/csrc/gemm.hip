@@ -35,6 +35,7 @@ namespace {
 constexpr int kChunkBytes = 256;                 // bytes of one row in one chunk
 constexpr int kRowStride = kChunkBytes + 16;     // LDS row pitch: 16-byte skew, conflict-free 16-byte reads
 constexpr int kSteps = 4;                        // matrix-core steps per chunk
+constexpr int kSuperRows = 8, kSuperCols = 4;    // many rows: block of workgroups that share an XCD's L2
 
 // RING = number of weight chunks a wave keeps in registers (one being consumed, RING-1 in flight).
 // MODE: 0 = W row-major [N, K]; 1 = W pre-tiled; 2 = W pre-tiled with gate and up tiles interleaved and the
@@ -47,16 +48,29 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_rows_kernel(
     size_t split_stride, int m, int N, int K, int k_per_split, int n_blocks, int n_splits, int row_chunks, int rot_mul,
     T* __restrict__ act) {
   constexpr bool PRE = MODE != kRowMajor;
-  static_assert(MODE != kPreSwiglu || NT == 2 || WAVES % 2 == 0, "the SwiGLU epilogue pairs neighbouring waves");
+  static_assert(MODE != kPreSwiglu || NT % 2 == 0 || WAVES % 2 == 0, "the SwiGLU epilogue pairs neighbouring waves");
   constexpr int RING = 2;
   constexpr int kThreads = WAVES * 64;
   constexpr int kAFrags = MT * 256;                              // 16-byte fragments of one activation chunk
   constexpr int AI = (kAFrags + kThreads - 1) / kThreads;        // of which one thread moves this many
   // workgroup id -> (weight tile, row chunk): id % 8 is the XCD, within an XCD the row chunk varies fastest
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int tile = (slot / row_chunks) * 8 + xcd;
-  if (tile >= n_blocks * n_splits) return;       // padding of the last group of 8 (whole workgroup leaves)
-  const int bz = slot % row_chunks, by = tile / n_blocks, bx = tile - by * n_blocks;
+  int tile, bz;
+  if constexpr (NT >= 4) {
+    // Many rows: the 32 workgroups that run on an XCD at one time form a block of kSuperRows row chunks x
+    // kSuperCols weight tiles, so that what its L2 has to bring in per k-step (8 x 128 activation rows +
+    // 4 x 256 weight rows) is less than half of that of 32 row chunks of one weight tile.
+    const int n_row_st = (row_chunks + kSuperRows - 1) / kSuperRows;
+    const int st = slot / (kSuperRows * kSuperCols), w = slot % (kSuperRows * kSuperCols);
+    bz = (st % n_row_st) * kSuperRows + w % kSuperRows;
+    tile = ((st / n_row_st) * kSuperCols + w / kSuperRows) * 8 + xcd;
+    if (bz >= row_chunks) return;
+  } else {
+    tile = (slot / row_chunks) * 8 + xcd;
+    bz = slot % row_chunks;
+  }
+  if (tile >= n_blocks * n_splits) return;       // padding (whole workgroup leaves)
+  const int by = tile / n_blocks, bx = tile - by * n_blocks;
   constexpr int E = Frag<T>::kElems;
   constexpr int KS = Frag<T>::kStep;
   constexpr int KC = kSteps * KS;                // elements per chunk (= 256 bytes)
@@ -148,8 +162,65 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_rows_kernel(
     }
   };
 
-  // prologue: weight chunks 0..PB-1 and activation chunks 0, 1 are requested; chunk 0 reaches LDS
   if (n_chunks <= 0) return;
+  if constexpr (NT >= 4) {
+    // Many rows: 128 x 64 outputs per wave, one wave per SIMD.  Nothing else hides latencies here, so the
+    // loop is pipelined by hand and the scheduler is told to keep the interleaving:
+    //   * the activation fragments are read from LDS three matrix-core groups ahead of their use;
+    //   * the weight registers of a k-step are refilled as soon as that step is done, with the same step
+    //     of the chunk two ahead (two chunks of flight time: an L2 miss costs more than one);
+    //   * the next activation chunk is requested at the top of an iteration and stored behind it.
+    // The launcher guarantees whole chunks and an even number of them per split: nothing to mask.
+    static_assert(RING == 2, "the wide loop keeps two weight chunks");
+    constexpr int NI = kSteps * MT;
+    auto load_b_step = [&](Frag<T> (&b)[NT][kSteps], int chunk, int step) {
+      const size_t off = PRE ? (size_t)(chunk_k(chunk) / KC) * kBlockElems + step * 64 * E
+                             : (size_t)(chunk_k(chunk) + step * KS + g * E);
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) b[nt][step].raw = ld16(wrow[nt] + off);
+    };
+    load_a(areg[0], 0);
+    load_b(breg[0], 0);
+    load_b(breg[1], 1);
+    store_a(areg[0], 0);
+    __syncthreads();
+    for (int base = 0; base < n_chunks; base += 2) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int c = base + u;
+        load_a(areg[0], c + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        const unsigned char* abuf = lds[u];
+        auto read_af = [&](int i) {
+          Frag<T> f;
+          f.raw = *reinterpret_cast<const u32x4*>(&abuf[((i % MT) * 16 + r) * kRowStride + ((i / MT) * 4 + g) * 16]);
+          return f;
+        };
+        Frag<T> af[4];
+        af[0] = read_af(0);
+        af[1] = read_af(1);
+        af[2] = read_af(2);
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) mfma16(acc[i % MT][nt], af[i % 4], breg[u][nt][i / MT]);
+          if (i + 3 < NI) af[(i + 3) % 4] = read_af(i + 3);
+          if (i % MT == MT - 1) load_b_step(breg[u], c + 2, i / MT);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, NT, 0);                          // NT matrix-core instructions
+          if (i + 3 < NI) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);           // one LDS read
+          if (i % MT == MT - 1) __builtin_amdgcn_sched_group_barrier(0x020, NT, 0);    // the k-step's refill
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        store_a(areg[0], u ^ 1);
+        __syncthreads();
+      }
+    }
+  } else {
+  // prologue: weight chunks 0..PB-1 and activation chunks 0, 1 are requested; chunk 0 reaches LDS
 #pragma unroll
   for (int u = 0; u < PB; ++u) load_b(breg[u], u);
   load_a(areg[0], 0);
@@ -191,19 +262,25 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_rows_kernel(
     }
   }
 
-  if (MODE == kPreSwiglu && NT == 2) {
-    // Column tiles alternate gate, up, gate, up ..: with two tiles per wave the pair sits in one wave
+  }   // narrow loop
+
+  if (MODE == kPreSwiglu && NT % 2 == 0) {
+    // Column tiles alternate gate, up, gate, up ..: with an even number of tiles per wave each pair sits in one wave
     const int F = N >> 1;
-    const int col = (n_base >> 5) * 16 + r;                     // n_base = 32 * (hidden tile)
-    if (col >= F) return;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int p = 0; p < NT / 2; ++p) {
+      const int col = ((n_base >> 5) + p) * 16 + r;             // n_base = 32 * (first hidden tile of the wave)
+      if (col >= F) continue;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int row = row0 + mt * 16 + g * 4 + j;
-        const float gv = acc[mt][0][j];
-        if (row < m) act[(size_t)row * F + col] = from_f32<T>(gv / (1.0f + expf(-gv)) * acc[mt][NT - 1][j]);
-      }
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int row = row0 + mt * 16 + g * 4 + j;
+          const float gv = acc[mt][2 * p][j];
+          if (row < m)
+            act[(size_t)row * F + col] = from_f32<T>(gv / (1.0f + expf(-gv)) * acc[mt][NT > 1 ? 2 * p + 1 : 0][j]);
+        }
+    }
     return;
   }
   if (MODE == kPreSwiglu) {
@@ -255,6 +332,9 @@ hipError_t launch_t(const GemmPlan& pl, const void* A, int lda, const void* W, i
   const int n_blocks = (N + cols - 1) / cols;
   const int groups = (n_blocks * pl.splits + 7) / 8;            // weight tiles are dealt to the XCDs in groups of 8
   dim3 grid(groups * 8 * pl.row_chunks);
+  if (NT >= 4)
+    grid.x = 8 * ((groups + kSuperCols - 1) / kSuperCols) * ((pl.row_chunks + kSuperRows - 1) / kSuperRows) *
+             (kSuperRows * kSuperCols);
   hipLaunchKernelGGL((gemm_rows_kernel<T, MT, NT, WAVES, MODE>), grid, dim3(WAVES * 64), 0, st, (const T*)A, lda,
                      (const T*)W, ldw, P, ldp, split_stride, m, N, K, pl.k_per_split, n_blocks, pl.splits,
                      pl.row_chunks, pl.rot, (T*)act);
@@ -284,6 +364,15 @@ hipError_t launch_nt(const GemmPlan& pl, const void* A, int lda, const void* W, 
   if (pl.nt == 1) {
     if (pl.waves == 8) return launch_mt<T, 1, 8, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
     return launch_mt<T, 1, 4, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+  }
+  if (pl.nt == 4) {
+    // 128 rows x 64 columns per wave, one wave per SIMD: only for full row chunks in bf16
+    if constexpr (sizeof(T) == 2) {
+      const int kc = 256 / (int)sizeof(T);
+      if (pl.mt == 8 && pl.waves == 4 && K % kc == 0 && pl.k_per_split % (2 * kc) == 0 && K % (2 * kc) == 0)
+        return launch_t<T, 8, 4, 4, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+    }
+    return hipErrorInvalidValue;
   }
   if (pl.waves == 8) return launch_mt<T, 2, 8, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
   return launch_mt<T, 2, 4, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
@@ -321,10 +410,14 @@ GemmPlan plan_gemm(int dtype, int m, int N, int K, bool single_split) {
   // two column tiles per wave halve the LDS reads per matrix-core step: a gain once there are several
   // row chunks (the kernel is LDS- and L2-bound there), a loss for a handful of rows (fewer waves in flight)
   pl.nt = (N > t.gemm_nt_big_n || tiles > 8) ? 2 : 1;
+  // several row chunks in bf16: four column tiles per wave and one wave per SIMD (128 x 64 outputs per wave)
+  // halve the LDS reads per matrix-core step once more
+  const bool wide = tiles > 8 && dtype == kBF16 && t.gemm_wide_tiles && K % 256 == 0;   // needs an even number of whole chunks
+  if (wide) pl.nt = 4;
   pl.rot = t.gemm_rot;
   // 8 waves share one activation chunk in LDS: fewer, fatter workgroups (about 1.5 per compute unit) with
   // fewer k splits measured faster than 4-wave groups at every projection shape of the two models
-  pl.waves = t.gemm_waves == 4 ? 4 : 8;
+  pl.waves = (t.gemm_waves == 4 || wide) ? 4 : 8;
   const int kc = dtype == kBF16 ? 128 : 64;                       // elements per 256-byte chunk
   const int n_blocks = (N + 16 * pl.nt * pl.waves - 1) / (16 * pl.nt * pl.waves);
   const int chunks = (K + kc - 1) / kc;
@@ -332,7 +425,8 @@ GemmPlan plan_gemm(int dtype, int m, int N, int K, bool single_split) {
   while (!single_split && splits < t.gemm_max_splits && n_blocks * (pl.waves / 4) * pl.row_chunks * splits < t.gemm_target_wgs &&
          chunks / (splits * 2) >= 2)
     splits *= 2;
-  const int chunks_per_split = (chunks + splits - 1) / splits;
+  int chunks_per_split = (chunks + splits - 1) / splits;
+  if (wide) chunks_per_split += chunks_per_split & 1;
   pl.k_per_split = chunks_per_split * kc;
   pl.splits = (K + pl.k_per_split - 1) / pl.k_per_split;
   return pl;

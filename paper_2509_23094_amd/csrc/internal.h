@@ -14,6 +14,7 @@ inline size_t dtype_size(int dt) { return dt == kBF16 ? 2 : 4; }
 struct Tunables {
   int gemm_target_wgs = 384;   // aim for at least this many groups of 4 waves per GEMM
   int gemm_max_splits = 8;
+  int gemm_wide_tiles = 1;     // more than 128 rows in bf16: 128 x 64 outputs per wave, 4 waves per workgroup
   int gemm_nt_big_n = 1 << 30; // N above this uses two column tiles per wave even for few rows (measured slower);
                                // more than 128 rows always do
   int gemm_waves = 0;          // waves per workgroup sharing one activation chunk in LDS: 4, 8; 0 = by shape
