@@ -11,7 +11,7 @@ Prints one JSON line.  value = timed steps / wall time between two device synchr
 roofline = algorithmic weight bytes of the projection launches / their HIP-event durations
 (a second pass over the same steps with an event pair around every launch), against 8 TB/s;
 full_recompute = the same engine with every row selected; cpu_baseline = the CPU oracle on a
-bounded sample of the same workload.  --workload C4 / C5 / C2 run the other configurations.
+bounded sample of the same workload.  --workload C4 / C5 / C6 / C2 run the other configurations.
 """
 import argparse
 import json
@@ -165,7 +165,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=128)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="C3", choices=["C3", "C4", "C5", "C2"],
+    ap.add_argument("--workload", default="C3", choices=["C3", "C4", "C5", "C6", "C2"],
                     help="C3 (default, the metric's workload), C4, or C2 = the isolated selective-refresh attention op")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (the result is then not the metric)")
     ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
@@ -297,7 +297,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: %s-shaped random-init model, %d layers, d_model %d, %dx%d heads, FFN %d, "
                                "vocab %d; prompt %d + gen %d, block %d, %d token/step, sigma %g k %d p %g"
-                               % (args.workload, {"C3": "LLaDA-8B", "C4": "Dream-7B", "C5": "LLaDA-8B"}[args.workload], dims.n_layers, dims.d_model, dims.n_heads, dims.head_dim, dims.d_ffn,
+                               % (args.workload, {"C3": "LLaDA-8B", "C4": "Dream-7B", "C5": "LLaDA-8B", "C6": "Dream-7B"}[args.workload], dims.n_layers, dims.d_model, dims.n_heads, dims.head_dim, dims.d_ffn,
                                   dims.vocab, su.prompt_len, su.gen_len, su.block_len, su.n_unmask, su.sigma, su.k,
                                   su.p),
                    "batch": su.batch, "seq_len": su.seq_len, "mean_rows_per_step": round(mean_m, 2),

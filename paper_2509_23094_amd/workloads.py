@@ -61,7 +61,7 @@ class DecodeSetup:
         return self.prompt_len + self.gen_len
 
 
-# The five workloads.  C3-C5 use the paper's default hyper-parameters
+# The workloads.  C3-C6 use the paper's default hyper-parameters
 # (sigma = 10, k = 32, p = 0.1; "Implementation details" in Sec. 5.1).
 DIMS = {
     "C1": ModelDims(2, 256, 4, 4, 64, 688, 1024, dtype="f32"),
@@ -69,11 +69,14 @@ DIMS = {
     "C4": ModelDims(28, 3584, 28, 4, 128, 18944, 152064, dtype="bf16"),
 }
 DIMS["C5"] = DIMS["C3"]
+DIMS["C6"] = DIMS["C4"]
 SETUP = {
     "C1": DecodeSetup(64, 64, 32, 1, k=8, p=0.9),
     "C3": DecodeSetup(256, 256, 32, 1, k=32, p=0.1),
     "C4": DecodeSetup(512, 256, 32, 1, k=32, p=0.1),
     "C5": DecodeSetup(2048, 1024, 64, 2, k=32, p=0.1, batch=4),
+    # long generation at the Dream-7B shape (the long-context table of Appendix: gen 1024, prompts up to ~800)
+    "C6": DecodeSetup(800, 1024, 32, 1, k=32, p=0.1),
 }
 
 

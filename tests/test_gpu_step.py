@@ -243,6 +243,16 @@ def test_step_bf16_many_rows_per_step(B):
     _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=6)
 
 
+def test_step_bf16_long_sequence_few_rows(B):
+    """More than 1024 positions with a few dozen selected rows per step (the long-generation regime): the
+    few-row attention kernel cannot keep its scores, so every layer runs the second Q K^T pass for the head
+    average on the second stream; grouped-query geometry (8 query heads on 2 kv heads)."""
+    wd = W.ModelDims(2, 512, 8, 2, 64, 1024, 1024, dtype="bf16")
+    su = W.DecodeSetup(1040, 64, 32, 1, k=16, p=0.02)
+    mdl = W.model_weights(wd, 9)
+    _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=3)
+
+
 def test_step_batch_of_ragged_sequences(B):
     """Two independent sequences of different length in one d2c_step call equal two separate calls."""
     wd = W.ModelDims(2, 256, 4, 4, 64, 688, 512, dtype="bf16")
