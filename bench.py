@@ -11,7 +11,7 @@ Prints one JSON line.  value = timed steps / wall time between two device synchr
 roofline = algorithmic weight bytes of the projection launches / their HIP-event durations
 (a second pass over the same steps with an event pair around every launch), against 8 TB/s;
 full_recompute = the same engine with every row selected; cpu_baseline = the CPU oracle on a
-bounded sample of the same workload.  --workload C4 / C5 / C6 / C2 run the other configurations.
+bounded sample of the same workload.  --workload C4 / C5 / C6 / C2 / select run the other configurations.
 """
 import argparse
 import json
@@ -109,6 +109,76 @@ def cpu_baseline(W, dims, su, m_rows, n_logit_rows, n_steps=2):
                        % (n_steps, m_rows, n_logit_rows, L, total, dims.n_layers, t_layers, t_roll, t_head, t_sel))}
 
 
+def bench_select_op(args, B, W, torch, np):
+    """The isolated two-stage selection (Eq. 1, 3, 4, top-p over the influence scores) at the two sequence
+    lengths of the step workloads, on two input regimes: weakly structured scores (what random-init weights
+    give) and skewed ones (a few sink positions carry most of the influence, a Zipf-like tail, and a few
+    confident rows), which is what trained models show.  Latency-bound: reported in microseconds per call."""
+    # every call decodes one token in place, so the masked set shrinks by one per call: the repetitions are
+    # capped well below the ~180 masked positions the inputs start with
+    K, Wm = min(args.steps, 64), min(args.warmup, 8)
+    res = {}
+    for L, P, V, k, n_rows in ((512, 256, 126464, 32, 32), (3072, 2048, 126464, 32, 32)):
+        wd = W.ModelDims(1, 64, 4, 4, 16, 80, V, dtype="f32")
+        mdl = W.model_weights(W.ModelDims(1, 64, 4, 4, 16, 80, 8, dtype="f32"), 0)
+        mdl["tok_emb"] = mdl["lm_head"] = np.zeros((V, 64), np.float32)      # the selection never reads them
+        ctx = B.Context(wd, mdl, L)
+        prm = B.make_params(10.0, k, 0.1, 32, 1, 0)
+        is_masked = W.random_mask(L, L, P, 0.3).astype(bool)
+        y = np.where(is_masked, wd.mask_id, 7).astype(np.int32)
+        masked_pos = np.flatnonzero(is_masked)
+        logit_pos = masked_pos[:n_rows].astype(np.int32)
+        logits = W.logits_rows(L, len(logit_pos), V)
+        for regime in ("weak", "skewed"):
+            if regime == "weak":
+                conf, c = W.random_scores(L, L), W.random_scores(L + 1, L) + np.float32(0.5)
+            else:
+                conf = (W.random_scores(L, L) ** 8).astype(np.float32)
+                c = W.skewed_influence(L, L)
+            t = {"tokens": torch.from_numpy(y).cuda(), "is_masked": torch.from_numpy(is_masked.astype(np.uint8)).cuda(),
+                 "conf": torch.from_numpy(conf.astype(np.float32)).cuda(),
+                 "pred": torch.zeros(L, dtype=torch.int32, device="cuda"),
+                 "influence": torch.from_numpy(c.astype(np.float32)).cuda(),
+                 "counts": torch.zeros(B.N_COUNTS, dtype=torch.int32, device="cuda"),
+                 "score": torch.zeros(L, dtype=torch.float32, device="cuda")}
+            for name in ("mstar", "u_set", "decode_idx", "s_next", "s_rows_next"):
+                t[name] = torch.full((L,), -1, dtype=torch.int32, device="cuda")
+            lg, lp = torch.from_numpy(logits).cuda(), torch.from_numpy(logit_pos).cuda()
+
+            def call():
+                ctx.d2c_select(prm, lg, lp, len(logit_pos), t["tokens"], t["is_masked"], L, P, t["conf"], t["pred"],
+                               t["influence"], t["mstar"], t["u_set"], t["decode_idx"], t["s_next"], t["s_rows_next"],
+                               t["counts"], t["score"])
+            for _ in range(Wm):
+                call()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(K):
+                call()
+            e1.record()
+            torch.cuda.synchronize()
+            cnt = t["counts"].cpu().numpy()
+            res["L%d_%s" % (L, regime)] = {"us_per_call": round(1e3 * e0.elapsed_time(e1) / K, 2),
+                                           "n_mstar": int(cnt[B.CNT_MSTAR]), "n_u": int(cnt[B.CNT_U]),
+                                           "logit_rows": int(len(logit_pos)), "vocab": V}
+        ctx.close()
+    main_r = res["L512_skewed"]
+    logits_bytes = 32 * 126464 * 4
+    return {
+        "metric": "selection_calls_per_sec", "value": round(1e6 / main_r["us_per_call"], 1), "unit": "calls/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(main_r["us_per_call"] / 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "isolated d2c_select: 32 logit rows x vocab 126464, L 512 (and 3072), sigma 10, k 32, "
+                               "p 0.1; weakly structured and skewed confidence / influence inputs"},
+        "roofline": {"bound": "hbm", "achieved": round(logits_bytes / main_r["us_per_call"] / 1e3, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(logits_bytes / main_r["us_per_call"] / 1e3 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "note": "latency-bound chain of three small launches; the only streamed bytes are the logits"},
+        "variants": res, "cpu_baseline": None,
+    }
+
+
 def bench_attention_op(args, B, W, torch, np):
     """The isolated selective-refresh attention op: scatter of m new K/V rows, then m queries against all
     L cached keys, no mask, with and without the head-averaged probabilities.  One "step" = one call."""
@@ -165,7 +235,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=128)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="C3", choices=["C3", "C4", "C5", "C6", "C2"],
+    ap.add_argument("--workload", default="C3", choices=["C3", "C4", "C5", "C6", "C2", "select"],
                     help="C3 (default, the metric's workload), C4, or C2 = the isolated selective-refresh attention op")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (the result is then not the metric)")
     ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
@@ -205,6 +275,9 @@ def main():
         return
     if args.workload == "C2":
         print(json.dumps(bench_attention_op(args, B, W, torch, np)))
+        return
+    if args.workload == "select":
+        print(json.dumps(bench_select_op(args, B, W, torch, np)))
         return
     dims, su = W.DIMS[args.workload], W.SETUP[args.workload]
     if args.layers:
