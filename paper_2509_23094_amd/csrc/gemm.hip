@@ -363,6 +363,7 @@ hipError_t launch_nt(const GemmPlan& pl, const void* A, int lda, const void* W, 
                      size_t ss, int m, int N, int K, hipStream_t st, void* act) {
   if (pl.nt == 1) {
     if (pl.waves == 8) return launch_mt<T, 1, 8, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+    if (pl.waves == 6) return launch_mt<T, 1, 6, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
     return launch_mt<T, 1, 4, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
   }
   if (pl.nt == 4) {
@@ -417,14 +418,34 @@ GemmPlan plan_gemm(int dtype, int m, int N, int K, bool single_split) {
   pl.rot = t.gemm_rot;
   // 8 waves share one activation chunk in LDS: fewer, fatter workgroups (about 1.5 per compute unit) with
   // fewer k splits measured faster than 4-wave groups at every projection shape of the two models
-  pl.waves = (t.gemm_waves == 4 || wide) ? 4 : 8;
+  pl.waves = wide ? 4 : (t.gemm_waves == 4 || t.gemm_waves == 6) ? t.gemm_waves : 8;
   const int kc = dtype == kBF16 ? 128 : 64;                       // elements per 256-byte chunk
-  const int n_blocks = (N + 16 * pl.nt * pl.waves - 1) / (16 * pl.nt * pl.waves);
   const int chunks = (K + kc - 1) / kc;
-  int splits = 1;
-  while (!single_split && splits < t.gemm_max_splits && n_blocks * (pl.waves / 4) * pl.row_chunks * splits < t.gemm_target_wgs &&
-         chunks / (splits * 2) >= 2)
-    splits *= 2;
+  const int max_splits = single_split ? 1 : t.gemm_max_splits;
+  auto blocks_of = [&](int waves) { return (N + 16 * pl.nt * waves - 1) / (16 * pl.nt * waves); };
+  auto splits_for = [&](int waves) {
+    int s = 1;
+    while (s < max_splits && blocks_of(waves) * (waves / 4) * pl.row_chunks * s < t.gemm_target_wgs && chunks / (s * 2) >= 2)
+      s *= 2;
+    return s;
+  };
+  int splits = splits_for(pl.waves);
+  // A launch of exactly one (or two) equal workgroups per compute unit streams measurably faster than one
+  // that leaves a quarter of the units without a workgroup (LLaDA's QKV: +11 %, gate/up: +1..8 %): where the
+  // 8-wave shape does not give a multiple of the unit count and a 6-wave shape does, take the 6-wave one.
+  constexpr int kUnits = 256;
+  if (!wide && t.gemm_waves == 0 && pl.nt == 1 && pl.row_chunks == 1 && (blocks_of(8) * splits) % kUnits != 0 &&
+      ((N + 15) / 16) % 6 == 0) {
+    for (int s = 1; s <= max_splits && chunks / (s * 2) >= 2; s *= 2) {
+      const int wgs = blocks_of(6) * s;
+      if (wgs % kUnits == 0 && wgs <= 2 * kUnits && chunks % s == 0) {
+        pl.waves = 6;
+        splits = s;
+        break;
+      }
+      if (s == max_splits) break;
+    }
+  }
   int chunks_per_split = (chunks + splits - 1) / splits;
   if (wide) chunks_per_split += chunks_per_split & 1;
   pl.k_per_split = chunks_per_split * kc;
