@@ -364,6 +364,7 @@ hipError_t launch_nt(const GemmPlan& pl, const void* A, int lda, const void* W, 
   if (pl.nt == 1) {
     if (pl.waves == 8) return launch_mt<T, 1, 8, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
     if (pl.waves == 6) return launch_mt<T, 1, 6, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+    if (pl.waves == 10) return launch_mt<T, 1, 10, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
     return launch_mt<T, 1, 4, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
   }
   if (pl.nt == 4) {
@@ -418,7 +419,7 @@ GemmPlan plan_gemm(int dtype, int m, int N, int K, bool single_split) {
   pl.rot = t.gemm_rot;
   // 8 waves share one activation chunk in LDS: fewer, fatter workgroups (about 1.5 per compute unit) with
   // fewer k splits measured faster than 4-wave groups at every projection shape of the two models
-  pl.waves = wide ? 4 : (t.gemm_waves == 4 || t.gemm_waves == 6) ? t.gemm_waves : 8;
+  pl.waves = wide ? 4 : (t.gemm_waves == 4 || t.gemm_waves == 6 || t.gemm_waves == 10) ? t.gemm_waves : 8;
   const int kc = dtype == kBF16 ? 128 : 64;                       // elements per 256-byte chunk
   const int chunks = (K + kc - 1) / kc;
   const int max_splits = single_split ? 1 : t.gemm_max_splits;
@@ -430,20 +431,31 @@ GemmPlan plan_gemm(int dtype, int m, int N, int K, bool single_split) {
     return s;
   };
   int splits = splits_for(pl.waves);
-  // A launch of exactly one (or two) equal workgroups per compute unit streams measurably faster than one
-  // that leaves a quarter of the units without a workgroup (LLaDA's QKV: +11 %, gate/up: +1..8 %): where the
-  // 8-wave shape does not give a multiple of the unit count and a 6-wave shape does, take the 6-wave one.
+  // Few rows (one row chunk, one column tile per wave): the kernel streams fastest when every compute unit
+  // holds one workgroup of equal size, so the waves per workgroup and the split count are chosen together.
+  // Cost of a shape = rounds of workgroups over the 256 units x (waves x chunks per split), +4 % per
+  // additional split (its partial is written and read again).  Measured at 48-69 rows: LLaDA QKV 25.1 ->
+  // 22.5 us (6 waves x 2 splits = 256 workgroups instead of 8 x 2 = 192), Dream gate/up 68.6 -> 51.5 us
+  // (10 waves = 237 workgroups in one round instead of 296 in two); 4-wave workgroups were slower at every
+  // shape and are not searched.
   constexpr int kUnits = 256;
-  if (!wide && t.gemm_waves == 0 && pl.nt == 1 && pl.row_chunks == 1 && (blocks_of(8) * splits) % kUnits != 0 &&
-      ((N + 15) / 16) % 6 == 0) {
-    for (int s = 1; s <= max_splits && chunks / (s * 2) >= 2; s *= 2) {
-      const int wgs = blocks_of(6) * s;
-      if (wgs % kUnits == 0 && wgs <= 2 * kUnits && chunks % s == 0) {
-        pl.waves = 6;
-        splits = s;
-        break;
+  if (pl.nt == 1 && pl.row_chunks == 1) {
+    double best = 1e30;
+    for (int w : {8, 6, 10}) {                                    // 8 first: ties keep the 8-wave shape
+      if (t.gemm_waves != 0 && w != pl.waves) continue;
+      for (int s = 1; s <= max_splits; s *= 2) {
+        const int cps = (chunks + s - 1) / s;
+        if (s > 1 && cps < 2) break;
+        const int eff = (chunks + cps - 1) / cps;
+        const int wgs = blocks_of(w) * eff;
+        const int rounds = (wgs + kUnits - 1) / kUnits;
+        const double cost = (double)rounds * w * cps * (1.0 + 0.04 * (eff - 1));
+        if (cost < best * 0.999) {
+          best = cost;
+          pl.waves = w;
+          splits = s;
+        }
       }
-      if (s == max_splits) break;
     }
   }
   int chunks_per_split = (chunks + splits - 1) / splits;

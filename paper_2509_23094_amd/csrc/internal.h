@@ -17,7 +17,7 @@ struct Tunables {
   int gemm_wide_tiles = 1;     // more than 128 rows in bf16: 128 x 64 outputs per wave, 4 waves per workgroup
   int gemm_nt_big_n = 1 << 30; // N above this uses two column tiles per wave even for few rows (measured slower);
                                // more than 128 rows always do
-  int gemm_waves = 0;          // waves per workgroup sharing one activation chunk in LDS: 4, 8; 0 = by shape
+  int gemm_waves = 0;          // waves per workgroup sharing one activation chunk in LDS: 4, 6, 8, 10; 0 = by shape
   bool gemm_preshuffle = true; // d2c_init keeps pre-tiled copies of the projection matrices (costs their size again)
   int gemm_rot = 0;            // start chunk of a workgroup's k walk = (column block * this) % chunks
   int attn_tiled_min_m = 96;   // bf16 attention: from this many query rows on, the LDS-tiled kernels
