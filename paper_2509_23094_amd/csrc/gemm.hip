@@ -458,6 +458,23 @@ GemmPlan plan_gemm(int dtype, int m, int N, int K, bool single_split) {
       }
     }
   }
+  if (wide && !single_split) {
+    // Many rows: the same count of rounds, with +7 % per additional split (the partials are as large as
+    // the output and there are hundreds of rows of them)
+    double best = 1e30;
+    for (int s = 1; s <= max_splits; s *= 2) {
+      int cps = (chunks + s - 1) / s;
+      cps += cps & 1;                                             // the wide loop takes chunks in pairs
+      if (s > 1 && cps < 4) break;
+      const int eff = (chunks + cps - 1) / cps;
+      const int wgs = blocks_of(pl.waves) * pl.row_chunks * eff;
+      const double cost = (double)((wgs + kUnits - 1) / kUnits) * cps * (1.0 + 0.07 * (eff - 1));
+      if (cost < best * 0.999) {
+        best = cost;
+        splits = s;
+      }
+    }
+  }
   int chunks_per_split = (chunks + splits - 1) / splits;
   if (wide) chunks_per_split += chunks_per_split & 1;
   pl.k_per_split = chunks_per_split * kc;
