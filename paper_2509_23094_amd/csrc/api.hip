@@ -224,7 +224,7 @@ int layer_impl(d2c_ctx* c, int layer, float* hidden, const Seg* segs, int n_seg,
       D2C_TIMED(c, side, D2C_PROF_ATTN_AVG, 0.0,
                 launch_attention_avg(dt, q + (size_t)g.off * dq * ts, g.k_cache, lse + (size_t)D.n_heads * g.off, g.m,
                                      g.L, D.n_heads, D.n_kv_heads, D.head_dim, g.abar, c->avg_part,
-                                     c->avg_part_floats, side));
+                                     c->avg_part_floats, side, /*one_group=*/side != st));
       if (g.roll_out)
         D2C_TIMED(c, side, D2C_PROF_ROLLOUT, 0.0,
                   launch_rollout(g.abar, g.roll_in, g.roll_out, g.idx, g.m, g.L, layer == 0, side));
@@ -418,6 +418,7 @@ int d2c_set_tunable(const char* name, int32_t value) {
   else if (!strcmp(name, "gemm_max_splits")) t.gemm_max_splits = std::max(1, std::min(8, (int)value));
   else if (!strcmp(name, "gemm_nt_big_n")) t.gemm_nt_big_n = value;
   else if (!strcmp(name, "gemm_wide_tiles")) t.gemm_wide_tiles = value;
+  else if (!strcmp(name, "attn_side_groups")) t.attn_side_groups = value;
   else if (!strcmp(name, "gemm_waves")) t.gemm_waves = (value == 8 || value == 4 || value == 6 || value == 10) ? value : 0;
   else if (!strcmp(name, "gemm_preshuffle")) t.gemm_preshuffle = value != 0;
   else if (!strcmp(name, "gemm_rot")) t.gemm_rot = value < 0 ? 0 : value;

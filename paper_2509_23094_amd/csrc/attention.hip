@@ -538,13 +538,13 @@ size_t attention_avg_scratch_floats(int dtype, int max_m, int max_L, int n_heads
 
 hipError_t launch_attention_avg(int dtype, const void* q, const void* k_cache, const float* lse, int m, int L,
                                 int n_heads, int n_kv_heads, int head_dim, float* attn_avg, float* scratch,
-                                size_t scratch_floats, hipStream_t st) {
+                                size_t scratch_floats, hipStream_t st, bool one_group) {
   if (m <= 0) return hipSuccess;
   if (L <= 0 || n_heads % n_kv_heads) return hipErrorInvalidValue;
   if (dtype == kBF16) {
     if (m >= tunables().attn_tiled_min_m)
       return launch_attention_tiled_avg(q, k_cache, lse, m, L, n_heads, n_kv_heads, head_dim, attn_avg, scratch,
-                                        scratch_floats, st);
+                                        scratch_floats, st, one_group);
     if (head_dim == 128) return launch_avg_bf16<128>(q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, st);
     if (head_dim == 64) return launch_avg_bf16<64>(q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, st);
     return hipErrorInvalidValue;

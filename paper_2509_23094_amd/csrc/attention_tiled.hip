@@ -517,7 +517,7 @@ hipError_t launch_fwd(const void* q, const void* k_cache, const void* v_cache, i
 struct AvgPlan {
   int ka, qt, key_blocks, q_blocks, groups, heads_per_group;
 };
-AvgPlan plan_avg(int m, int L, int n_heads) {
+AvgPlan plan_avg(int m, int L, int n_heads, bool one_group = false) {
   AvgPlan p;
   // the largest tile the row and key counts fill: 128 x 128, 64 x 128 (m <= 64) or 64 x 32 (L <= 32)
   p.qt = m > 64 ? 2 : 1;
@@ -526,8 +526,11 @@ AvgPlan plan_avg(int m, int L, int n_heads) {
   p.key_blocks = (L + 16 * p.ka - 1) / (16 * p.ka);
   // The loop over the heads is a chain of dependent load latencies: when the tile grid alone leaves
   // most of the chip idle, the heads are dealt to several workgroups per tile.
+  // one_group: the caller runs the launch beside other work and wants less total work rather than the
+  // shortest launch: fewer head groups, fewer partials to add
   int groups = 1;
-  while (groups < 8 && groups * 2 <= n_heads && (size_t)p.q_blocks * p.key_blocks * groups < 2 * kTargetWgs) groups *= 2;
+  const int max_groups = one_group ? std::max(1, std::min(8, tunables().attn_side_groups)) : 8;
+  while (groups < max_groups && groups * 2 <= n_heads && (size_t)p.q_blocks * p.key_blocks * groups < 2 * kTargetWgs) groups *= 2;
   p.heads_per_group = (n_heads + groups - 1) / groups;
   p.groups = (n_heads + p.heads_per_group - 1) / p.heads_per_group;
   return p;
@@ -535,9 +538,10 @@ AvgPlan plan_avg(int m, int L, int n_heads) {
 
 template <int DH>
 hipError_t launch_avg(const void* q, const void* k_cache, const float* lse, int m, int L, int n_heads,
-                      int n_kv_heads, float* attn_avg, float* scratch, size_t scratch_floats, hipStream_t st) {
+                      int n_kv_heads, float* attn_avg, float* scratch, size_t scratch_floats, hipStream_t st,
+                      bool one_group) {
   const float scale = 1.0f / sqrtf((float)DH);
-  const AvgPlan p = plan_avg(m, L, n_heads);
+  const AvgPlan p = plan_avg(m, L, n_heads, one_group);
   if (p.groups > 1 && (!scratch || (size_t)p.groups * m * L > scratch_floats)) return hipErrorInvalidValue;
   float* dst = p.groups > 1 ? scratch : attn_avg;
   const dim3 grid(p.q_blocks, p.key_blocks, p.groups);
@@ -598,11 +602,13 @@ size_t attention_tiled_avg_scratch_floats(int max_m, int max_L, int n_heads) {
 
 hipError_t launch_attention_tiled_avg(const void* q, const void* k_cache, const float* lse, int m, int L,
                                       int n_heads, int n_kv_heads, int head_dim, float* attn_avg, float* scratch,
-                                      size_t scratch_floats, hipStream_t st) {
+                                      size_t scratch_floats, hipStream_t st, bool one_group) {
   if (head_dim == 128)
-    return launch_avg<128>(q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, scratch, scratch_floats, st);
+    return launch_avg<128>(q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, scratch, scratch_floats, st,
+                           one_group);
   if (head_dim == 64)
-    return launch_avg<64>(q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, scratch, scratch_floats, st);
+    return launch_avg<64>(q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, scratch, scratch_floats, st,
+                          one_group);
   return hipErrorInvalidValue;
 }
 

@@ -14,6 +14,7 @@ inline size_t dtype_size(int dt) { return dt == kBF16 ? 2 : 4; }
 struct Tunables {
   int gemm_target_wgs = 384;   // aim for at least this many groups of 4 waves per GEMM
   int gemm_max_splits = 8;
+  int attn_side_groups = 4;    // most head groups of the head average when it runs beside other work (d2c_step)
   int gemm_wide_tiles = 1;     // more than 128 rows in bf16: 128 x 64 outputs per wave, 4 waves per workgroup
   int gemm_nt_big_n = 1 << 30; // N above this uses two column tiles per wave even for few rows (measured slower);
                                // more than 128 rows always do
@@ -100,9 +101,11 @@ hipError_t launch_head_mean(const float* probs, size_t probs_layer_stride, float
 // avg: attn_avg float [m, L] = mean over heads of exp(q k / sqrt(dh) - lse); needs fwd's lse
 // scratch: attention_avg_scratch_floats(...) floats (per-head-group partials), may be null for fp32
 size_t attention_avg_scratch_floats(int dtype, int max_m, int max_L, int n_heads);
+// one_group: least total work (no head groups, no partials) instead of the shortest launch, for a caller
+// that runs the head average beside other work
 hipError_t launch_attention_avg(int dtype, const void* q, const void* k_cache, const float* lse, int m, int L,
                                 int n_heads, int n_kv_heads, int head_dim, float* attn_avg, float* scratch,
-                                size_t scratch_floats, hipStream_t st);
+                                size_t scratch_floats, hipStream_t st, bool one_group = false);
 
 // the bf16 kernels for many query rows (K/V blocks staged through LDS, optional key split + merge)
 size_t attention_tiled_scratch_floats(int max_m, int max_L, int n_heads, int head_dim);
@@ -112,7 +115,7 @@ hipError_t launch_attention_tiled_fwd(const void* q, const void* k_cache, const 
 size_t attention_tiled_avg_scratch_floats(int max_m, int max_L, int n_heads);
 hipError_t launch_attention_tiled_avg(const void* q, const void* k_cache, const float* lse, int m, int L,
                                       int n_heads, int n_kv_heads, int head_dim, float* attn_avg, float* scratch,
-                                      size_t scratch_floats, hipStream_t st);
+                                      size_t scratch_floats, hipStream_t st, bool one_group = false);
 
 // ---- rollout on the compact block: c_out = (A[:,S] c_in + A[:,notS] + c_in) / 2; first: c_in = one-hot rows
 hipError_t launch_rollout(const float* attn_avg, const float* c_in, float* c_out, const int32_t* idx, int m, int L,
