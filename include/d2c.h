@@ -233,10 +233,15 @@ int d2c_profile_begin(d2c_ctx* ctx);
 int d2c_profile_end(d2c_ctx* ctx, double* ms, int64_t* launches, double* bytes);
 
 /* Launch-shape tunables, process-wide; set them before d2c_init.  Names:
- * "gemm_target_wgs", "gemm_max_splits" (1..8), "gemm_nt_big_n", "gemm_waves" (4, 8; 0 = chosen by shape), "gemm_preshuffle" (0/1), "gemm_rot"
- * for the projection kernel; "attn_tiled_min_m" (bf16 attention switches to the LDS-tiled kernels from
- * this many query rows on), "attn_max_splits" (1..8, key-range splits of one attention launch); "side_stream" (0/1: whether d2c_step runs the head
- * average and the rollout on a second stream).  Returns D2C_EINVAL for an unknown name. */
+ * projection kernel: "gemm_waves" (waves per workgroup: 4, 6, 8, 10; 0 = chosen by shape together with the
+ * split count), "gemm_max_splits" (1..8), "gemm_target_wgs" (workgroups aimed at where the shape search does
+ * not apply), "gemm_nt_big_n", "gemm_wide_tiles" (0/1: 128 x 64 outputs per wave for more than 128 bf16 rows),
+ * "gemm_preshuffle" (0/1: pre-tiled weight copies), "gemm_rot";
+ * attention: "attn_tiled_min_m" (bf16 attention switches to the LDS-tiled kernels from this many query rows
+ * on), "attn_max_splits" (1..8, key-range splits of one attention launch), "attn_qt", "attn_target_wgs",
+ * "attn_side_groups" (1..8: most head groups of the head average when d2c_step runs it beside the projections);
+ * "side_stream" (0/1: whether d2c_step runs the head average and the rollout on a second stream).
+ * Returns D2C_EINVAL for an unknown name. */
 int d2c_set_tunable(const char* name, int32_t value);
 
 #ifdef __cplusplus
