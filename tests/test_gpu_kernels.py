@@ -55,6 +55,19 @@ def test_linear_parity(B, dtype, m, N, K):
     ctx.close()
 
 
+@pytest.mark.parametrize("waves", [4, 6, 8, 10])
+@pytest.mark.parametrize("dtype,m,N,K", [("f32", 37, 250, 132), ("bf16", 70, 1000, 520), ("bf16", 9, 176, 4096)])
+def test_linear_parity_every_workgroup_width(B, waves, dtype, m, N, K):
+    """The planner picks 6, 8 or 10 waves per workgroup by shape; here each width (and the 4-wave one) is
+    forced on shapes whose column count is no multiple of the workgroup's columns."""
+    say(f"linear waves={waves} dtype={dtype} m={m} N={N} K={K}")
+    B.d2c_set_tunable("gemm_waves", waves)
+    try:
+        test_linear_parity(B, dtype, m, N, K)
+    finally:
+        B.d2c_set_tunable("gemm_waves", 0)
+
+
 # ------------------------------------------------------------------ attention (config "C2" and edge shapes)
 ATTN_CASES = [
     # dtype, H, Hkv, dh, L, m, kernels ("few": the few-row kernels, "tiled": the LDS-tiled ones, "": fp32)
@@ -168,6 +181,19 @@ def test_refresh_layer_parity_row_major_weights(B, name):
         _refresh_layer_parity(B, *case)
     finally:
         B.d2c_set_tunable("gemm_preshuffle", 1)
+
+
+@pytest.mark.parametrize("waves", [6, 10])
+@pytest.mark.parametrize("name", ["C1-f32", "bf16-small", "tiny-f32-odd-ffn"])
+def test_refresh_layer_parity_forced_workgroup_width(B, name, waves):
+    """The gated epilogue pairs neighbouring waves: checked for the 6- and 10-wave workgroups on shapes where
+    the planner would not pick them by itself."""
+    case = [c for c in LAYER_CASES if c[0] == name][0]
+    B.d2c_set_tunable("gemm_waves", waves)
+    try:
+        _refresh_layer_parity(B, *case)
+    finally:
+        B.d2c_set_tunable("gemm_waves", 0)
 
 
 def _refresh_layer_parity(B, name, wd, L, m):
