@@ -336,10 +336,11 @@ def test_step_parallel_decoding_and_short_rollout(B):
     _teacher_forced(B, wd, mdl, su, prm, n_steps=su.gen_len)
 
 
-@pytest.mark.parametrize("workload", ["C3", "C4"])
+@pytest.mark.parametrize("workload", ["C3", "C4", "C5"])
 def test_step_full_depth_properties_and_sampled_rows(B, workload):
     """The benchmark's own configurations (LLaDA-8B and Dream-7B shapes at full depth, weights drawn on the
-    device as bench.py draws them), free-running for step 0 and three d2Cache steps.  A CPU forward at this size
+    device as bench.py draws them; the long-context batch of four sequences projected together),
+    free-running for step 0 and three d2Cache steps.  A CPU forward at this size
     takes minutes, so the check is what holds at any size plus sampled outputs the oracle computes row by
     row: the influence scores sum to L and are at least 1 outside S (Eq. 6-9 with rows of W summing to
     1), every index set is reproduced bit-exactly by the oracle's integer selection from the GPU's own
@@ -348,60 +349,62 @@ def test_step_full_depth_properties_and_sampled_rows(B, workload):
     import bench
     dims, su = W.DIMS[workload], W.SETUP[workload]
     mdl = bench.device_model(W, dims, 0, torch)
-    ctx = B.Context(dims, mdl, su.seq_len, device_weights=True)
+    ctx = B.Context(dims, mdl, su.seq_len, device_weights=True, max_batch=su.batch)
     od = oracle_dims(dims, dims.n_layers)
     prm = oracle_params(su)
     gp = _gpu_params(B, prm)
-    y0, m0 = W.initial_sequence(dims, su, 0)
+    inits = [W.initial_sequence(dims, su, b) for b in range(su.batch)]
     L, dq, dkv = su.seq_len, dims.d_q, dims.d_kv
     wk = mdl["layers"][0]["wqkv"][dq: dq + dkv].float().cpu().numpy().astype(np.float64)      # [d_kv, d]
     emb = mdl["tok_emb"]
     gain = np.ones(dims.d_model)
     finals = []
     for rep in range(2):
-        seq = B.Sequence_(ctx, y0, m0, su.prompt_len, trace=True, max_trace_rows=su.gen_len)
+        seqs = [B.Sequence_(ctx, y0, m0, su.prompt_len, trace=True, max_trace_rows=su.gen_len) for y0, m0 in inits]
         for t in range(4):
-            say(f"full-depth {workload} shape rep={rep} t={t} m={seq.n_s}")
-            masked_before = seq.is_masked.cpu().numpy().astype(bool)
-            S = seq.s_idx.cpu().numpy()[: seq.n_s].astype(np.int64)
-            tokens_in = seq.tokens.cpu().numpy()
-            ctx.d2c_step(gp, [seq])
+            say(f"full-depth {workload} shape rep={rep} t={t} m={[q.n_s for q in seqs]}")
+            before = [(q.is_masked.cpu().numpy().astype(bool), q.s_idx.cpu().numpy()[: q.n_s].astype(np.int64),
+                       q.tokens.cpu().numpy()) for q in seqs]
+            ctx.d2c_step(gp, seqs)
             torch.cuda.synchronize()
-            infl = host(seq.influence)
-            if rep == 0:
-                # Eq. 9 invariants
-                assert abs(float(infl.astype(np.float64).sum()) - L) < 1e-3 * L, f"sum of influence t={t}"
-                outside = np.setdiff1d(np.arange(L), S)
-                assert np.all(infl[outside] >= 1.0 - 1e-4) and np.all(infl >= 0.0)
-                # index sets: integer-exact on the GPU's own float arrays
-                g = _sets(B, seq)
-                score_g, conf_g = host(seq.score), host(seq.conf)
-                lo, hi = g["block"]
-                assert (lo, hi) == O.current_block(masked_before, su.prompt_len, su.block_len)
-                cand1 = np.array([i for i in range(lo, hi) if masked_before[i]], np.int64)
-                np.testing.assert_array_equal(g["mstar"], O.top_k_select(score_g, cand1, prm.k))
-                np.testing.assert_array_equal(g["decode"], O.top_k_select(score_g, cand1, prm.n_unmask))
-                cand2 = np.flatnonzero(~masked_before)
-                np.testing.assert_array_equal(g["u"], O.top_p_select(infl, cand2, prm.p))
-                np.testing.assert_array_equal(g["s_next"], np.union1d(np.union1d(g["mstar"], g["decode"]), g["u"]))
-                assert seq.n_masked == su.gen_len - su.n_unmask * (t + 1)
-                # Eq. 1 on sampled rows, from the logits this step produced
-                rows = np.array([i for i in S if masked_before[i]], np.int64)
-                if len(rows):
-                    lg = host(seq.logits_out)[: len(rows)]
-                    s_ref, x_ref = O.confidence(lg[:4])
-                    np.testing.assert_allclose(conf_g[rows[:4]], s_ref, rtol=1e-4)
-                    np.testing.assert_array_equal(seq.pred.cpu().numpy()[rows[:4]], x_ref)
-                # layer-0 key rows of sampled refreshed positions
-                kc0 = seq.k_cache[0].float().cpu().numpy()
-                for i in S[:: max(1, len(S) // 3)][:3]:
-                    x = emb[int(tokens_in[i])].float().cpu().numpy().astype(np.float64)[None, :]
-                    a = W.round_bf16(O.rmsnorm(x, gain, od.rms_eps).astype(np.float32)).astype(np.float64)
-                    k = (a @ wk.T).reshape(1, dims.n_kv_heads, dims.head_dim)
-                    k = O.rope(k, np.array([i]), od.rope_theta).reshape(-1)
-                    assert rel_l2(kc0[i], k) < TOL["bf16"], f"layer-0 key row {i} t={t}"
-        finals.append({n: getattr(seq, n).clone() for n in ("tokens", "is_masked", "k_cache", "v_cache", "conf", "pred",
-                                                               "influence", "s_idx")})
-    for n in finals[0]:
-        assert torch.equal(finals[0][n], finals[1][n]), f"run-to-run difference in {n}"
+            for seq, (masked_before, S, tokens_in) in zip(seqs, before):
+                infl = host(seq.influence)
+                if rep == 0:
+                    # Eq. 9 invariants
+                    assert abs(float(infl.astype(np.float64).sum()) - L) < 1e-3 * L, f"sum of influence t={t}"
+                    outside = np.setdiff1d(np.arange(L), S)
+                    assert np.all(infl[outside] >= 1.0 - 1e-4) and np.all(infl >= 0.0)
+                    # index sets: integer-exact on the GPU's own float arrays
+                    g = _sets(B, seq)
+                    score_g, conf_g = host(seq.score), host(seq.conf)
+                    lo, hi = g["block"]
+                    assert (lo, hi) == O.current_block(masked_before, su.prompt_len, su.block_len)
+                    cand1 = np.array([i for i in range(lo, hi) if masked_before[i]], np.int64)
+                    np.testing.assert_array_equal(g["mstar"], O.top_k_select(score_g, cand1, prm.k))
+                    np.testing.assert_array_equal(g["decode"], O.top_k_select(score_g, cand1, prm.n_unmask))
+                    cand2 = np.flatnonzero(~masked_before)
+                    np.testing.assert_array_equal(g["u"], O.top_p_select(infl, cand2, prm.p))
+                    np.testing.assert_array_equal(g["s_next"], np.union1d(np.union1d(g["mstar"], g["decode"]), g["u"]))
+                    assert seq.n_masked == su.gen_len - su.n_unmask * (t + 1)
+                    # Eq. 1 on sampled rows, from the logits this step produced
+                    rows = np.array([i for i in S if masked_before[i]], np.int64)
+                    if len(rows):
+                        lg = host(seq.logits_out)[: len(rows)]
+                        s_ref, x_ref = O.confidence(lg[:4])
+                        np.testing.assert_allclose(conf_g[rows[:4]], s_ref, rtol=1e-4)
+                        np.testing.assert_array_equal(seq.pred.cpu().numpy()[rows[:4]], x_ref)
+                    # layer-0 key rows of sampled refreshed positions
+                    kc0 = seq.k_cache[0].float().cpu().numpy()
+                    for i in S[:: max(1, len(S) // 3)][:3]:
+                        x = emb[int(tokens_in[i])].float().cpu().numpy().astype(np.float64)[None, :]
+                        a = W.round_bf16(O.rmsnorm(x, gain, od.rms_eps).astype(np.float32)).astype(np.float64)
+                        k = (a @ wk.T).reshape(1, dims.n_kv_heads, dims.head_dim)
+                        k = O.rope(k, np.array([i]), od.rope_theta).reshape(-1)
+                        assert rel_l2(kc0[i], k) < TOL["bf16"], f"layer-0 key row {i} t={t}"
+        finals.append([{n: getattr(q, n).clone() for n in ("tokens", "is_masked", "k_cache", "v_cache", "conf", "pred",
+                                                            "influence", "s_idx")} for q in seqs])
+        del seqs
+    for fa, fb in zip(finals[0], finals[1]):
+        for n in fa:
+            assert torch.equal(fa[n], fb[n]), f"run-to-run difference in {n}"
     ctx.close()
