@@ -85,6 +85,8 @@ ATTN_CASES = [
     ("bf16", 3, 1, 64, 1000, 129, "tiled"),       # odd head count (A-bar loop tail), head_dim 64, 3 query blocks
     ("bf16", 6, 3, 64, 100, 20, "few"),           # 3 kv heads: neither divides nor is divided by the 8 XCDs
     ("bf16", 16, 2, 128, 600, 50, "few"),         # 4 XCDs per kv head, 8 query heads each; L above 512
+    ("bf16", 32, 32, 128, 512, 46, "few"),        # the LLaDA-8B decode step: 96 (tile, head) pairs
+    ("bf16", 5, 5, 128, 300, 16, "few"),          # 5 kv heads: plain placement
     ("f32", 4, 4, 64, 128, 73, ""),               # the small fp32 model's geometry
     ("f32", 4, 2, 8, 19, 5, ""),
 ]
