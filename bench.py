@@ -10,7 +10,8 @@ unmasking.  Step 0 (all 512 rows) fills the caches before the clock starts.
 Prints one JSON line.  value = timed steps / wall time between two device synchronisations;
 roofline = algorithmic weight bytes of the projection launches / their HIP-event durations
 (a second pass over the same steps with an event pair around every launch), against 8 TB/s;
-full_recompute = the same engine with every row selected; cpu_baseline = the CPU oracle on a
+full_recompute = the same engine with every row selected; generation = one whole generation timed
+from before step 0 to the last token (generated tokens per second); cpu_baseline = the CPU oracle on a
 bounded sample of the same workload.  --workload C4 / C5 / C6 / C2 / select run the other configurations.
 """
 import argparse
@@ -248,6 +249,7 @@ def main():
                          "R = 5 there); 0 = all layers, the metric's setting")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-vanilla", action="store_true")
+    ap.add_argument("--no-generation", action="store_true", help="skip the whole-generation leg (tokens/s incl. step 0)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported (sequences are independent, so "
@@ -359,6 +361,22 @@ def main():
         vanilla = {"ms_per_step": round(1e3 * (time.perf_counter() - t0) / nv, 3), "rows_per_step": su.seq_len * su.batch}
         vanilla["steps_per_sec"] = round(1e3 / vanilla["ms_per_step"], 2)
 
+    # ---- one whole generation, step 0 (every row, fills the caches) included: generated tokens per second
+    generation = None
+    if not args.no_generation:
+        seqg = fresh_sequences(B, W, ctx, dims, su, 1000)
+        n_gen_steps = su.gen_len // su.n_unmask
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_gen_steps):
+            ctx.d2c_step(prm, seqg)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        left = sum(q.n_masked for q in seqg)
+        generation = {"tokens_per_sec": round((su.batch * su.gen_len - left) / dt, 2), "seconds": round(dt, 4),
+                      "steps": n_gen_steps, "tokens": su.batch * su.gen_len - left, "masked_left": left,
+                      "includes": "step 0 over all %d rows per sequence" % su.seq_len}
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(W, dims, su, int(round(mean_m)), max(1, int(round(mean_rows))))
@@ -378,6 +396,7 @@ def main():
         "tokens_per_sec": round(su.batch * su.n_unmask * K / elapsed, 3),
         "algorithmic_gb_per_step": round(step_bytes / 1e9, 3),
         "step_hbm_frac": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "generation": generation,
         "roofline": roofline, "kernel_classes": by_class, "full_recompute": vanilla, "cpu_baseline": cpu,
     }
     print(json.dumps(out))

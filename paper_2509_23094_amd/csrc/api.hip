@@ -418,6 +418,8 @@ int d2c_set_tunable(const char* name, int32_t value) {
   else if (!strcmp(name, "gemm_max_splits")) t.gemm_max_splits = std::max(1, std::min(8, (int)value));
   else if (!strcmp(name, "gemm_nt_big_n")) t.gemm_nt_big_n = value;
   else if (!strcmp(name, "gemm_wide_tiles")) t.gemm_wide_tiles = value;
+  else if (!strcmp(name, "gemm_wide_min_rows")) t.gemm_wide_min_rows = value;
+  else if (!strcmp(name, "gemm_tall_chunk")) t.gemm_tall_chunk = value;
   else if (!strcmp(name, "attn_side_groups")) t.attn_side_groups = value;
   else if (!strcmp(name, "gemm_waves")) t.gemm_waves = (value == 8 || value == 4 || value == 6 || value == 10) ? value : 0;
   else if (!strcmp(name, "gemm_preshuffle")) t.gemm_preshuffle = value != 0;

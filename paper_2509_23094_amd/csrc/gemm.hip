@@ -355,6 +355,14 @@ hipError_t launch_mt(const GemmPlan& pl, const void* A, int lda, const void* W, 
     case 8: return launch_t<T, 8, NT, WAVES, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
     default: break;
   }
+  // 129-192 rows in one row chunk (bf16, one column tile per wave, 8 waves): even tile counts only
+  if constexpr (sizeof(T) == 2 && NT == 1 && WAVES == 8) {
+    switch (pl.mt) {
+      case 10: return launch_t<T, 10, NT, WAVES, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+      case 12: return launch_t<T, 12, NT, WAVES, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+      default: break;
+    }
+  }
   return hipErrorInvalidValue;
 }
 
@@ -409,12 +417,21 @@ GemmPlan plan_gemm(int dtype, int m, int N, int K, bool single_split) {
   const int tiles = (m + 15) / 16;
   pl.mt = tiles <= 8 ? (tiles < 1 ? 1 : tiles) : 8;
   pl.row_chunks = tiles <= 8 ? 1 : (tiles + 7) / 8;
+  // 129-192 rows in bf16: still one row chunk (10 or 12 row tiles).  Two row chunks pull every weight tile
+  // through the L1 of two compute units, and that pull rate, not HBM, is what bounds the kernel; beyond 12
+  // row tiles the LDS reads of one column tile per wave cost more than the second pull (measured per layer
+  // at the LLaDA shape: 140 rows 170 vs 196 us, 166 rows 192 vs 200 us, 200 rows 214 vs 200 us).
+  if (tiles > 8 && tiles <= 12 && dtype == kBF16 && t.gemm_tall_chunk && (t.gemm_waves == 0 || t.gemm_waves == 8)) {
+    pl.mt = tiles + (tiles & 1);
+    pl.row_chunks = 1;
+  }
   // two column tiles per wave halve the LDS reads per matrix-core step: a gain once there are several
   // row chunks (the kernel is LDS- and L2-bound there), a loss for a handful of rows (fewer waves in flight)
-  pl.nt = (N > t.gemm_nt_big_n || tiles > 8) ? 2 : 1;
+  pl.nt = (N > t.gemm_nt_big_n || pl.row_chunks > 1) ? 2 : 1;
   // several row chunks in bf16: four column tiles per wave and one wave per SIMD (128 x 64 outputs per wave)
   // halve the LDS reads per matrix-core step once more
-  const bool wide = tiles > 8 && dtype == kBF16 && t.gemm_wide_tiles && K % 256 == 0;   // needs an even number of whole chunks
+  const bool wide = pl.row_chunks > 1 && m >= t.gemm_wide_min_rows && dtype == kBF16 && t.gemm_wide_tiles &&
+                    K % 256 == 0;                       // needs an even number of whole chunks
   if (wide) pl.nt = 4;
   pl.rot = t.gemm_rot;
   // 8 waves share one activation chunk in LDS: fewer, fatter workgroups (about 1.5 per compute unit) with
@@ -443,6 +460,7 @@ GemmPlan plan_gemm(int dtype, int m, int N, int K, bool single_split) {
     double best = 1e30;
     for (int w : {8, 6, 10}) {                                    // 8 first: ties keep the 8-wave shape
       if (t.gemm_waves != 0 && w != pl.waves) continue;
+      if (pl.mt > 8 && w != 8) continue;                          // the tall chunk fits the registers of 8 waves only
       for (int s = 1; s <= max_splits; s *= 2) {
         const int cps = (chunks + s - 1) / s;
         if (s > 1 && cps < 2) break;

@@ -15,6 +15,8 @@ struct Tunables {
   int gemm_target_wgs = 384;   // aim for at least this many groups of 4 waves per GEMM
   int gemm_max_splits = 8;
   int attn_side_groups = 4;    // most head groups of the head average when it runs beside other work (d2c_step)
+  int gemm_wide_min_rows = 257; // the wide instantiation from this many rows on (3 row chunks)
+  int gemm_tall_chunk = 1;      // 129-192 bf16 rows as ONE row chunk of 10 or 12 row tiles
   int gemm_wide_tiles = 1;     // more than 128 rows in bf16: 128 x 64 outputs per wave, 4 waves per workgroup
   int gemm_nt_big_n = 1 << 30; // N above this uses two column tiles per wave even for few rows (measured slower);
                                // more than 128 rows always do
