@@ -35,6 +35,7 @@ LINEAR_CASES = [
     ("f32", 200, 100, 132),
     ("bf16", 1, 64, 128), ("bf16", 83, 1024, 512), ("bf16", 17, 40, 72), ("bf16", 96, 4096, 1408),
     ("bf16", 130, 200, 264), ("bf16", 300, 3000, 520), ("bf16", 64, 33000, 256),
+    ("bf16", 185, 1000, 392), ("bf16", 192, 4096, 512), ("bf16", 200, 520, 256),   # 12 row tiles in one chunk; two chunks
 ]
 
 
@@ -160,6 +161,7 @@ LAYER_CASES = [
     ("tiny-f32-gqa", W.ModelDims(1, 64, 4, 2, 16, 80, 64, dtype="f32"), 33, 7),
     ("bf16-small", W.ModelDims(1, 512, 4, 4, 128, 1408, 64, dtype="bf16"), 200, 45),
     ("bf16-gqa", W.ModelDims(1, 512, 8, 2, 64, 1024, 64, dtype="bf16"), 300, 150),
+    ("bf16-185-rows", W.ModelDims(1, 512, 4, 4, 128, 1408, 64, dtype="bf16"), 260, 185),   # 12 row tiles in one chunk
     ("C3-width", W.DIMS["C3"], 512, 83),     # one LLaDA-8B-shaped layer at full width
     ("C4-width", W.DIMS["C4"], 768, 100),    # one Dream-7B-shaped layer at full width
 
