@@ -235,7 +235,8 @@ int d2c_profile_end(d2c_ctx* ctx, double* ms, int64_t* launches, double* bytes);
 /* Launch-shape tunables, process-wide; set them before d2c_init.  Names:
  * projection kernel: "gemm_waves" (waves per workgroup: 4, 6, 8, 10; 0 = chosen by shape together with the
  * split count), "gemm_max_splits" (1..8), "gemm_target_wgs" (workgroups aimed at where the shape search does
- * not apply), "gemm_nt_big_n", "gemm_wide_tiles" (0/1: 128 x 64 outputs per wave for more than 128 bf16 rows),
+ * not apply), "gemm_nt_big_n", "gemm_wide_tiles" (0/1: 128 x 64 outputs per wave for many bf16 rows), "gemm_wide_min_rows"
+ * (that instantiation from this many rows on), "gemm_tall_chunk" (0/1: 129-192 bf16 rows as one row chunk),
  * "gemm_preshuffle" (0/1: pre-tiled weight copies), "gemm_rot";
  * attention: "attn_tiled_min_m" (bf16 attention switches to the LDS-tiled kernels from this many query rows
  * on), "attn_max_splits" (1..8, key-range splits of one attention launch), "attn_qt", "attn_target_wgs",
@@ -243,6 +244,14 @@ int d2c_profile_end(d2c_ctx* ctx, double* ms, int64_t* launches, double* bytes);
  * "side_stream" (0/1: whether d2c_step runs the head average and the rollout on a second stream).
  * Returns D2C_EINVAL for an unknown name. */
 int d2c_set_tunable(const char* name, int32_t value);
+
+/* The launch shape the projection kernel would take for P = A[m, K] W[N, K]^T under the current tunables
+ * (host-side arithmetic only: no context, no GPU).  single_split != 0: the projection must not split the
+ * contraction (the gate/up projection with the gated epilogue).  Writes
+ * shape[0..6] = row tiles per workgroup (16 rows each), column tiles per wave, waves per workgroup, splits of
+ * the contraction, contraction elements per split, row chunks, workgroups of the launch.
+ * Returns D2C_EINVAL for a null pointer, a dtype other than D2C_F32 / D2C_BF16 or non-positive sizes. */
+int d2c_plan_projection(int32_t dtype, int32_t m, int32_t N, int32_t K, int32_t single_split, int32_t shape[7]);
 
 #ifdef __cplusplus
 }

@@ -56,7 +56,7 @@ class d2c_seq_state(C.Structure):
 
 
 EXPORTS = ["d2c_init", "d2c_destroy", "d2c_last_error", "d2c_seq_reset", "d2c_select", "d2c_refresh_layer",
-           "d2c_attention", "d2c_influence", "d2c_linear", "d2c_step", "d2c_profile_begin", "d2c_profile_end", "d2c_workspace_bytes", "d2c_set_tunable"]
+           "d2c_attention", "d2c_influence", "d2c_linear", "d2c_step", "d2c_profile_begin", "d2c_profile_end", "d2c_workspace_bytes", "d2c_set_tunable", "d2c_plan_projection"]
 
 
 def load_library() -> C.CDLL:
@@ -82,6 +82,7 @@ def load_library() -> C.CDLL:
     lib.d2c_workspace_bytes.argtypes = [vp]
     lib.d2c_workspace_bytes.restype = C.c_int64
     lib.d2c_set_tunable.argtypes = [C.c_char_p, i32]
+    lib.d2c_plan_projection.argtypes = [i32, i32, i32, i32, i32, C.POINTER(i32)]
     for name in EXPORTS:
         if name not in ("d2c_last_error", "d2c_workspace_bytes"):
             getattr(lib, name).restype = C.c_int
@@ -109,6 +110,16 @@ def torch_dtype(dtype: str) -> torch.dtype:
 def to_device(a: np.ndarray, dtype: str) -> torch.Tensor:
     """numpy float32 -> device tensor of the storage type (exact for bf16-representable values)."""
     return torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(torch_dtype(dtype)).cuda().contiguous()
+
+
+def d2c_plan_projection(dtype: str, m: int, N: int, K: int, single_split: bool = False) -> Dict[str, int]:
+    """Launch shape of the projection kernel for m rows of a [N, K] matrix (host arithmetic, no GPU)."""
+    shape = (C.c_int32 * 7)()
+    rc = _lib.d2c_plan_projection(D2C_BF16 if dtype == "bf16" else D2C_F32, int(m), int(N), int(K), int(single_split), shape)
+    if rc != 0:
+        raise D2CError(rc, "d2c_plan_projection: bad arguments")
+    return dict(zip(("row_tiles", "col_tiles_per_wave", "waves", "splits", "k_per_split", "row_chunks", "workgroups"),
+                    [int(x) for x in shape]))
 
 
 def d2c_set_tunable(name: str, value: int) -> None:

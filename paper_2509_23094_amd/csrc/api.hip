@@ -411,6 +411,20 @@ const char* d2c_last_error(const d2c_ctx* c) { return c ? c->err.c_str() : g_ini
 
 int64_t d2c_workspace_bytes(const d2c_ctx* c) { return c ? c->ws_bytes : 0; }
 
+int d2c_plan_projection(int32_t dtype, int32_t m, int32_t N, int32_t K, int32_t single_split, int32_t shape[7]) {
+  if (!shape || (dtype != D2C_F32 && dtype != D2C_BF16) || m <= 0 || N <= 0 || K <= 0) return D2C_EINVAL;
+  const GemmPlan pl = plan_gemm(dtype, m, N, K, single_split != 0);
+  const int cols = 16 * pl.nt * pl.waves;
+  shape[0] = pl.mt;
+  shape[1] = pl.nt;
+  shape[2] = pl.waves;
+  shape[3] = pl.splits;
+  shape[4] = pl.k_per_split;
+  shape[5] = pl.row_chunks;
+  shape[6] = ((N + cols - 1) / cols) * pl.splits * pl.row_chunks;
+  return D2C_OK;
+}
+
 int d2c_set_tunable(const char* name, int32_t value) {
   if (!name) return D2C_EINVAL;
   Tunables& t = tunables();
