@@ -224,9 +224,9 @@ def current_block(is_masked: np.ndarray, prompt_len: int, block_len: int) -> Tup
     masked = np.flatnonzero(np.asarray(is_masked, bool))
     if len(masked) == 0:
         return L, L
-    b = (int(masked[0]) - prompt_len) // block_len
+    b = (int(masked[0]) - prompt_len) // block_len          # floor: blocks count from the prompt's end both ways
     lo = prompt_len + b * block_len
-    return lo, min(L, lo + block_len)
+    return max(0, lo), min(L, lo + block_len)
 
 
 # ----------------------------------------------------------------------------

@@ -7,7 +7,7 @@
 // top-k ranks 64-bit keys (float bits of the non-negative score, then lower
 // index first); top-p sorts such keys with a bitonic network in LDS and scans
 // fixed-point masses floor(c * 2^32) in uint64.  Ties always go to the lowest index.
-#include "common.cuh"
+#include "common.h"
 #include "internal.h"
 
 namespace d2c {
@@ -350,9 +350,14 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a, int N
   const int n_masked = sh->scalar[1];
   int lo = L, hi = L;
   if (n_masked > 0) {
-    const int b = (first_masked - a.prompt_len) / a.block_len;
-    lo = a.prompt_len + b * a.block_len;
-    hi = min(L, lo + a.block_len);
+    // blocks are counted from the end of the prompt in both directions (floor division): a masked
+    // position inside the prompt -- nothing the decoding loop produces, but a legal input -- lies in a
+    // block with a negative number, cut at position 0
+    const int diff = first_masked - a.prompt_len;
+    const int b = diff >= 0 ? diff / a.block_len : -((-diff + a.block_len - 1) / a.block_len);
+    const int lo_raw = a.prompt_len + b * a.block_len;
+    lo = max(0, lo_raw);
+    hi = min(L, lo_raw + a.block_len);
   }
 
   // ---- phase 1: Eq. 3 on the masked tokens of the current block, score = D(i) * s^i

@@ -204,6 +204,19 @@ def test_current_block():
     assert O.current_block(m, 20, 32) == (100, 100)
     m[60] = True
     assert O.current_block(m, 20, 80) == (20, 100)            # NAR: one block
+    # a masked position inside the prompt (not produced by the decoding loop, but a legal input): blocks
+    # are counted from the prompt's end in both directions and cut at position 0
+    m[:] = False
+    m[[17, 60]] = True
+    assert O.current_block(m, 20, 8) == (12, 20)
+    m[3] = True
+    assert O.current_block(m, 20, 8) == (0, 4)
+    assert O.current_block(m, 5, 8) == (0, 5)
+    for P, bl in ((20, 8), (5, 8), (7, 3), (64, 32)):           # the block always holds the first masked position
+        for first in range(0, 40):
+            mm = np.zeros(100, bool); mm[[first, 99]] = True
+            lo, hi = O.current_block(mm, P, bl)
+            assert 0 <= lo <= first < hi <= 100 and hi - lo <= bl and (hi - P) % bl == 0 or hi == 100
 
 
 def test_select_contract():
