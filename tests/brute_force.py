@@ -130,3 +130,26 @@ def brute_step(wd, mdl, prm, prompt_len, before):
 def _f32(x):
     import struct
     return struct.unpack("f", struct.pack("f", x))[0]
+
+
+def brute_influence(abars, S, L):
+    """Eq. 6-9 over any number of layers as scalar nested loops: E^(l) (rows in S carry the head-averaged
+    attention row, every other row is one-hot), W^(l) = row-normalised E^(l) + I, C^(l) = W^(l) C^(l-1)
+    from C^(0) = I, and c_j = sum_i C_ij.  abars: one [|S|][L] array per layer, in layer order."""
+    S = [int(i) for i in S]
+    C = [[1.0 if i == j else 0.0 for j in range(L)] for i in range(L)]
+    for a in abars:
+        Wm = []
+        for i in range(L):
+            row = [0.0] * L
+            if i in S:
+                r = S.index(i)
+                for j in range(L):
+                    row[j] = float(a[r][j])
+            else:
+                row[i] = 1.0
+            row[i] += 1.0
+            tot = sum(row)
+            Wm.append([v / tot for v in row])
+        C = [[sum(Wm[i][t] * C[t][j] for t in range(L)) for j in range(L)] for i in range(L)]
+    return [sum(C[i][j] for i in range(L)) for j in range(L)]

@@ -13,7 +13,7 @@ import torch.nn.functional as F
 from oracle import d2cache_oracle as O
 from paper_2509_23094_amd import workloads as W
 
-from brute_force import brute_step
+from brute_force import brute_influence, brute_step
 
 
 def _dims(wd: W.ModelDims) -> O.Dims:
@@ -222,6 +222,58 @@ def test_step_brute_force_tiny(seed):
         np.testing.assert_array_equal(st.y, ref["y"])
         np.testing.assert_array_equal(st.is_masked, ref["is_masked"])
     assert not st.is_masked.any()
+
+
+@pytest.mark.parametrize("seed", range(2))
+def test_step_rollout_over_first_layers(seed):
+    """The lightweight rollout of the appendix (rollout over the first r layers only): on a 4-layer model
+    the influence scores of d2cache_step(rollout_layers = r) must equal Eq. 6-9 written as nested loops over
+    the step's own head-averaged attention of layers 0 .. r-1 (not the last r, not r +- 1), r = N must equal
+    r = 0 (all layers), and r = 1 must equal the single-layer closed form
+    c_j = [j not in S] + sum_{i in S} (A_ij + [i = j]) / 2.  The forward pass itself does not depend on r."""
+    wd = W.ModelDims(4, 16, 2, 1, 8, 24, 32, dtype="f32")
+    su = W.DecodeSetup(5, 7, 4, 1, k=2, p=0.4, sigma=1.5)
+    dims, mdl = _dims(wd), _tiny_model(seed + 5, wd, std_scale=12.0)
+    y0, m0 = W.initial_sequence(wd, su, seed)
+    L, N = su.seq_len, wd.n_layers
+    traces = {}
+    for r in (0, 1, 2, 3, N, N + 3):
+        prm = O.Params(sigma=su.sigma, k=su.k, p=su.p, block_len=su.block_len, n_unmask=1, rollout_layers=r)
+        st = O.new_state(dims, y0, m0, su.prompt_len)
+        O.d2cache_step(dims, mdl, prm, st)                       # step 0: every row
+        first = dict(st.trace)
+        # the second step from a FIXED partial row set, so that every r sees the same S
+        st.S = np.array([1, 4, 6, 7, 10], np.int32)
+        O.d2cache_step(dims, mdl, prm, st)
+        traces[r] = (first, dict(st.trace))
+    for r, steps in traces.items():
+        for tr in steps:
+            S, abars = tr["S"], tr["abars"]
+            assert len(abars) == N
+            used = abars if r == 0 else abars[:min(r, N)]
+            np.testing.assert_allclose(tr["c"], brute_influence(used, S, L), rtol=1e-12, atol=1e-13)
+            np.testing.assert_allclose(tr["c"], O.influence(O.rollout(used, S, L)), rtol=0, atol=0)
+            assert abs(tr["c"].sum() - L) < 1e-11
+    for step in (0, 1):
+        base = traces[0][step]
+        for r in traces:
+            for l in range(N):                                   # the forward does not depend on r
+                np.testing.assert_array_equal(traces[r][step]["abars"][l], base["abars"][l])
+        np.testing.assert_array_equal(traces[N][step]["c"], base["c"])
+        np.testing.assert_array_equal(traces[N + 3][step]["c"], base["c"])
+        # r = 1: the closed form of one layer, from layer 0's attention (and not from the last layer's)
+        tr = traces[1][step]
+        S, a0, a_last = [int(i) for i in tr["S"]], tr["abars"][0], tr["abars"][-1]
+        for j in range(L):
+            ref = (0.0 if j in S else 1.0) + sum(0.5 * (a0[q, j] + (1.0 if S[q] == j else 0.0)) for q in range(len(S)))
+            assert abs(tr["c"][j] - ref) < 1e-13
+        wrong = np.array([(0.0 if j in S else 1.0) + sum(0.5 * (a_last[q, j] + (1.0 if S[q] == j else 0.0))
+                                                         for q in range(len(S))) for j in range(L)])
+        assert np.max(np.abs(wrong - tr["c"])) > 1e-3            # the pin can tell the first layer from the last
+        # and the depths differ from one another, so an off-by-one would show
+        cs = [traces[r][step]["c"] for r in (1, 2, 3, N)]
+        for a, b in zip(cs, cs[1:]):
+            assert np.max(np.abs(a - b)) > 1e-4
 
 
 def test_generation_loop_contract():
