@@ -180,12 +180,12 @@ def bench_select_op(args, B, W, torch, np):
     }
 
 
-def bench_attention_op(args, B, W, torch, np):
+def bench_attention_op(args, B, W, torch, np, tune=None):
     """The isolated selective-refresh attention op: scatter of m new K/V rows, then m queries against all
     L cached keys, no mask, with and without the head-averaged probabilities.  One "step" = one call."""
     H, Hkv, dh, L, m = 32, 32, 128, 2048, 256
     wd = W.with_layers(W.ModelDims(1, H * dh, H, Hkv, dh, 64, 64, dtype="bf16"), 1)
-    ctx = B.Context(wd, W.model_weights(wd, 0), L)
+    ctx = B.Context(wd, W.model_weights(wd, 0), L, tunables=tune)
     case = W.attention_case(1, H, Hkv, dh, L, m, dtype="bf16")
     q = B.to_device(case["q"], "bf16")
     kc, vc = B.to_device(case["k_cache"], "bf16"), B.to_device(case["v_cache"], "bf16")
@@ -240,7 +240,7 @@ def main():
                     help="C3 (default, the metric's workload), C4, or C2 = the isolated selective-refresh attention op")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (the result is then not the metric)")
     ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
-                    help="library tunable (see d2c_set_tunable), e.g. --tune gemm_target_wgs=768")
+                    help="library tunable of the context (include/d2c_tools.h), e.g. --tune gemm_target_wgs=768")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run five plain 256 MiB device copies (known size, for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE) and exit")
@@ -264,9 +264,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    for kv in args.tune:
-        name, value = kv.split("=")
-        B.d2c_set_tunable(name, int(value))
+    tune = {kv.split("=")[0]: int(kv.split("=")[1]) for kv in args.tune}
     if args.copy_calibration:
         src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
         dst = torch.zeros_like(src)
@@ -276,7 +274,7 @@ def main():
         print(json.dumps({"copy_calibration_bytes": 256 << 20, "copies": 5}))
         return
     if args.workload == "C2":
-        print(json.dumps(bench_attention_op(args, B, W, torch, np)))
+        print(json.dumps(bench_attention_op(args, B, W, torch, np, tune)))
         return
     if args.workload == "select":
         print(json.dumps(bench_select_op(args, B, W, torch, np)))
@@ -289,7 +287,7 @@ def main():
     assert Wm < per_gen, "warmup must be shorter than one generation"
 
     mdl = device_model(W, dims, 0, torch)
-    ctx = B.Context(dims, mdl, su.seq_len, device_weights=True, max_batch=su.batch)
+    ctx = B.Context(dims, mdl, su.seq_len, device_weights=True, max_batch=su.batch, tunables=tune)
     prm = B.make_params(su.sigma, su.k, su.p, su.block_len, su.n_unmask, 0, rollout_layers=args.rollout_layers)
 
     def run_steps(seqs, n, collect=None):
@@ -327,11 +325,15 @@ def main():
     gm = prof["gemm"]
     gemm_ms = gm["ms"] / max(1, gm["launches"])
     gemm_gbs = gm["bytes"] / max(1e-12, gm["ms"] * 1e-3) / 1e9
+    # measured HBM bytes per projection launch (rocprofv3 counters, profiles/gemm_rows_traffic.*): the stored
+    # figure describes the default workload's decode steps only, so it is reported for that workload only
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "gemm_rows_traffic.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and not args.layers and not tune and args.rollout_layers == 0:
         try:
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+            tj = json.load(open(tpath))
+            if str(tj.get("workload", "")).split()[0] == args.workload:
+                traffic = tj.get("hbm_bytes_per_launch")
         except Exception:
             traffic = None
     roofline = {"bound": "hbm", "kernel": "gemm_rows_kernel", "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS,
@@ -397,6 +399,9 @@ def main():
         "algorithmic_gb_per_step": round(step_bytes / 1e9, 3),
         "step_hbm_frac": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "generation": generation,
+        "memory": dict(ctx.memory_info(), note="device bytes the library holds beside the caller's weights and "
+                       "K/V caches: pre-tiled copies of the projection matrices, every layer's head-averaged "
+                       "attention for the rollout chain (max_batch x layers x max_seq^2 floats), attention partials"),
         "roofline": roofline, "kernel_classes": by_class, "full_recompute": vanilla, "cpu_baseline": cpu,
     }
     print(json.dumps(out))

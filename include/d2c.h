@@ -22,6 +22,7 @@
  *   - storage type T is float (D2C_F32) or bfloat16 (D2C_BF16): weights,
  *     embeddings and the K/V cache are T; the residual stream, logits,
  *     attention averages, rollout, confidences and norm gains are float;
+ *   - timing, launch-shape tunables and the launch planner are tooling and live in d2c_tools.h;
  *   - a context is not thread-safe: calls that share a d2c_ctx must be issued
  *     from one thread at a time and on one stream at a time (they share the
  *     context's workspace).
@@ -215,43 +216,6 @@ int d2c_step(d2c_ctx* ctx, const d2c_params* params, d2c_seq_state* seqs, int32_
 
 /* Bytes of device workspace the context holds. */
 int64_t d2c_workspace_bytes(const d2c_ctx* ctx);
-
-/* Per-launch timing with HIP events on the stream the kernels run on, by kernel class.
- * Between d2c_profile_begin and d2c_profile_end every launch of the calls above is
- * bracketed by an event pair (this perturbs the stream: do not time end-to-end while
- * it is on).  d2c_profile_end waits for the events and returns, per class, the summed
- * kernel time in milliseconds, the number of launches and the summed algorithmic
- * bytes (projection: the weight matrix once; attention: the K and V cache once). */
-#define D2C_PROF_GEMM      0
-#define D2C_PROF_ATTENTION 1
-#define D2C_PROF_ROLLOUT   2
-#define D2C_PROF_ROWWISE   3
-#define D2C_PROF_SELECT    4
-#define D2C_PROF_ATTN_AVG  5
-#define D2C_PROF_CLASSES   6
-int d2c_profile_begin(d2c_ctx* ctx);
-int d2c_profile_end(d2c_ctx* ctx, double* ms, int64_t* launches, double* bytes);
-
-/* Launch-shape tunables, process-wide; set them before d2c_init.  Names:
- * projection kernel: "gemm_waves" (waves per workgroup: 4, 6, 8, 10; 0 = chosen by shape together with the
- * split count), "gemm_max_splits" (1..8), "gemm_target_wgs" (workgroups aimed at where the shape search does
- * not apply), "gemm_nt_big_n", "gemm_wide_tiles" (0/1: 128 x 64 outputs per wave for many bf16 rows), "gemm_wide_min_rows"
- * (that instantiation from this many rows on), "gemm_tall_chunk" (0/1: 129-192 bf16 rows as one row chunk),
- * "gemm_preshuffle" (0/1: pre-tiled weight copies), "gemm_rot";
- * attention: "attn_tiled_min_m" (bf16 attention switches to the LDS-tiled kernels from this many query rows
- * on), "attn_max_splits" (1..8, key-range splits of one attention launch), "attn_qt", "attn_target_wgs",
- * "attn_side_groups" (1..8: most head groups of the head average when d2c_step runs it beside the projections);
- * "side_stream" (0/1: whether d2c_step runs the head average and the rollout on a second stream).
- * Returns D2C_EINVAL for an unknown name. */
-int d2c_set_tunable(const char* name, int32_t value);
-
-/* The launch shape the projection kernel would take for P = A[m, K] W[N, K]^T under the current tunables
- * (host-side arithmetic only: no context, no GPU).  single_split != 0: the projection must not split the
- * contraction (the gate/up projection with the gated epilogue).  Writes
- * shape[0..6] = row tiles per workgroup (16 rows each), column tiles per wave, waves per workgroup, splits of
- * the contraction, contraction elements per split, row chunks, workgroups of the launch.
- * Returns D2C_EINVAL for a null pointer, a dtype other than D2C_F32 / D2C_BF16 or non-positive sizes. */
-int d2c_plan_projection(int32_t dtype, int32_t m, int32_t N, int32_t K, int32_t single_split, int32_t shape[7]);
 
 #ifdef __cplusplus
 }

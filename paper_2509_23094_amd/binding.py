@@ -55,8 +55,15 @@ class d2c_seq_state(C.Structure):
                [(n, C.c_int32) for n in ("L", "prompt_len", "n_s", "n_rows", "n_masked", "step")]
 
 
+class d2c_tunable(C.Structure):
+    _fields_ = [("name", C.c_char_p), ("value", C.c_int32)]
+
+
+# include/d2c.h (the method's calls) and include/d2c_tools.h (timing, tunables, planner)
 EXPORTS = ["d2c_init", "d2c_destroy", "d2c_last_error", "d2c_seq_reset", "d2c_select", "d2c_refresh_layer",
-           "d2c_attention", "d2c_influence", "d2c_linear", "d2c_step", "d2c_profile_begin", "d2c_profile_end", "d2c_workspace_bytes", "d2c_set_tunable", "d2c_plan_projection"]
+           "d2c_attention", "d2c_influence", "d2c_linear", "d2c_step", "d2c_workspace_bytes"]
+TOOL_EXPORTS = ["d2c_profile_begin", "d2c_profile_end", "d2c_init_tuned", "d2c_ctx_set_tunable",
+                "d2c_plan_projection", "d2c_memory_info"]
 
 
 def load_library() -> C.CDLL:
@@ -81,9 +88,12 @@ def load_library() -> C.CDLL:
     lib.d2c_profile_end.argtypes = [vp, vp, vp, vp]
     lib.d2c_workspace_bytes.argtypes = [vp]
     lib.d2c_workspace_bytes.restype = C.c_int64
-    lib.d2c_set_tunable.argtypes = [C.c_char_p, i32]
+    lib.d2c_init_tuned.argtypes = [C.POINTER(d2c_dims), C.POINTER(d2c_weights), C.POINTER(d2c_tunable), i32,
+                                   C.POINTER(vp)]
+    lib.d2c_ctx_set_tunable.argtypes = [vp, C.c_char_p, i32]
+    lib.d2c_memory_info.argtypes = [vp, C.POINTER(C.c_int64)]
     lib.d2c_plan_projection.argtypes = [i32, i32, i32, i32, i32, C.POINTER(i32)]
-    for name in EXPORTS:
+    for name in EXPORTS + TOOL_EXPORTS:
         if name not in ("d2c_last_error", "d2c_workspace_bytes"):
             getattr(lib, name).restype = C.c_int
     return lib
@@ -122,12 +132,6 @@ def d2c_plan_projection(dtype: str, m: int, N: int, K: int, single_split: bool =
                     [int(x) for x in shape]))
 
 
-def d2c_set_tunable(name: str, value: int) -> None:
-    rc = _lib.d2c_set_tunable(name.encode(), int(value))
-    if rc != D2C_OK:
-        raise D2CError(rc, "unknown tunable %r" % name)
-
-
 def make_params(sigma=10.0, k=32, p=0.1, block_len=32, n_unmask=1, cand_mode=0, threshold=0.0, conf_decode=0,
                 rollout_layers=0) -> d2c_params:
     return d2c_params(float(sigma), int(k), float(p), int(block_len), int(n_unmask), int(cand_mode),
@@ -137,9 +141,11 @@ def make_params(sigma=10.0, k=32, p=0.1, block_len=32, n_unmask=1, cand_mode=0, 
 class Context:
     """Owns a d2c_ctx and keeps the borrowed weight tensors alive."""
 
-    def __init__(self, dims, weights: Dict, max_seq: int, device_weights: bool = False, max_batch: int = 1):
+    def __init__(self, dims, weights: Dict, max_seq: int, device_weights: bool = False, max_batch: int = 1,
+                 tunables: Optional[Dict[str, int]] = None):
         """dims: workloads.ModelDims; weights: {tok_emb, final_norm, lm_head, layers: [{...}]} as numpy
-        float32 arrays, or (device_weights=True) as device tensors already in the storage type."""
+        float32 arrays, or (device_weights=True) as device tensors already in the storage type.
+        tunables: launch-shape tunables of this context (d2c_tools.h), in force from d2c_init_tuned on."""
         self.dims = dims
         self.dtype = dims.dtype
         self.max_seq = int(max_seq)
@@ -186,7 +192,10 @@ class Context:
                      dims.mask_id, int(max_batch))
         self.n_layers = n_layers
         self.handle = C.c_void_p()
-        rc = _lib.d2c_init(C.byref(d), C.byref(w), C.byref(self.handle))
+        tun = sorted((tunables or {}).items())
+        names = [k.encode() for k, _ in tun]
+        arr_t = (d2c_tunable * max(1, len(tun)))(*[d2c_tunable(n, int(v)) for n, (_, v) in zip(names, tun)])
+        rc = _lib.d2c_init_tuned(C.byref(d), C.byref(w), arr_t, len(tun), C.byref(self.handle))
         if rc != D2C_OK:
             raise D2CError(rc, (_lib.d2c_last_error(None) or b"").decode())
 
@@ -207,6 +216,15 @@ class Context:
 
     def workspace_bytes(self) -> int:
         return int(_lib.d2c_workspace_bytes(self.handle))
+
+    def set_tunable(self, name: str, value: int) -> None:
+        self._check(_lib.d2c_ctx_set_tunable(self.handle, name.encode(), int(value)))
+
+    def memory_info(self) -> Dict[str, int]:
+        b = (C.c_int64 * 4)()
+        self._check(_lib.d2c_memory_info(self.handle, b))
+        return dict(zip(("total_bytes", "pretiled_weight_bytes", "rollout_bytes", "attention_scratch_bytes"),
+                        [int(x) for x in b]))
 
     # ------------------------------------------------------------------ C ABI calls
     def d2c_refresh_layer(self, layer: int, hidden: torch.Tensor, idx: torch.Tensor, idx_host: np.ndarray,

@@ -10,13 +10,38 @@
 #include <vector>
 
 #include "../../include/d2c.h"
+#include "../../include/d2c_tools.h"
 #include "internal.h"
 
 using namespace d2c;
 
+bool d2c::set_tunable(Tunables& t, const char* name, int value) {
+  if (!strcmp(name, "gemm_target_wgs")) t.gemm_target_wgs = value;
+  else if (!strcmp(name, "gemm_max_splits")) t.gemm_max_splits = std::max(1, std::min(8, value));
+  else if (!strcmp(name, "gemm_nt_big_n")) t.gemm_nt_big_n = value;
+  else if (!strcmp(name, "gemm_wide_tiles")) t.gemm_wide_tiles = value;
+  else if (!strcmp(name, "gemm_wide_min_rows")) t.gemm_wide_min_rows = value;
+  else if (!strcmp(name, "gemm_tall_chunk")) t.gemm_tall_chunk = value;
+  else if (!strcmp(name, "attn_side_groups")) t.attn_side_groups = value;
+  else if (!strcmp(name, "gemm_waves")) t.gemm_waves = (value == 8 || value == 4 || value == 6 || value == 10) ? value : 0;
+  else if (!strcmp(name, "gemm_preshuffle")) t.gemm_preshuffle = value != 0;
+  else if (!strcmp(name, "gemm_rot")) t.gemm_rot = value < 0 ? 0 : value;
+  else if (!strcmp(name, "attn_tiled_min_m")) t.attn_tiled_min_m = value < 1 ? 1 : value;
+  else if (!strcmp(name, "attn_max_splits")) t.attn_max_splits = std::max(1, std::min(8, value));
+  else if (!strcmp(name, "attn_qt")) t.attn_qt = value == 1 ? 1 : value == 2 ? 2 : 0;
+  else if (!strcmp(name, "attn_target_wgs")) t.attn_target_wgs = std::max(1, value);
+  else if (!strcmp(name, "side_stream")) t.side_stream = value != 0;
+  else return false;
+  return true;
+}
+
 struct d2c_ctx {
   d2c_dims dims{};
+  Tunables tun;                 // this context's launch-shape tunables
   int device = 0;
+  int64_t pre_bytes = 0;        // library-owned pre-tiled weight copies
+  int64_t rollout_bytes = 0;    // head averages, per-head probability rows, chain scratch, rollout block
+  int64_t attn_scratch_bytes = 0;
   // borrowed weights
   const void* tok_emb = nullptr;
   const float* final_norm = nullptr;
@@ -150,7 +175,7 @@ int pre_chunks(const d2c_ctx* c, int K) { return (int)(((size_t)K * tsize(c) + 2
 // context's own projection matrices (pre-tiled when c->pre).
 int project(d2c_ctx* c, const void* A, int lda, const void* W, int m, int N, int K, GemmPlan* plan_out,
             size_t* stride_out, hipStream_t st, bool single_split = false, float* dst = nullptr) {
-  GemmPlan pl = plan_gemm(c->dims.dtype, m, N, K, single_split);
+  GemmPlan pl = plan_gemm(c->tun, c->dims.dtype, m, N, K, single_split);
   const size_t stride = (size_t)m * N;
   float* P = dst ? dst : c->partial;
   if (!dst && stride * pl.splits > c->partial_floats) return fail(c, D2C_ESHAPE, "projection partials exceed workspace");
@@ -206,7 +231,7 @@ int layer_impl(d2c_ctx* c, int layer, float* hidden, const Seg* segs, int n_seg,
                                       D.n_heads, D.n_kv_heads, D.head_dim, c->rope_cos, c->rope_sin, qb, g.k_cache,
                                       g.v_cache, st));
     D2C_TIMED(c, st, D2C_PROF_ATTENTION, 2.0 * g.L * dkv * ts,
-              launch_attention_fwd(dt, qb, g.k_cache, g.v_cache, g.m, g.L, D.n_heads, D.n_kv_heads, D.head_dim,
+              launch_attention_fwd(c->tun, dt, qb, g.k_cache, g.v_cache, g.m, g.L, D.n_heads, D.n_kv_heads, D.head_dim,
                                    (char*)c->attn_o + (size_t)g.off * dq * ts, lse + (size_t)D.n_heads * g.off,
                                    c->attn_part, c->attn_part_floats, st, g.probs));
   }
@@ -222,7 +247,7 @@ int layer_impl(d2c_ctx* c, int layer, float* hidden, const Seg* segs, int n_seg,
       const Seg& g = segs[b];
       if (g.m <= 0 || !g.abar) continue;
       D2C_TIMED(c, side, D2C_PROF_ATTN_AVG, 0.0,
-                launch_attention_avg(dt, q + (size_t)g.off * dq * ts, g.k_cache, lse + (size_t)D.n_heads * g.off, g.m,
+                launch_attention_avg(c->tun, dt, q + (size_t)g.off * dq * ts, g.k_cache, lse + (size_t)D.n_heads * g.off, g.m,
                                      g.L, D.n_heads, D.n_kv_heads, D.head_dim, g.abar, c->avg_part,
                                      c->avg_part_floats, side, /*one_group=*/side != st));
       if (g.roll_out)
@@ -235,7 +260,7 @@ int layer_impl(d2c_ctx* c, int layer, float* hidden, const Seg* segs, int n_seg,
             launch_add_norm(dt, hidden, c->partial, pl.splits, stride, d, M, d, c->ffn_norm[layer], D.rms_eps,
                             c->a_norm, st));
   if (c->fused_swiglu) {
-    pl = plan_gemm(dt, M, 2 * F, d, true);
+    pl = plan_gemm(c->tun, dt, M, 2 * F, d, true);
     D2C_TIMED(c, st, D2C_PROF_GEMM, 2.0 * F * d * tsize(c),
               launch_gemm_swiglu(dt, pl, c->a_norm, d, c->w_gate_up[layer], pre_chunks(c, d), c->act, F, M, d, st));
   } else {
@@ -270,12 +295,37 @@ int check_params(d2c_ctx* c, const d2c_params* p) {
   return D2C_OK;
 }
 
+// Floats of split partials, attention partials and head-average partials that the launch plans can ask for
+// under tunables t, over every row count and sequence length the context admits.
+struct WsNeeds { size_t partial, attn_part, avg_part; };
+WsNeeds ws_needs(const d2c_dims& D, size_t max_rows, const Tunables& t) {
+  const int dq = D.n_heads * D.head_dim, dkv = D.n_kv_heads * D.head_dim;
+  const int shapes[4][2] = {{dq + 2 * dkv, D.d_model}, {D.d_model, dq}, {2 * D.d_ffn, D.d_model}, {D.d_model, D.d_ffn}};
+  WsNeeds n{0, 0, 0};
+  for (int m = 1; m <= (int)max_rows; ++m)
+    for (auto& s : shapes) {
+      // up to 128 rows leave room for the largest split count; beyond that the planner's choice is taken
+      const GemmPlan pl = plan_gemm(t, D.dtype, m, s[0], s[1]);
+      n.partial = std::max(n.partial, (size_t)(m <= 128 ? 8 : pl.splits) * m * s[0]);
+    }
+  n.attn_part = attention_scratch_floats(t, D.dtype, D.max_seq, D.max_seq, D.n_heads, D.head_dim);
+  n.avg_part = attention_avg_scratch_floats(t, D.dtype, D.max_seq, D.max_seq, D.n_heads);
+  return n;
+}
+
 }  // namespace
 
 extern "C" {
 
-int d2c_init(const d2c_dims* dims, const d2c_weights* w, d2c_ctx** out) {
+int d2c_init(const d2c_dims* dims, const d2c_weights* w, d2c_ctx** out) { return d2c_init_tuned(dims, w, nullptr, 0, out); }
+
+int d2c_init_tuned(const d2c_dims* dims, const d2c_weights* w, const d2c_tunable* tun, int32_t n_tun, d2c_ctx** out) {
   if (!dims || !w || !out) return fail(nullptr, D2C_EINVAL, "null argument");
+  if (n_tun < 0 || (n_tun > 0 && !tun)) return fail(nullptr, D2C_EINVAL, "bad tunable list");
+  Tunables tn;
+  for (int i = 0; i < n_tun; ++i)
+    if (!tun[i].name || !set_tunable(tn, tun[i].name, tun[i].value))
+      return fail(nullptr, D2C_EINVAL, std::string("unknown tunable ") + (tun[i].name ? tun[i].name : "(null)"));
   const d2c_dims& D = *dims;
   if (D.n_layers <= 0 || D.d_model <= 0 || D.n_heads <= 0 || D.n_kv_heads <= 0 || D.head_dim <= 0 || D.d_ffn <= 0 ||
       D.vocab <= 0 || D.max_seq <= 0)
@@ -302,6 +352,7 @@ int d2c_init(const d2c_dims* dims, const d2c_weights* w, d2c_ctx** out) {
   d2c_ctx* c = new (std::nothrow) d2c_ctx();
   if (!c) return fail(nullptr, D2C_ENOMEM, "out of host memory");
   c->dims = D;
+  c->tun = tn;
   c->tok_emb = w->tok_emb; c->final_norm = w->final_norm; c->lm_head = w->lm_head;
   for (int l = 0; l < D.n_layers; ++l) {
     c->attn_norm.push_back(w->attn_norm[l]); c->wqkv.push_back(w->wqkv[l]); c->wo.push_back(w->wo[l]);
@@ -316,20 +367,13 @@ int d2c_init(const d2c_dims* dims, const d2c_weights* w, d2c_ctx** out) {
   c->max_rows = (size_t)D.max_seq * c->max_batch;
   const size_t ts = tsize(c), Lm = (size_t)D.max_seq, Lr = c->max_rows, d = (size_t)D.d_model, dq = (size_t)d_q(c),
                F = (size_t)D.d_ffn;
-  // largest split-partial footprint over every row count the context can see
-  const int shapes[4][2] = {{d_q(c) + 2 * d_kv(c), D.d_model}, {D.d_model, d_q(c)}, {2 * D.d_ffn, D.d_model},
-                            {D.d_model, D.d_ffn}};
-  size_t pf = 0;
-  for (int m = 1; m <= (int)Lr; ++m)
-    for (auto& s : shapes) {
-      // up to 128 rows leave room for the largest split count; beyond that the planner's choice is taken
-      GemmPlan pl = plan_gemm(D.dtype, m, s[0], s[1]);
-      pf = std::max(pf, (size_t)(m <= 128 ? 8 : pl.splits) * m * s[0]);
-    }
+  const WsNeeds need = ws_needs(D, Lr, c->tun);
+  const size_t pf = need.partial;
   c->partial_floats = pf;
   c->head_rows = (int)std::min<size_t>(Lm, 256);
-  c->attn_part_floats = attention_scratch_floats(D.dtype, D.max_seq, D.max_seq, D.n_heads, D.head_dim);
-  c->avg_part_floats = attention_avg_scratch_floats(D.dtype, D.max_seq, D.max_seq, D.n_heads);
+  c->attn_part_floats = need.attn_part;
+  c->avg_part_floats = need.avg_part;
+  const int64_t ws0 = c->ws_bytes;
   if ((rc = ws_alloc(c, &c->roll, Lm * Lm * 4)) ||
       (rc = ws_alloc(c, &c->abar_all, (size_t)c->max_batch * D.n_layers * Lm * Lm * 4)))
     return bail(rc);
@@ -338,6 +382,8 @@ int d2c_init(const d2c_dims* dims, const d2c_weights* w, d2c_ctx** out) {
       (rc = ws_alloc(c, &c->chain_u, (size_t)D.n_layers * Lm * 4)) ||
       (rc = ws_alloc(c, &c->chain_g, (size_t)D.n_layers * Lm * Lm * 4)))
     return bail(rc);
+  c->rollout_bytes = c->ws_bytes - ws0;
+  c->attn_scratch_bytes = (int64_t)(std::max<size_t>(1, c->attn_part_floats) + std::max<size_t>(1, c->avg_part_floats)) * 4;
   if ((rc = ws_alloc(c, &c->hidden, Lr * d * 4)) || (rc = ws_alloc(c, &c->a_norm, Lr * d * ts)) ||
       (rc = ws_alloc(c, &c->q, (size_t)D.n_layers * Lr * dq * ts)) || (rc = ws_alloc(c, &c->attn_o, Lr * dq * ts)) ||
       (rc = ws_alloc(c, &c->act, Lr * F * ts)) ||
@@ -362,7 +408,7 @@ int d2c_init(const d2c_dims* dims, const d2c_weights* w, d2c_ctx** out) {
       return bail(fail(c, D2C_EHIP, "hipEventCreateWithFlags failed"));
   if (hipEventCreateWithFlags(&c->side_done, hipEventDisableTiming) != hipSuccess)
     return bail(fail(c, D2C_EHIP, "hipEventCreateWithFlags failed"));
-  if (tunables().gemm_preshuffle) {
+  if (c->tun.gemm_preshuffle) {
     // library-owned pre-tiled copies of every projection matrix; the caller's matrices are read here only
     // (whatever stream wrote them must be done: wait for the device once)
     if (hipDeviceSynchronize() != hipSuccess) return bail(fail(c, D2C_EHIP, "hipDeviceSynchronize failed"));
@@ -373,6 +419,7 @@ int d2c_init(const d2c_dims* dims, const d2c_weights* w, d2c_ctx** out) {
       if (rc2) return rc2;
       hipError_t e = launch_preshuffle(D.dtype, W, K, N, K, dstp, nullptr, half);
       if (e != hipSuccess) return fail(c, D2C_EHIP, std::string("preshuffle: ") + hipGetErrorString(e));
+      c->pre_bytes += (int64_t)preshuffled_bytes(N, K, D.dtype);
       W = dstp;
       return D2C_OK;
     };
@@ -413,7 +460,7 @@ int64_t d2c_workspace_bytes(const d2c_ctx* c) { return c ? c->ws_bytes : 0; }
 
 int d2c_plan_projection(int32_t dtype, int32_t m, int32_t N, int32_t K, int32_t single_split, int32_t shape[7]) {
   if (!shape || (dtype != D2C_F32 && dtype != D2C_BF16) || m <= 0 || N <= 0 || K <= 0) return D2C_EINVAL;
-  const GemmPlan pl = plan_gemm(dtype, m, N, K, single_split != 0);
+  const GemmPlan pl = plan_gemm(Tunables{}, dtype, m, N, K, single_split != 0);
   const int cols = 16 * pl.nt * pl.waves;
   shape[0] = pl.mt;
   shape[1] = pl.nt;
@@ -425,25 +472,25 @@ int d2c_plan_projection(int32_t dtype, int32_t m, int32_t N, int32_t K, int32_t 
   return D2C_OK;
 }
 
-int d2c_set_tunable(const char* name, int32_t value) {
-  if (!name) return D2C_EINVAL;
-  Tunables& t = tunables();
-  if (!strcmp(name, "gemm_target_wgs")) t.gemm_target_wgs = value;
-  else if (!strcmp(name, "gemm_max_splits")) t.gemm_max_splits = std::max(1, std::min(8, (int)value));
-  else if (!strcmp(name, "gemm_nt_big_n")) t.gemm_nt_big_n = value;
-  else if (!strcmp(name, "gemm_wide_tiles")) t.gemm_wide_tiles = value;
-  else if (!strcmp(name, "gemm_wide_min_rows")) t.gemm_wide_min_rows = value;
-  else if (!strcmp(name, "gemm_tall_chunk")) t.gemm_tall_chunk = value;
-  else if (!strcmp(name, "attn_side_groups")) t.attn_side_groups = value;
-  else if (!strcmp(name, "gemm_waves")) t.gemm_waves = (value == 8 || value == 4 || value == 6 || value == 10) ? value : 0;
-  else if (!strcmp(name, "gemm_preshuffle")) t.gemm_preshuffle = value != 0;
-  else if (!strcmp(name, "gemm_rot")) t.gemm_rot = value < 0 ? 0 : value;
-  else if (!strcmp(name, "attn_tiled_min_m")) t.attn_tiled_min_m = value < 1 ? 1 : value;
-  else if (!strcmp(name, "attn_max_splits")) t.attn_max_splits = std::max(1, std::min(8, (int)value));
-  else if (!strcmp(name, "attn_qt")) t.attn_qt = value == 1 ? 1 : value == 2 ? 2 : 0;
-  else if (!strcmp(name, "attn_target_wgs")) t.attn_target_wgs = std::max(1, (int)value);
-  else if (!strcmp(name, "side_stream")) t.side_stream = value != 0;
-  else return D2C_EINVAL;
+int d2c_ctx_set_tunable(d2c_ctx* c, const char* name, int32_t value) {
+  if (!c || !name) return D2C_EINVAL;
+  if (!strcmp(name, "gemm_preshuffle")) return fail(c, D2C_EINVAL, "gemm_preshuffle is fixed at d2c_init_tuned");
+  Tunables t = c->tun;
+  if (!set_tunable(t, name, value)) return fail(c, D2C_EINVAL, std::string("unknown tunable ") + name);
+  // the workspace was sized for the launch shapes of the tunables given at init: a change that asks for more is refused
+  const WsNeeds need = ws_needs(c->dims, c->max_rows, t);
+  if (need.partial > c->partial_floats || need.attn_part > c->attn_part_floats || need.avg_part > c->avg_part_floats)
+    return fail(c, D2C_ESHAPE, std::string("tunable ") + name + " needs more workspace than the context holds: pass it to d2c_init_tuned");
+  c->tun = t;
+  return D2C_OK;
+}
+
+int d2c_memory_info(const d2c_ctx* c, int64_t bytes[4]) {
+  if (!c || !bytes) return D2C_EINVAL;
+  bytes[0] = c->ws_bytes;
+  bytes[1] = c->pre_bytes;
+  bytes[2] = c->rollout_bytes;
+  bytes[3] = c->attn_scratch_bytes;
   return D2C_OK;
 }
 
@@ -547,11 +594,11 @@ int d2c_attention(d2c_ctx* c, const void* q, const int32_t* idx, int32_t m, cons
     D2C_HIP(c, launch_scatter_rows(D.dtype, new_k, k_cache, new_v, v_cache, idx, m, d_kv(c), st));
   }
   D2C_TIMED(c, st, D2C_PROF_ATTENTION, 2.0 * L * d_kv(c) * tsize(c),
-            launch_attention_fwd(D.dtype, q, k_cache, v_cache, m, L, D.n_heads, D.n_kv_heads, D.head_dim, out, c->lse,
+            launch_attention_fwd(c->tun, D.dtype, q, k_cache, v_cache, m, L, D.n_heads, D.n_kv_heads, D.head_dim, out, c->lse,
                                  c->attn_part, c->attn_part_floats, st));
   if (attn_avg)
     D2C_TIMED(c, st, D2C_PROF_ATTN_AVG, 0.0,
-              launch_attention_avg(D.dtype, q, k_cache, c->lse, m, L, D.n_heads, D.n_kv_heads, D.head_dim, attn_avg,
+              launch_attention_avg(c->tun, D.dtype, q, k_cache, c->lse, m, L, D.n_heads, D.n_kv_heads, D.head_dim, attn_avg,
                                    c->avg_part, c->avg_part_floats, st));
   return D2C_OK;
 }
@@ -564,9 +611,9 @@ int d2c_linear(d2c_ctx* c, const void* a, const void* w, int32_t m, int32_t N, i
   if (m == 0) return D2C_OK;
   if (!a || !w || !out) return fail(c, D2C_EINVAL, "null buffer");
   hipStream_t st = (hipStream_t)stream;
-  GemmPlan pl = plan_gemm(c->dims.dtype, m, N, K);
+  GemmPlan pl = plan_gemm(c->tun, c->dims.dtype, m, N, K);
   const size_t stride = (size_t)m * N;
-  if (stride * pl.splits > c->partial_floats) pl = plan_gemm(c->dims.dtype, m, N, K, true);   // no room for partials
+  if (stride * pl.splits > c->partial_floats) pl = plan_gemm(c->tun, c->dims.dtype, m, N, K, true);   // no room for partials
   if (pl.splits == 1) {
     D2C_TIMED(c, st, D2C_PROF_GEMM, (double)N * K * tsize(c),
               launch_gemm(c->dims.dtype, pl, a, K, w, K, out, N, stride, m, N, K, st));
@@ -602,7 +649,7 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
     if (s.n_s < 0 || s.n_s > s.L || s.n_rows < 0 || s.n_rows > s.n_s) return fail(c, D2C_EINVAL, "bad set sizes");
   }
   hipStream_t st = (hipStream_t)stream;
-  hipStream_t side = tunables().side_stream ? c->side : st;
+  hipStream_t side = c->tun.side_stream ? c->side : st;
   const int dt = D.dtype, d = D.d_model;
   const size_t ts = tsize(c), cache_layer = (size_t)d_kv(c) * ts;
   const int roll_layers = p->rollout_layers > 0 ? std::min(p->rollout_layers, D.n_layers) : D.n_layers;
@@ -655,7 +702,7 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
           segs[i].v_cache = (char*)s.v_cache + (size_t)l * s.L * cache_layer;
           // few rows: the attention launch writes the per-head rows itself and the head means of all layers
           // are taken in one launch after the last layer; otherwise a second pass per layer on the side stream
-          const bool emits = attention_fwd_emits_probs(dt, segs[i].m, s.L);
+          const bool emits = attention_fwd_emits_probs(c->tun, dt, segs[i].m, s.L);
           segs[i].probs = in_rollout && emits ? probs_slot(i, l) : nullptr;
           segs[i].abar = in_rollout && !emits ? abar_slot(i, l) : nullptr;
           segs[i].roll_in = nullptr;               // no rollout block here: Eq. 9 comes from the chain below
@@ -671,7 +718,7 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
     // reverse order, one launch per sequence.  It runs beside the last layer's FFN and the LM head.
     for (int i = 0; i < n_seg; ++i) {
       d2c_seq_state& s = seqs[group[i]];
-      if (attention_fwd_emits_probs(dt, segs[i].m, s.L))
+      if (attention_fwd_emits_probs(c->tun, dt, segs[i].m, s.L))
         D2C_TIMED(c, side, D2C_PROF_ATTN_AVG, 0.0,
                   launch_head_mean(probs_slot(i, 0), c->probs_floats, abar_slot(i, 0), abar_stride, roll_layers,
                                    D.n_heads, segs[i].m, s.L, side));

@@ -22,7 +22,7 @@
 // fp32 path (small test model only): the same two passes, one workgroup per query row, plain FMA.
 #include <algorithm>
 
-#include "common.cuh"
+#include "common.h"
 #include "internal.h"
 
 namespace d2c {
@@ -488,8 +488,8 @@ hipError_t launch_avg_bf16(const void* q, const void* k_cache, const float* lse,
 
 constexpr int kProbsMaxM = 128, kProbsMaxL = 1024;
 
-bool attention_fwd_emits_probs(int dtype, int m, int L) {
-  return dtype == kBF16 && m > 0 && m < tunables().attn_tiled_min_m && m <= kProbsMaxM && L <= kProbsMaxL;
+bool attention_fwd_emits_probs(const Tunables& t, int dtype, int m, int L) {
+  return dtype == kBF16 && m > 0 && m < t.attn_tiled_min_m && m <= kProbsMaxM && L <= kProbsMaxL;
 }
 
 size_t attention_probs_floats(int dtype, int n_heads, int max_L) {
@@ -505,19 +505,19 @@ hipError_t launch_head_mean(const float* probs, size_t probs_layer_stride, float
   return hipGetLastError();
 }
 
-size_t attention_scratch_floats(int dtype, int max_m, int max_L, int n_heads, int head_dim) {
-  return dtype == kBF16 ? attention_tiled_scratch_floats(max_m, max_L, n_heads, head_dim) : 0;
+size_t attention_scratch_floats(const Tunables& t, int dtype, int max_m, int max_L, int n_heads, int head_dim) {
+  return dtype == kBF16 ? attention_tiled_scratch_floats(t, max_m, max_L, n_heads, head_dim) : 0;
 }
 
-hipError_t launch_attention_fwd(int dtype, const void* q, const void* k_cache, const void* v_cache, int m, int L,
+hipError_t launch_attention_fwd(const Tunables& t, int dtype, const void* q, const void* k_cache, const void* v_cache, int m, int L,
                                 int n_heads, int n_kv_heads, int head_dim, void* out, float* lse, float* scratch,
                                 size_t scratch_floats, hipStream_t st, float* probs) {
   if (m <= 0) return hipSuccess;
   if (L <= 0 || n_heads % n_kv_heads) return hipErrorInvalidValue;
-  if (probs && !attention_fwd_emits_probs(dtype, m, L)) return hipErrorInvalidValue;
+  if (probs && !attention_fwd_emits_probs(t, dtype, m, L)) return hipErrorInvalidValue;
   if (dtype == kBF16) {
-    if (m >= tunables().attn_tiled_min_m)
-      return launch_attention_tiled_fwd(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, head_dim, out, lse, scratch,
+    if (m >= t.attn_tiled_min_m)
+      return launch_attention_tiled_fwd(t, q, k_cache, v_cache, m, L, n_heads, n_kv_heads, head_dim, out, lse, scratch,
                                         scratch_floats, st);
     if (head_dim == 128)
       return launch_fwd_bf16<128>(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, probs, st);
@@ -532,18 +532,18 @@ hipError_t launch_attention_fwd(int dtype, const void* q, const void* k_cache, c
   return hipGetLastError();
 }
 
-size_t attention_avg_scratch_floats(int dtype, int max_m, int max_L, int n_heads) {
-  return dtype == kBF16 ? attention_tiled_avg_scratch_floats(max_m, max_L, n_heads) : 0;
+size_t attention_avg_scratch_floats(const Tunables& t, int dtype, int max_m, int max_L, int n_heads) {
+  return dtype == kBF16 ? attention_tiled_avg_scratch_floats(t, max_m, max_L, n_heads) : 0;
 }
 
-hipError_t launch_attention_avg(int dtype, const void* q, const void* k_cache, const float* lse, int m, int L,
+hipError_t launch_attention_avg(const Tunables& t, int dtype, const void* q, const void* k_cache, const float* lse, int m, int L,
                                 int n_heads, int n_kv_heads, int head_dim, float* attn_avg, float* scratch,
                                 size_t scratch_floats, hipStream_t st, bool one_group) {
   if (m <= 0) return hipSuccess;
   if (L <= 0 || n_heads % n_kv_heads) return hipErrorInvalidValue;
   if (dtype == kBF16) {
-    if (m >= tunables().attn_tiled_min_m)
-      return launch_attention_tiled_avg(q, k_cache, lse, m, L, n_heads, n_kv_heads, head_dim, attn_avg, scratch,
+    if (m >= t.attn_tiled_min_m)
+      return launch_attention_tiled_avg(t, q, k_cache, lse, m, L, n_heads, n_kv_heads, head_dim, attn_avg, scratch,
                                         scratch_floats, st, one_group);
     if (head_dim == 128) return launch_avg_bf16<128>(q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, st);
     if (head_dim == 64) return launch_avg_bf16<64>(q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, st);

@@ -21,7 +21,7 @@
 #include <algorithm>
 #include <cmath>
 
-#include "common.cuh"
+#include "common.h"
 #include "internal.h"
 
 namespace d2c {
@@ -472,15 +472,15 @@ constexpr int kTargetWgs = 256;       // one workgroup per compute unit before t
 struct FwdPlan {
   int qt, q_blocks, n_splits, keys_per_split;
 };
-FwdPlan plan_fwd(int m, int L, int n_heads) {
+FwdPlan plan_fwd(const Tunables& t, int m, int L, int n_heads) {
   FwdPlan p;
-  const int want_qt = tunables().attn_qt;
+  const int want_qt = t.attn_qt;
   p.qt = want_qt == 1 ? 1 : want_qt == 2 ? 2 : (m > 64 ? 2 : 1);
   p.q_blocks = (m + 64 * p.qt - 1) / (64 * p.qt);
   const int blocks = (L + kBlockKeys - 1) / kBlockKeys;
   int splits = 1;
-  const int max_splits = std::max(1, std::min(8, tunables().attn_max_splits));
-  while (splits < max_splits && p.q_blocks * n_heads * splits < tunables().attn_target_wgs && blocks / (splits * 2) >= 1) splits *= 2;
+  const int max_splits = std::max(1, std::min(8, t.attn_max_splits));
+  while (splits < max_splits && p.q_blocks * n_heads * splits < t.attn_target_wgs && blocks / (splits * 2) >= 1) splits *= 2;
   const int blocks_per_split = (blocks + splits - 1) / splits;
   p.keys_per_split = blocks_per_split * kBlockKeys;
   p.n_splits = (L + p.keys_per_split - 1) / p.keys_per_split;     // every split holds at least one key
@@ -488,9 +488,9 @@ FwdPlan plan_fwd(int m, int L, int n_heads) {
 }
 
 template <int DH>
-hipError_t launch_fwd(const void* q, const void* k_cache, const void* v_cache, int m, int L, int n_heads,
+hipError_t launch_fwd(const Tunables& t, const void* q, const void* k_cache, const void* v_cache, int m, int L, int n_heads,
                       int n_kv_heads, void* out, float* lse, float* scratch, size_t scratch_floats, hipStream_t st) {
-  const FwdPlan p = plan_fwd(m, L, n_heads);
+  const FwdPlan p = plan_fwd(t, m, L, n_heads);
   if (p.n_splits > 1 && (size_t)p.n_splits * n_heads * m * (DH + 2) > scratch_floats) return hipErrorInvalidValue;
   const float scale = 1.0f / sqrtf((float)DH);
   float* o_part = scratch;
@@ -517,7 +517,7 @@ hipError_t launch_fwd(const void* q, const void* k_cache, const void* v_cache, i
 struct AvgPlan {
   int ka, qt, key_blocks, q_blocks, groups, heads_per_group;
 };
-AvgPlan plan_avg(int m, int L, int n_heads, bool one_group = false) {
+AvgPlan plan_avg(const Tunables& t, int m, int L, int n_heads, bool one_group = false) {
   AvgPlan p;
   // the largest tile the row and key counts fill: 128 x 128, 64 x 128 (m <= 64) or 64 x 32 (L <= 32)
   p.qt = m > 64 ? 2 : 1;
@@ -529,7 +529,7 @@ AvgPlan plan_avg(int m, int L, int n_heads, bool one_group = false) {
   // one_group: the caller runs the launch beside other work and wants less total work rather than the
   // shortest launch: fewer head groups, fewer partials to add
   int groups = 1;
-  const int max_groups = one_group ? std::max(1, std::min(8, tunables().attn_side_groups)) : 8;
+  const int max_groups = one_group ? std::max(1, std::min(8, t.attn_side_groups)) : 8;
   while (groups < max_groups && groups * 2 <= n_heads && (size_t)p.q_blocks * p.key_blocks * groups < 2 * kTargetWgs) groups *= 2;
   p.heads_per_group = (n_heads + groups - 1) / groups;
   p.groups = (n_heads + p.heads_per_group - 1) / p.heads_per_group;
@@ -537,11 +537,11 @@ AvgPlan plan_avg(int m, int L, int n_heads, bool one_group = false) {
 }
 
 template <int DH>
-hipError_t launch_avg(const void* q, const void* k_cache, const float* lse, int m, int L, int n_heads,
+hipError_t launch_avg(const Tunables& t, const void* q, const void* k_cache, const float* lse, int m, int L, int n_heads,
                       int n_kv_heads, float* attn_avg, float* scratch, size_t scratch_floats, hipStream_t st,
                       bool one_group) {
   const float scale = 1.0f / sqrtf((float)DH);
-  const AvgPlan p = plan_avg(m, L, n_heads, one_group);
+  const AvgPlan p = plan_avg(t, m, L, n_heads, one_group);
   if (p.groups > 1 && (!scratch || (size_t)p.groups * m * L > scratch_floats)) return hipErrorInvalidValue;
   float* dst = p.groups > 1 ? scratch : attn_avg;
   const dim3 grid(p.q_blocks, p.key_blocks, p.groups);
@@ -562,12 +562,12 @@ hipError_t launch_avg(const void* q, const void* k_cache, const float* lse, int 
 
 // Worst case over every (m <= max_m, L <= max_L): the split count depends on the number of 64-key blocks
 // and shorter sequences can be split as often as longer ones, so both are scanned (L at block boundaries).
-size_t attention_tiled_scratch_floats(int max_m, int max_L, int n_heads, int head_dim) {
+size_t attention_tiled_scratch_floats(const Tunables& t, int max_m, int max_L, int n_heads, int head_dim) {
   size_t worst = 0;
   for (int L = kBlockKeys;; L += kBlockKeys) {
     const int Lc = std::min(L, max_L);
     for (int m = 1; m <= max_m; ++m) {
-      const FwdPlan p = plan_fwd(m, Lc, n_heads);
+      const FwdPlan p = plan_fwd(t, m, Lc, n_heads);
       if (p.n_splits > 1) worst = std::max(worst, (size_t)p.n_splits * n_heads * m * (head_dim + 2));
     }
     if (L >= max_L) break;
@@ -575,24 +575,24 @@ size_t attention_tiled_scratch_floats(int max_m, int max_L, int n_heads, int hea
   return worst;
 }
 
-hipError_t launch_attention_tiled_fwd(const void* q, const void* k_cache, const void* v_cache, int m, int L,
+hipError_t launch_attention_tiled_fwd(const Tunables& t, const void* q, const void* k_cache, const void* v_cache, int m, int L,
                                       int n_heads, int n_kv_heads, int head_dim, void* out, float* lse,
                                       float* scratch, size_t scratch_floats, hipStream_t st) {
   if (head_dim == 128)
-    return launch_fwd<128>(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, scratch, scratch_floats, st);
+    return launch_fwd<128>(t, q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, scratch, scratch_floats, st);
   if (head_dim == 64)
-    return launch_fwd<64>(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, scratch, scratch_floats, st);
+    return launch_fwd<64>(t, q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, scratch, scratch_floats, st);
   return hipErrorInvalidValue;
 }
 
 // Worst case over every (m <= max_m, L <= max_L): a short sequence has few key tiles and therefore more
 // head groups, so the product groups * m * L does not peak at max_L; L is scanned at tile boundaries.
-size_t attention_tiled_avg_scratch_floats(int max_m, int max_L, int n_heads) {
+size_t attention_tiled_avg_scratch_floats(const Tunables& t, int max_m, int max_L, int n_heads) {
   size_t worst = 0;
   for (int L = 32;; L += 32) {
     const int Lc = std::min(L, max_L);
     for (int m = 1; m <= max_m; ++m) {
-      const AvgPlan p = plan_avg(m, Lc, n_heads);
+      const AvgPlan p = plan_avg(t, m, Lc, n_heads);
       if (p.groups > 1) worst = std::max(worst, (size_t)p.groups * m * Lc);
     }
     if (L >= max_L) break;
@@ -600,14 +600,14 @@ size_t attention_tiled_avg_scratch_floats(int max_m, int max_L, int n_heads) {
   return worst;
 }
 
-hipError_t launch_attention_tiled_avg(const void* q, const void* k_cache, const float* lse, int m, int L,
+hipError_t launch_attention_tiled_avg(const Tunables& t, const void* q, const void* k_cache, const float* lse, int m, int L,
                                       int n_heads, int n_kv_heads, int head_dim, float* attn_avg, float* scratch,
                                       size_t scratch_floats, hipStream_t st, bool one_group) {
   if (head_dim == 128)
-    return launch_avg<128>(q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, scratch, scratch_floats, st,
+    return launch_avg<128>(t, q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, scratch, scratch_floats, st,
                            one_group);
   if (head_dim == 64)
-    return launch_avg<64>(q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, scratch, scratch_floats, st,
+    return launch_avg<64>(t, q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, scratch, scratch_floats, st,
                           one_group);
   return hipErrorInvalidValue;
 }

@@ -20,15 +20,10 @@
 //     XCDs, each with its own L2: the mapping below gives the row chunks of one weight
 //     tile consecutive slots of the SAME XCD, so the tile comes from HBM once and the
 //     other chunks hit it in L2.
-#include "common.cuh"
+#include "common.h"
 #include "internal.h"
 
 namespace d2c {
-
-Tunables& tunables() {
-  static Tunables t;
-  return t;
-}
 
 namespace {
 
@@ -411,8 +406,7 @@ __global__ __launch_bounds__(256) void preshuffle_kernel(const unsigned char* __
 
 }  // namespace
 
-GemmPlan plan_gemm(int dtype, int m, int N, int K, bool single_split) {
-  const Tunables& t = tunables();
+GemmPlan plan_gemm(const Tunables& t, int dtype, int m, int N, int K, bool single_split) {
   GemmPlan pl;
   const int tiles = (m + 15) / 16;
   pl.mt = tiles <= 8 ? (tiles < 1 ? 1 : tiles) : 8;

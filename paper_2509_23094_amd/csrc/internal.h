@@ -10,7 +10,8 @@ enum DType { kF32 = 0, kBF16 = 1 };
 
 inline size_t dtype_size(int dt) { return dt == kBF16 ? 2 : 4; }
 
-// Tunables (defaults chosen by measurement; d2c_set_tunable changes them).
+// Launch-shape tunables.  Every context holds its own copy (defaults chosen by measurement); the tooling
+// calls d2c_init_tuned / d2c_ctx_set_tunable change them per context.
 struct Tunables {
   int gemm_target_wgs = 384;   // aim for at least this many groups of 4 waves per GEMM
   int gemm_max_splits = 8;
@@ -29,7 +30,8 @@ struct Tunables {
   int attn_target_wgs = 256;   // split the key range until the forward grid has this many workgroups
   bool side_stream = true;     // d2c_step: head average + rollout on a second stream
 };
-Tunables& tunables();
+// name -> field; false for an unknown name
+bool set_tunable(Tunables& t, const char* name, int value);
 
 // ---- GEMM on a ragged handful of rows: P[s] = A[m,K] * W[N,K]^T over the k-range of split s
 struct GemmPlan {
@@ -41,7 +43,7 @@ struct GemmPlan {
   int row_chunks;
   int rot;       // multiplier of the per-workgroup start-chunk rotation (0 = none)
 };
-GemmPlan plan_gemm(int dtype, int m, int N, int K, bool single_split = false);
+GemmPlan plan_gemm(const Tunables& t, int dtype, int m, int N, int K, bool single_split = false);
 // P must hold plan.splits * split_stride floats; split_stride >= m * ldp.
 // pre = W is a pre-tiled copy made by launch_preshuffle (then ldw = 256-byte chunks per row).
 hipError_t launch_gemm(int dtype, const GemmPlan& plan, const void* A, int lda, const void* W, int ldw,
@@ -89,12 +91,12 @@ hipError_t launch_rope_table(float* cos_t, float* sin_t, int max_pos, int head_d
 // ---- attention of m query rows against all L cached keys, no mask, in two launches
 // fwd: out T [m, H*dh] and the log-sum-exp per (head, row), lse float [H, m]
 // scratch: attention_scratch_floats(...) floats (partials of a split key range), may be null for fp32
-size_t attention_scratch_floats(int dtype, int max_m, int max_L, int n_heads, int head_dim);
+size_t attention_scratch_floats(const Tunables& t, int dtype, int max_m, int max_L, int n_heads, int head_dim);
 // probs (optional, only where attention_fwd_emits_probs): float [H, m, L], the normalised attention rows of
 // every head, written by the same launch; launch_head_mean turns them into the head average.
-bool attention_fwd_emits_probs(int dtype, int m, int L);
+bool attention_fwd_emits_probs(const Tunables& t, int dtype, int m, int L);
 size_t attention_probs_floats(int dtype, int n_heads, int max_L);      // capacity one (layer, sequence) needs
-hipError_t launch_attention_fwd(int dtype, const void* q, const void* k_cache, const void* v_cache, int m, int L,
+hipError_t launch_attention_fwd(const Tunables& t, int dtype, const void* q, const void* k_cache, const void* v_cache, int m, int L,
                                 int n_heads, int n_kv_heads, int head_dim, void* out, float* lse, float* scratch,
                                 size_t scratch_floats, hipStream_t st, float* probs = nullptr);
 // abar[l] (at abar + l * abar_layer_stride, [m, L]) = mean over heads of probs[l] (at probs + l * stride, [H, m, L])
@@ -102,20 +104,20 @@ hipError_t launch_head_mean(const float* probs, size_t probs_layer_stride, float
                             int n_layers, int n_heads, int m, int L, hipStream_t st);
 // avg: attn_avg float [m, L] = mean over heads of exp(q k / sqrt(dh) - lse); needs fwd's lse
 // scratch: attention_avg_scratch_floats(...) floats (per-head-group partials), may be null for fp32
-size_t attention_avg_scratch_floats(int dtype, int max_m, int max_L, int n_heads);
+size_t attention_avg_scratch_floats(const Tunables& t, int dtype, int max_m, int max_L, int n_heads);
 // one_group: least total work (no head groups, no partials) instead of the shortest launch, for a caller
 // that runs the head average beside other work
-hipError_t launch_attention_avg(int dtype, const void* q, const void* k_cache, const float* lse, int m, int L,
+hipError_t launch_attention_avg(const Tunables& t, int dtype, const void* q, const void* k_cache, const float* lse, int m, int L,
                                 int n_heads, int n_kv_heads, int head_dim, float* attn_avg, float* scratch,
                                 size_t scratch_floats, hipStream_t st, bool one_group = false);
 
 // the bf16 kernels for many query rows (K/V blocks staged through LDS, optional key split + merge)
-size_t attention_tiled_scratch_floats(int max_m, int max_L, int n_heads, int head_dim);
-hipError_t launch_attention_tiled_fwd(const void* q, const void* k_cache, const void* v_cache, int m, int L,
+size_t attention_tiled_scratch_floats(const Tunables& t, int max_m, int max_L, int n_heads, int head_dim);
+hipError_t launch_attention_tiled_fwd(const Tunables& t, const void* q, const void* k_cache, const void* v_cache, int m, int L,
                                       int n_heads, int n_kv_heads, int head_dim, void* out, float* lse,
                                       float* scratch, size_t scratch_floats, hipStream_t st);
-size_t attention_tiled_avg_scratch_floats(int max_m, int max_L, int n_heads);
-hipError_t launch_attention_tiled_avg(const void* q, const void* k_cache, const float* lse, int m, int L,
+size_t attention_tiled_avg_scratch_floats(const Tunables& t, int max_m, int max_L, int n_heads);
+hipError_t launch_attention_tiled_avg(const Tunables& t, const void* q, const void* k_cache, const float* lse, int m, int L,
                                       int n_heads, int n_kv_heads, int head_dim, float* attn_avg, float* scratch,
                                       size_t scratch_floats, hipStream_t st, bool one_group = false);
 

@@ -3,7 +3,7 @@
 // RoPE + K/V cache update ("updates their KV states", Sec. 4 overview), SwiGLU.
 // All of them are HBM/L2-bound copies with a little arithmetic: one workgroup
 // per row, 16-byte coalesced accesses where the layout allows.
-#include "common.cuh"
+#include "common.h"
 #include "internal.h"
 
 namespace d2c {
@@ -327,7 +327,9 @@ hipError_t launch_qkv_rope_scatter(int dtype, const float* P, int n_splits, size
                                    void* k_cache, void* v_cache, hipStream_t st) {
   if (m <= 0) return hipSuccess;
   if (head_dim % 2) return hipErrorInvalidValue;
-  if (head_dim % 8 == 0 && ldp % 4 == 0 && split_stride % 4 == 0) {
+  // the vector kernel reads P, the bias and the RoPE table in 16-byte pieces
+  if (head_dim % 8 == 0 && ldp % 4 == 0 && split_stride % 4 == 0 && (uintptr_t)P % 16 == 0 &&
+      (bias == nullptr || (uintptr_t)bias % 16 == 0)) {
     const int items = ((n_heads + n_kv_heads) * (head_dim / 8) + n_kv_heads * head_dim / 4);
     const dim3 grid(m, (items + 2 * kThreads - 1) / (2 * kThreads));
     D2C_DISPATCH(dtype,

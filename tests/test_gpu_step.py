@@ -50,67 +50,105 @@ def _force(seq, st: O.SeqState):
     seq.c.n_masked = int(st.is_masked.sum())
 
 
-def _teacher_forced(B, dims, mdl, su, prm, n_steps, seed=0, check_free_run=True):
+def _rows_close(got, ref, rows, tol, what):
+    """Every row on its own: max over the rows of the per-row relative L2 error.  One wrong row among
+    hundreds fails here; it would vanish in a norm over the whole tensor."""
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    for r in rows:
+        e = rel_l2(got[r], ref[r])
+        assert e < tol, f"{what}: row {int(r)} rel-L2 {e:.3g} >= {tol}"
+
+
+def _teacher_forced(B, dims, mdl, su, prm, n_steps, seed=0, check_free_run=True, n_seqs=1, prompt_lens=None,
+                    max_batch=None, tunables=None):
+    """Teacher-forced comparison of d2c_step with the oracle for n_seqs independent sequences that go
+    through every d2c_step call together (max_batch of them share the projection launches).
+
+    Floats are compared row by row: final hidden rows, logits rows, the refreshed K/V rows S_t of every
+    layer (per row and layer), all within the dtype's tolerance; the cache rows outside S_t must keep the
+    bits they had before the step.  Index sets are checked bit-exactly by running the oracle's integer
+    selection on the GPU's own float arrays.  The direct comparison with the oracle's sets only runs while
+    the oracle's decision margins exceed 50 x the tolerance; in bf16 (tolerance 2e-2) that would need
+    relative margins above 1, which no score gap has, so there the sets are verified through the GPU's own
+    arrays only -- the float scores those sets are drawn from are themselves compared with the oracle's."""
     od = oracle_dims(dims, len(mdl["layers"]))
     tol = TOL[dims.dtype]
-    L = su.seq_len
-    ctx = B.Context(dims, mdl, L)
-    y0, m0 = W.initial_sequence(dims, su, seed)
-    st = O.new_state(od, y0, m0, su.prompt_len)
-    seq = B.Sequence_(ctx, y0, m0, su.prompt_len, trace=True, max_trace_rows=su.gen_len)
+    prompt_lens = prompt_lens or [su.prompt_len] * n_seqs
+    Ls = [P + su.gen_len for P in prompt_lens]
+    ctx = B.Context(dims, mdl, max(Ls), max_batch=max_batch or n_seqs, tunables=tunables)
     gp = _gpu_params(B, prm)
-    assert (seq.n_s, seq.n_rows, seq.n_masked) == (L, su.gen_len, su.gen_len)
+    sts, seqs = [], []
+    for b in range(n_seqs):
+        sub = W.DecodeSetup(prompt_lens[b], su.gen_len, su.block_len, su.n_unmask, su.k, su.p, su.sigma)
+        y0, m0 = W.initial_sequence(dims, sub, seed, seq=b)
+        sts.append(O.new_state(od, y0, m0, sub.prompt_len))
+        seqs.append(B.Sequence_(ctx, y0, m0, sub.prompt_len, trace=True, max_trace_rows=su.gen_len))
+        assert (seqs[b].n_s, seqs[b].n_rows, seqs[b].n_masked) == (Ls[b], su.gen_len, su.gen_len)
     free_running = check_free_run
     for t in range(n_steps):
-        if not st.is_masked.any():
+        if not any(st.is_masked.any() for st in sts):
             break
-        say(f"d2c_step teacher-forced t={t} m={len(st.S)} dtype={dims.dtype} d={dims.d_model} L={L}")
-        masked_before = st.is_masked.copy()
-        O.d2cache_step(od, mdl, prm, st)
-        ctx.d2c_step(gp, [seq])
-        tr = st.trace
-        S, m = tr["S"], len(tr["S"])
-        rows = tr["logit_rows"]
-        # --- floats
-        assert rel_l2(host(seq.hidden_out)[:m], tr["hidden"]) < tol, f"hidden t={t}"
-        if len(rows):
-            assert rel_l2(host(seq.logits_out)[: len(rows)], tr["logits"]) < tol, f"logits t={t}"
-        assert rel_l2(host(seq.k_cache), st.k_cache) < tol and rel_l2(host(seq.v_cache), st.v_cache) < tol, f"kv t={t}"
-        infl = host(seq.influence)
-        assert rel_l2(infl, tr["c"]) < tol and np.max(np.abs(infl - tr["c"])) < tol * max(1.0, tr["c"].max()), f"c t={t}"
-        conf_g, pred_g = host(seq.conf), seq.pred.cpu().numpy()
-        if len(rows):
-            np.testing.assert_allclose(conf_g[rows], st.conf[rows], rtol=max(tol, 1e-5) * 5, err_msg=f"conf t={t}")
-            lg = tr["logits"]
-            picked = lg[np.arange(len(rows)), pred_g[rows]]
-            assert np.all(lg.max(axis=1) - picked <= 4 * tol * np.abs(lg).max() + 1e-12), f"pred t={t}"
-            if dims.dtype == "f32":
-                np.testing.assert_array_equal(pred_g[rows], st.pred[rows])
-        g = _sets(B, seq)
-        assert g["block"] == tr["block"]
-        score_g = host(seq.score)
-        cand1 = np.array([i for i in range(*tr["block"]) if masked_before[i]], np.int64)
-        if len(cand1):
-            np.testing.assert_allclose(score_g[cand1], tr["score"][cand1], rtol=max(tol, 1e-5) * 5)
-        # --- index sets, integer-exact on the GPU's own float arrays
-        np.testing.assert_array_equal(g["mstar"], O.top_k_select(score_g, cand1, prm.k))
-        dec_ref = O.top_k_select(conf_g if prm.conf_decode else score_g, cand1, prm.n_unmask)
-        if prm.threshold > 0:
-            dec_ref = np.union1d(dec_ref, cand1[conf_g[cand1] > np.float32(prm.threshold)]).astype(np.int32)
-        np.testing.assert_array_equal(g["decode"], dec_ref)
-        cand2 = np.flatnonzero(~masked_before)
-        np.testing.assert_array_equal(g["u"], O.top_p_select(infl, cand2, prm.p))
-        np.testing.assert_array_equal(g["s_next"], np.union1d(np.union1d(g["mstar"], g["decode"]), g["u"]))
-        # --- the same sets against the oracle's, while its margins are wide
-        if free_running:
-            safe = (topk_margin(tr["score"], cand1, prm.k) > 50 * tol and
-                    topk_margin(tr["score"], cand1, prm.n_unmask) > 50 * tol and
-                    topp_margin(tr["c"], cand2, prm.p) > 50 * tol and prm.threshold == 0 and not prm.conf_decode)
-            if safe:
-                np.testing.assert_array_equal(g["mstar"], tr["mstar"])
-                np.testing.assert_array_equal(g["decode"], tr["decode"])
-                np.testing.assert_array_equal(g["u"], tr["u"])
-        _force(seq, st)
+        say(f"d2c_step teacher-forced t={t} m={[len(st.S) for st in sts]} dtype={dims.dtype} d={dims.d_model} L={Ls}")
+        before = []
+        for st, seq in zip(sts, seqs):
+            before.append((st.is_masked.copy(), host(seq.k_cache), host(seq.v_cache)))
+            if st.is_masked.any():
+                O.d2cache_step(od, mdl, prm, st)
+        ctx.d2c_step(gp, seqs)
+        for b, (st, seq) in enumerate(zip(sts, seqs)):
+            masked_before, k_prev, v_prev = before[b]
+            if not masked_before.any():
+                continue
+            L = Ls[b]
+            tr = st.trace
+            S, m = tr["S"], len(tr["S"])
+            rows = tr["logit_rows"]
+            # --- floats, row by row
+            _rows_close(host(seq.hidden_out)[:m], tr["hidden"], range(m), tol, f"hidden seq={b} t={t}")
+            if len(rows):
+                _rows_close(host(seq.logits_out)[: len(rows)], tr["logits"], range(len(rows)), tol, f"logits seq={b} t={t}")
+            k_now, v_now = host(seq.k_cache), host(seq.v_cache)
+            rest = np.setdiff1d(np.arange(L), S)
+            for l in range(od.n_layers):
+                _rows_close(k_now[l], st.k_cache[l], S, tol, f"K layer={l} seq={b} t={t}")
+                _rows_close(v_now[l], st.v_cache[l], S, tol, f"V layer={l} seq={b} t={t}")
+                np.testing.assert_array_equal(k_now[l][rest], k_prev[l][rest])     # reused rows: untouched bits
+                np.testing.assert_array_equal(v_now[l][rest], v_prev[l][rest])
+            infl = host(seq.influence)
+            assert rel_l2(infl, tr["c"]) < tol and np.max(np.abs(infl - tr["c"])) < tol * max(1.0, tr["c"].max()), f"c t={t}"
+            conf_g, pred_g = host(seq.conf), seq.pred.cpu().numpy()
+            if len(rows):
+                np.testing.assert_allclose(conf_g[rows], st.conf[rows], rtol=max(tol, 1e-5) * 5, err_msg=f"conf t={t}")
+                lg = tr["logits"]
+                picked = lg[np.arange(len(rows)), pred_g[rows]]
+                assert np.all(lg.max(axis=1) - picked <= 4 * tol * np.abs(lg).max() + 1e-12), f"pred t={t}"
+                if dims.dtype == "f32":
+                    np.testing.assert_array_equal(pred_g[rows], st.pred[rows])
+            g = _sets(B, seq)
+            assert g["block"] == tr["block"]
+            score_g = host(seq.score)
+            cand1 = np.array([i for i in range(*tr["block"]) if masked_before[i]], np.int64)
+            if len(cand1):
+                np.testing.assert_allclose(score_g[cand1], tr["score"][cand1], rtol=max(tol, 1e-5) * 5)
+            # --- index sets, integer-exact on the GPU's own float arrays
+            np.testing.assert_array_equal(g["mstar"], O.top_k_select(score_g, cand1, prm.k))
+            dec_ref = O.top_k_select(conf_g if prm.conf_decode else score_g, cand1, prm.n_unmask)
+            if prm.threshold > 0:
+                dec_ref = np.union1d(dec_ref, cand1[conf_g[cand1] > np.float32(prm.threshold)]).astype(np.int32)
+            np.testing.assert_array_equal(g["decode"], dec_ref)
+            cand2 = np.flatnonzero(~masked_before)
+            np.testing.assert_array_equal(g["u"], O.top_p_select(infl, cand2, prm.p))
+            np.testing.assert_array_equal(g["s_next"], np.union1d(np.union1d(g["mstar"], g["decode"]), g["u"]))
+            # --- the same sets against the oracle's, while its margins are wide (fp32 only in practice)
+            if free_running:
+                safe = (topk_margin(tr["score"], cand1, prm.k) > 50 * tol and
+                        topk_margin(tr["score"], cand1, prm.n_unmask) > 50 * tol and
+                        topp_margin(tr["c"], cand2, prm.p) > 50 * tol and prm.threshold == 0 and not prm.conf_decode)
+                if safe:
+                    np.testing.assert_array_equal(g["mstar"], tr["mstar"])
+                    np.testing.assert_array_equal(g["decode"], tr["decode"])
+                    np.testing.assert_array_equal(g["u"], tr["u"])
+            _force(seq, st)
     ctx.close()
 
 
@@ -227,11 +265,7 @@ def test_step_bf16_small_on_one_stream(B):
     wd = W.ModelDims(3, 512, 8, 2, 64, 1408, 2048, dtype="bf16")
     su = W.DecodeSetup(40, 24, 12, 1, k=6, p=0.3)
     mdl = W.model_weights(wd, 3)
-    B.d2c_set_tunable("side_stream", 0)
-    try:
-        _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=8)
-    finally:
-        B.d2c_set_tunable("side_stream", 1)
+    _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=8, tunables={"side_stream": 0})
 
 
 def test_step_bf16_many_rows_per_step(B):
@@ -321,19 +355,98 @@ def test_step_llada_shape_reduced_depth(B):
     _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=3)
 
 
-def test_step_parallel_decoding_and_short_rollout(B):
-    """Parallel decoding by confidence threshold (1 to 7 tokens per step here), confidence-only decoding
-    and a rollout over the first layer only, on the small fp32 model with wider weights (so that the
-    confidences of the masked positions spread around the threshold)."""
-    wd, su = W.DIMS["C1"], W.DecodeSetup(32, 48, 16, 1, k=8, p=0.5)
-    mdl = W.model_weights(wd, 1)
+def _spread_model(wd, seed):
+    """The small fp32 model with wider weights, so that the confidences of the masked positions spread
+    around a threshold and the attention has structure."""
+    mdl = W.model_weights(wd, seed)
     for name in ("tok_emb", "lm_head"):
         mdl[name] = mdl[name] * np.float32(16.0)
     for lw in mdl["layers"]:
         for name in ("wqkv", "wo", "w_gate_up", "w_down"):
             lw[name] = lw[name] * np.float32(4.0)
+    return mdl
+
+
+def test_step_parallel_decoding_by_threshold(B):
+    """Parallel decoding by confidence threshold alone (1 to several tokens per step)."""
+    wd, su = W.DIMS["C1"], W.DecodeSetup(32, 48, 16, 1, k=8, p=0.5)
+    _teacher_forced(B, wd, _spread_model(wd, 1), su, oracle_params(su, threshold=0.5), n_steps=su.gen_len)
+
+
+def test_step_confidence_only_decoding(B):
+    """The decode set ranked by the confidence alone; M* still by D(i) s^i."""
+    wd, su = W.DIMS["C1"], W.DecodeSetup(32, 48, 16, 1, k=8, p=0.5)
+    _teacher_forced(B, wd, _spread_model(wd, 1), su, oracle_params(su, conf_decode=1), n_steps=su.gen_len)
+
+
+@pytest.mark.parametrize("r", [1, 2, 5])
+def test_step_rollout_over_first_layers_f32(B, r):
+    """Rollout over the first r layers of a 3-layer fp32 model (r = 5 exceeds the depth: all layers)."""
+    wd, su = W.with_layers(W.DIMS["C1"], 3), W.DecodeSetup(32, 48, 16, 1, k=8, p=0.5)
+    _teacher_forced(B, wd, _spread_model(wd, 2), su, oracle_params(su, rollout_layers=r), n_steps=12)
+
+
+@pytest.mark.parametrize("regime", ["few_rows", "many_rows", "long_sequence"])
+def test_step_rollout_over_first_layers_bf16(B, regime):
+    """bf16, 4 layers, rollout over the first 2: the later layers run the attention kernel that keeps no
+    probability rows and skip the head average.  few_rows: the attention launch itself writes the per-head
+    rows (fewer than 96 selected rows, L <= 1024); many_rows: the LDS-tiled kernels; long_sequence: more
+    than 1024 positions with few rows per step."""
+    if regime == "few_rows":
+        wd = W.ModelDims(4, 512, 8, 2, 64, 1408, 2048, dtype="bf16")
+        su = W.DecodeSetup(40, 24, 12, 1, k=6, p=0.3)
+        steps = 10
+    elif regime == "many_rows":
+        wd = W.ModelDims(4, 512, 4, 4, 128, 1408, 2048, dtype="bf16")
+        su = W.DecodeSetup(160, 96, 96, 2, k=64, p=0.6)
+        steps = 4
+    else:
+        wd = W.ModelDims(4, 512, 8, 2, 64, 1024, 1024, dtype="bf16")
+        su = W.DecodeSetup(1040, 64, 32, 1, k=16, p=0.02)
+        steps = 3
+    mdl = W.model_weights(wd, 13)
+    _teacher_forced(B, wd, mdl, su, oracle_params(su, rollout_layers=2), n_steps=steps)
+
+
+def test_step_parallel_confidence_and_short_rollout_together(B):
+    """All three switches at once (the combination a parallel-decoding run with the lightweight rollout uses)."""
+    wd, su = W.DIMS["C1"], W.DecodeSetup(32, 48, 16, 1, k=8, p=0.5)
     prm = oracle_params(su, threshold=0.5, conf_decode=1, rollout_layers=1)
-    _teacher_forced(B, wd, mdl, su, prm, n_steps=su.gen_len)
+    _teacher_forced(B, wd, _spread_model(wd, 1), su, prm, n_steps=su.gen_len)
+
+
+def test_step_dream_shape_reduced_depth(B):
+    """Dream-7B geometry (28 query heads on 4 kv heads, d_model 3584, FFN 18944) at full width and full
+    vocabulary (152064), 2 of the 28 layers: step 0 (all 768 rows) and two d2Cache steps, teacher-forced."""
+    wd, su = W.with_layers(W.DIMS["C4"], 2), W.SETUP["C4"]
+    mdl = W.model_weights(wd, 0)
+    _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=3)
+
+
+def test_step_long_context_batch_regime(B):
+    """The long-context batch regime: two sequences with different prompts (2048 and 1984 tokens) and
+    1024 generated positions each, blocks of 64, two tokens unmasked per step, sigma 10 / k 32 / p 0.1,
+    projected together (max_batch = 2); 2 layers of 8 x 128 heads so that the CPU side stays within a
+    minute.  Step 0 over all ~3000 rows per sequence, then two d2Cache steps of a few hundred ragged rows
+    each (the LDS-tiled attention kernels at L ~ 3072, the rollout chain at that length)."""
+    wd = W.ModelDims(2, 1024, 8, 8, 128, 2816, 8192, dtype="bf16")
+    su = W.SETUP["C5"]
+    mdl = W.model_weights(wd, 21)
+    _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=3, n_seqs=2, prompt_lens=[2048, 1984], max_batch=2)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_step_with_qkv_bias(B, dtype):
+    """A model whose QKV projection has a bias (the Qwen2.5 / Dream geometry), grouped-query heads."""
+    if dtype == "f32":
+        wd = W.ModelDims(2, 256, 4, 2, 64, 688, 1024, dtype="f32")
+    else:
+        wd = W.ModelDims(2, 512, 8, 2, 64, 1408, 2048, dtype="bf16")
+    su = W.DecodeSetup(40, 24, 12, 1, k=6, p=0.3)
+    mdl = W.model_weights(wd, 17)
+    for l, lw in enumerate(mdl["layers"]):
+        lw["bqkv"] = W.hidden_rows(17, 1, wd.d_q + 2 * wd.d_kv, std=0.5, extra=100 + l)[0]
+    _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=6)
 
 
 @pytest.mark.parametrize("workload", ["C3", "C4", "C5"])
