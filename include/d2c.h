@@ -171,6 +171,24 @@ int d2c_select(d2c_ctx* ctx, const d2c_params* params,
                int32_t* s_next, int32_t* s_rows_next, int32_t* counts, float* score_out,
                void* stream);
 
+/* d2c_select for callers that cannot allocate device memory or hold a context: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and error codes as
+ * d2c_select, with the vocabulary size passed in place of the context.  The call allocates nothing (no
+ * hipMalloc / hipFree, no context, no workspace): the only scratch its kernels need -- Eq. 1's per-chunk
+ * (max, argmax, sum) triples -- lives in an array inside the library's device code, 192 KiB per GPU, held
+ * until the process ends.  Limits: n_rows <= D2C_STATIC_MAX_ROWS and L <= 4096, else D2C_ESHAPE.
+ * Every call on a GPU shares that GPU's one array (nothing in it has to be cleared between calls): calls
+ * that overlap in time on one GPU, on any streams, race; issue them one after the other.
+ * d2c_last_error(NULL) holds the text of its last error. */
+#define D2C_STATIC_MAX_ROWS 256
+int d2c_select_static(const d2c_params* params, int32_t vocab,
+                      const float* logits, const int32_t* logit_pos, int32_t n_rows,
+                      int32_t* tokens, uint8_t* is_masked, int32_t L, int32_t prompt_len,
+                      float* conf, int32_t* pred, const float* influence,
+                      int32_t* mstar, int32_t* u_set, int32_t* decode_idx,
+                      int32_t* s_next, int32_t* s_rows_next, int32_t* counts, float* score_out,
+                      void* stream);
+
 /* One transformer block on the m selected rows (Eq. 5).
  *   hidden [m, d_model] float, in/out (compact rows, row r is position idx[r]);
  *   idx (host copy idx_host is validated: ascending, distinct, in [0, L));

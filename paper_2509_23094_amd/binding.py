@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libd2c.so")
 
 D2C_OK, D2C_EINVAL, D2C_ENOMEM, D2C_EHIP, D2C_ESHAPE = 0, -1, -2, -3, -4
 D2C_F32, D2C_BF16 = 0, 1
+D2C_STATIC_MAX_ROWS = 256
 CNT_MSTAR, CNT_U, CNT_S, CNT_DECODE, CNT_NEXT_ROWS, CNT_MASKED, CNT_BLOCK_LO, CNT_BLOCK_HI, N_COUNTS = range(9)
 
 
@@ -61,7 +62,7 @@ class d2c_tunable(C.Structure):
 
 # include/d2c.h (the method's calls) and include/d2c_tools.h (timing, tunables, planner)
 EXPORTS = ["d2c_init", "d2c_destroy", "d2c_last_error", "d2c_seq_reset", "d2c_select", "d2c_refresh_layer",
-           "d2c_attention", "d2c_influence", "d2c_linear", "d2c_step", "d2c_workspace_bytes"]
+           "d2c_attention", "d2c_influence", "d2c_linear", "d2c_step", "d2c_workspace_bytes", "d2c_select_static"]
 TOOL_EXPORTS = ["d2c_profile_begin", "d2c_profile_end", "d2c_init_tuned", "d2c_ctx_set_tunable",
                 "d2c_plan_projection", "d2c_memory_info"]
 
@@ -79,6 +80,8 @@ def load_library() -> C.CDLL:
     lib.d2c_seq_reset.argtypes = [vp, C.POINTER(d2c_seq_state), vp]
     lib.d2c_select.argtypes = [vp, C.POINTER(d2c_params), vp, vp, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp,
                                vp, vp, vp, vp]
+    lib.d2c_select_static.argtypes = [C.POINTER(d2c_params), i32, vp, vp, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp,
+                                      vp, vp, vp, vp, vp, vp]
     lib.d2c_refresh_layer.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp]
     lib.d2c_attention.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, i32, vp, vp, vp]
     lib.d2c_influence.argtypes = [vp, vp, vp, i32, i32, vp, vp]
@@ -136,6 +139,18 @@ def make_params(sigma=10.0, k=32, p=0.1, block_len=32, n_unmask=1, cand_mode=0, 
                 rollout_layers=0) -> d2c_params:
     return d2c_params(float(sigma), int(k), float(p), int(block_len), int(n_unmask), int(cand_mode),
                       float(threshold), int(conf_decode), int(rollout_layers))
+
+
+def d2c_select_static(params: d2c_params, vocab: int, logits, logit_pos, n_rows, tokens, is_masked, L, prompt_len,
+                      conf, pred, influence, mstar, u_set, decode_idx, s_next, s_rows_next, counts,
+                      score_out=None) -> None:
+    """d2c_select without a context and without any allocation (scratch in a static device array)."""
+    rc = _lib.d2c_select_static(C.byref(params), int(vocab), _ptr(logits), _ptr(logit_pos), n_rows, _ptr(tokens),
+                                _ptr(is_masked), L, prompt_len, _ptr(conf), _ptr(pred), _ptr(influence), _ptr(mstar),
+                                _ptr(u_set), _ptr(decode_idx), _ptr(s_next), _ptr(s_rows_next), _ptr(counts),
+                                _ptr(score_out), _stream())
+    if rc != D2C_OK:
+        raise D2CError(rc, (_lib.d2c_last_error(None) or b"").decode())
 
 
 class Context:

@@ -6,6 +6,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -34,6 +35,13 @@ bool d2c::set_tunable(Tunables& t, const char* name, int value) {
   else return false;
   return true;
 }
+
+// ---- d2c_select_static: Eq. 1's per-chunk (max, argmax, sum) triples live in this file-scope device array
+// instead of a context's workspace, so the call needs no context and never allocates.  Each GPU holds its
+// own copy of the array at its own address; the address is looked up once per device.
+constexpr int kStaticMaxRows = D2C_STATIC_MAX_ROWS;
+constexpr size_t kStaticFloats = (size_t)kStaticMaxRows * 64 * 3;        // 64 = most chunks per vocabulary row
+static __device__ __align__(256) float scratch[kStaticFloats];
 
 struct d2c_ctx {
   d2c_dims dims{};
@@ -110,6 +118,31 @@ int fail(d2c_ctx* ctx, int code, const std::string& msg) {
   if (ctx) ctx->err = msg; else g_init_err = msg;
   return code;
 }
+
+constexpr int kStaticMaxDevices = 64;
+float* g_static_ptr[kStaticMaxDevices] = {};
+std::mutex g_static_mu;
+
+// Device address of this GPU's copy of `scratch` (the array's name is only a host-side handle).
+int static_scratch(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(nullptr, D2C_EHIP, std::string("hipGetDevice: ") + hipGetErrorString(e));
+  if (dev < 0 || dev >= kStaticMaxDevices) return fail(nullptr, D2C_ESHAPE, "device ordinal beyond the static table");
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return fail(nullptr, D2C_EHIP, std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e));
+    }
+    g_static_ptr[dev] = static_cast<float*>(p);
+  }
+  *out = g_static_ptr[dev];
+  return D2C_OK;
+}
+
 
 #define D2C_HIP(ctx, expr)                                                                  \
   do {                                                                                      \
@@ -557,6 +590,37 @@ int d2c_select(d2c_ctx* c, const d2c_params* p, const float* logits, const int32
                tokens, is_masked, L, prompt_len,
                conf, pred, influence, mstar, u_set, decode_idx, s_next, s_rows_next, counts, score_out};
   D2C_HIP(c, launch_select(a, st));
+  return D2C_OK;
+}
+
+int d2c_select_static(const d2c_params* p, int32_t vocab, const float* logits, const int32_t* logit_pos,
+                      int32_t n_rows, int32_t* tokens, uint8_t* is_masked, int32_t L, int32_t prompt_len, float* conf,
+                      int32_t* pred, const float* influence, int32_t* mstar, int32_t* u_set, int32_t* decode_idx,
+                      int32_t* s_next, int32_t* s_rows_next, int32_t* counts, float* score_out, void* stream) {
+  int rc = check_params(nullptr, p);
+  if (rc) return rc;
+  if (!tokens || !is_masked || !conf || !pred || !influence || !mstar || !u_set || !decode_idx || !s_next ||
+      !s_rows_next || !counts)
+    return fail(nullptr, D2C_EINVAL, "null buffer");
+  if (vocab <= 0) return fail(nullptr, D2C_EINVAL, "vocab must be positive");
+  if (n_rows < 0 || (n_rows > 0 && (!logits || !logit_pos))) return fail(nullptr, D2C_EINVAL, "logits / logit_pos missing");
+  if (n_rows > kStaticMaxRows)
+    return fail(nullptr, D2C_ESHAPE, "n_rows exceeds D2C_STATIC_MAX_ROWS (" + std::to_string(kStaticMaxRows) +
+                                         "): the static scratch array holds no more");
+  if (L <= 0 || L > select_max_len())
+    return fail(nullptr, D2C_ESHAPE, "L outside (0, " + std::to_string(select_max_len()) + "]");
+  if (prompt_len < 0 || prompt_len > L) return fail(nullptr, D2C_EINVAL, "prompt_len outside [0, L]");
+  if (confidence_scratch_floats(n_rows) > kStaticFloats) return fail(nullptr, D2C_ESHAPE, "scratch array too small");
+  float* sp = nullptr;
+  if ((rc = static_scratch(&sp))) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  // every (row, chunk) triple that the merge reads is written by the chunk kernel of this call: nothing in
+  // the array has to start at zero, whatever the last call left there
+  D2C_HIP(nullptr, launch_confidence(logits, logit_pos, nullptr, n_rows, vocab, conf, pred, sp, st));
+  SelectArgs a{p->sigma, p->k, p->p, p->block_len, p->n_unmask, p->cand_mode, p->threshold, p->conf_decode,
+               tokens, is_masked, L, prompt_len,
+               conf, pred, influence, mstar, u_set, decode_idx, s_next, s_rows_next, counts, score_out};
+  D2C_HIP(nullptr, launch_select(a, st));
   return D2C_OK;
 }
 
