@@ -38,8 +38,9 @@ int d2c_profile_end(d2c_ctx* ctx, double* ms, int64_t* launches, double* bytes);
  * "gemm_wide_min_rows" (that instantiation from this many rows on), "gemm_tall_chunk" (0/1: 129-192 bf16 rows
  * as one row chunk), "gemm_preshuffle" (0/1: pre-tiled weight copies; only at d2c_init_tuned), "gemm_rot";
  * attention: "attn_tiled_min_m" (bf16 attention switches to the LDS-tiled kernels from this many query rows
- * on), "attn_max_splits" (1..8, key-range splits of one attention launch), "attn_qt", "attn_target_wgs",
- * "attn_side_groups"; "side_stream" (0/1: whether d2c_step runs the head average and the rollout on a second
+ * on), "attn_max_splits" (1..8, key-range splits of one attention launch), "attn_qt", "attn_waves" (4, 8),
+ * "attn_target_wgs",
+ * "side_stream" (0/1: whether d2c_step runs the head average and the rollout on a second
  * stream). */
 typedef struct {
   const char* name;

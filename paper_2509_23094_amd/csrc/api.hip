@@ -23,13 +23,13 @@ bool d2c::set_tunable(Tunables& t, const char* name, int value) {
   else if (!strcmp(name, "gemm_wide_tiles")) t.gemm_wide_tiles = value;
   else if (!strcmp(name, "gemm_wide_min_rows")) t.gemm_wide_min_rows = value;
   else if (!strcmp(name, "gemm_tall_chunk")) t.gemm_tall_chunk = value;
-  else if (!strcmp(name, "attn_side_groups")) t.attn_side_groups = value;
   else if (!strcmp(name, "gemm_waves")) t.gemm_waves = (value == 8 || value == 4 || value == 6 || value == 10) ? value : 0;
   else if (!strcmp(name, "gemm_preshuffle")) t.gemm_preshuffle = value != 0;
   else if (!strcmp(name, "gemm_rot")) t.gemm_rot = value < 0 ? 0 : value;
   else if (!strcmp(name, "attn_tiled_min_m")) t.attn_tiled_min_m = value < 1 ? 1 : value;
   else if (!strcmp(name, "attn_max_splits")) t.attn_max_splits = std::max(1, std::min(8, value));
   else if (!strcmp(name, "attn_qt")) t.attn_qt = value == 1 ? 1 : value == 2 ? 2 : 0;
+  else if (!strcmp(name, "attn_waves")) t.attn_waves = value == 4 ? 4 : value == 8 ? 8 : 0;
   else if (!strcmp(name, "attn_target_wgs")) t.attn_target_wgs = std::max(1, value);
   else if (!strcmp(name, "side_stream")) t.side_stream = value != 0;
   else return false;
@@ -71,9 +71,8 @@ struct d2c_ctx {
   void* attn_o = nullptr;       // T [max_seq, d_q]
   void* act = nullptr;          // T [max_seq, F]
   float* lse = nullptr;         // [n_layers, H, max_seq]
-  float* attn_part = nullptr;   // partial outputs of an attention launch that splits the key range
-  size_t attn_part_floats = 0, avg_part_floats = 0;
-  float* avg_part = nullptr;    // per-head-group partials of the head average (used on the side stream)
+  float* attn_part = nullptr;   // scratch of the LDS-tiled attention: split partials, unnormalised probabilities, references
+  size_t attn_part_floats = 0;
   float* partial = nullptr;     // split partials of the current projection
   size_t partial_floats = 0;
   float* roll = nullptr;        // d2c_refresh_layer: the rollout block after the layer, [max_seq, max_seq]
@@ -263,15 +262,20 @@ int layer_impl(d2c_ctx* c, int layer, float* hidden, const Seg* segs, int n_seg,
                                       dq + 2 * dkv, c->bqkv.empty() ? nullptr : c->bqkv[layer], g.idx, g.m,
                                       D.n_heads, D.n_kv_heads, D.head_dim, c->rope_cos, c->rope_sin, qb, g.k_cache,
                                       g.v_cache, st));
+    // many rows: the LDS-tiled kernels write the head average themselves, on this stream, right behind the forward
+    const bool tiled = attention_is_tiled(c->tun, dt, g.m);
     D2C_TIMED(c, st, D2C_PROF_ATTENTION, 2.0 * g.L * dkv * ts,
               launch_attention_fwd(c->tun, dt, qb, g.k_cache, g.v_cache, g.m, g.L, D.n_heads, D.n_kv_heads, D.head_dim,
                                    (char*)c->attn_o + (size_t)g.off * dq * ts, lse + (size_t)D.n_heads * g.off,
-                                   c->attn_part, c->attn_part_floats, st, g.probs));
+                                   c->attn_part, c->attn_part_floats, st, g.probs, tiled ? g.abar : nullptr));
   }
-  bool any_abar = false;
-  for (int b = 0; b < n_seg; ++b) any_abar = any_abar || (segs[b].m > 0 && segs[b].abar);
-  if (record_fwd && !any_abar && side != st) D2C_HIP(c, hipEventRecord(c->fwd_done[layer], st));
-  if (any_abar) {
+  // what is left for the second stream: the second pass of the few-row kernels and the rollout update
+  bool any_side = false;
+  for (int b = 0; b < n_seg; ++b)
+    any_side = any_side || (segs[b].m > 0 && segs[b].abar &&
+                            (!attention_is_tiled(c->tun, dt, segs[b].m) || segs[b].roll_out));
+  if (record_fwd && !any_side && side != st) D2C_HIP(c, hipEventRecord(c->fwd_done[layer], st));
+  if (any_side) {
     if (side != st) {
       D2C_HIP(c, hipEventRecord(c->fwd_done[layer], st));
       D2C_HIP(c, hipStreamWaitEvent(side, c->fwd_done[layer], 0));
@@ -279,10 +283,10 @@ int layer_impl(d2c_ctx* c, int layer, float* hidden, const Seg* segs, int n_seg,
     for (int b = 0; b < n_seg; ++b) {
       const Seg& g = segs[b];
       if (g.m <= 0 || !g.abar) continue;
-      D2C_TIMED(c, side, D2C_PROF_ATTN_AVG, 0.0,
-                launch_attention_avg(c->tun, dt, q + (size_t)g.off * dq * ts, g.k_cache, lse + (size_t)D.n_heads * g.off, g.m,
-                                     g.L, D.n_heads, D.n_kv_heads, D.head_dim, g.abar, c->avg_part,
-                                     c->avg_part_floats, side, /*one_group=*/side != st));
+      if (!attention_is_tiled(c->tun, dt, g.m))
+        D2C_TIMED(c, side, D2C_PROF_ATTN_AVG, 0.0,
+                  launch_attention_avg(c->tun, dt, q + (size_t)g.off * dq * ts, g.k_cache, lse + (size_t)D.n_heads * g.off,
+                                       g.m, g.L, D.n_heads, D.n_kv_heads, D.head_dim, g.abar, side));
       if (g.roll_out)
         D2C_TIMED(c, side, D2C_PROF_ROLLOUT, 0.0,
                   launch_rollout(g.abar, g.roll_in, g.roll_out, g.idx, g.m, g.L, layer == 0, side));
@@ -330,11 +334,11 @@ int check_params(d2c_ctx* c, const d2c_params* p) {
 
 // Floats of split partials, attention partials and head-average partials that the launch plans can ask for
 // under tunables t, over every row count and sequence length the context admits.
-struct WsNeeds { size_t partial, attn_part, avg_part; };
+struct WsNeeds { size_t partial, attn_part; };
 WsNeeds ws_needs(const d2c_dims& D, size_t max_rows, const Tunables& t) {
   const int dq = D.n_heads * D.head_dim, dkv = D.n_kv_heads * D.head_dim;
   const int shapes[4][2] = {{dq + 2 * dkv, D.d_model}, {D.d_model, dq}, {2 * D.d_ffn, D.d_model}, {D.d_model, D.d_ffn}};
-  WsNeeds n{0, 0, 0};
+  WsNeeds n{0, 0};
   for (int m = 1; m <= (int)max_rows; ++m)
     for (auto& s : shapes) {
       // up to 128 rows leave room for the largest split count; beyond that the planner's choice is taken
@@ -342,7 +346,6 @@ WsNeeds ws_needs(const d2c_dims& D, size_t max_rows, const Tunables& t) {
       n.partial = std::max(n.partial, (size_t)(m <= 128 ? 8 : pl.splits) * m * s[0]);
     }
   n.attn_part = attention_scratch_floats(t, D.dtype, D.max_seq, D.max_seq, D.n_heads, D.head_dim);
-  n.avg_part = attention_avg_scratch_floats(t, D.dtype, D.max_seq, D.max_seq, D.n_heads);
   return n;
 }
 
@@ -405,7 +408,6 @@ int d2c_init_tuned(const d2c_dims* dims, const d2c_weights* w, const d2c_tunable
   c->partial_floats = pf;
   c->head_rows = (int)std::min<size_t>(Lm, 256);
   c->attn_part_floats = need.attn_part;
-  c->avg_part_floats = need.avg_part;
   const int64_t ws0 = c->ws_bytes;
   if ((rc = ws_alloc(c, &c->roll, Lm * Lm * 4)) ||
       (rc = ws_alloc(c, &c->abar_all, (size_t)c->max_batch * D.n_layers * Lm * Lm * 4)))
@@ -416,13 +418,12 @@ int d2c_init_tuned(const d2c_dims* dims, const d2c_weights* w, const d2c_tunable
       (rc = ws_alloc(c, &c->chain_g, (size_t)D.n_layers * Lm * Lm * 4)))
     return bail(rc);
   c->rollout_bytes = c->ws_bytes - ws0;
-  c->attn_scratch_bytes = (int64_t)(std::max<size_t>(1, c->attn_part_floats) + std::max<size_t>(1, c->avg_part_floats)) * 4;
+  c->attn_scratch_bytes = (int64_t)std::max<size_t>(1, c->attn_part_floats) * 4;
   if ((rc = ws_alloc(c, &c->hidden, Lr * d * 4)) || (rc = ws_alloc(c, &c->a_norm, Lr * d * ts)) ||
       (rc = ws_alloc(c, &c->q, (size_t)D.n_layers * Lr * dq * ts)) || (rc = ws_alloc(c, &c->attn_o, Lr * dq * ts)) ||
       (rc = ws_alloc(c, &c->act, Lr * F * ts)) ||
       (rc = ws_alloc(c, &c->lse, (size_t)D.n_layers * D.n_heads * Lr * 4)) ||
       (rc = ws_alloc(c, &c->attn_part, std::max<size_t>(1, c->attn_part_floats) * 4)) ||
-      (rc = ws_alloc(c, &c->avg_part, std::max<size_t>(1, c->avg_part_floats) * 4)) ||
       (rc = ws_alloc(c, &c->partial, pf * 4)) ||
       (rc = ws_alloc(c, &c->head_a, (size_t)c->head_rows * d * ts)) ||
       (rc = ws_alloc(c, &c->logits, (size_t)c->head_rows * D.vocab * 4)) ||
@@ -512,7 +513,7 @@ int d2c_ctx_set_tunable(d2c_ctx* c, const char* name, int32_t value) {
   if (!set_tunable(t, name, value)) return fail(c, D2C_EINVAL, std::string("unknown tunable ") + name);
   // the workspace was sized for the launch shapes of the tunables given at init: a change that asks for more is refused
   const WsNeeds need = ws_needs(c->dims, c->max_rows, t);
-  if (need.partial > c->partial_floats || need.attn_part > c->attn_part_floats || need.avg_part > c->avg_part_floats)
+  if (need.partial > c->partial_floats || need.attn_part > c->attn_part_floats)
     return fail(c, D2C_ESHAPE, std::string("tunable ") + name + " needs more workspace than the context holds: pass it to d2c_init_tuned");
   c->tun = t;
   return D2C_OK;
@@ -657,13 +658,14 @@ int d2c_attention(d2c_ctx* c, const void* q, const int32_t* idx, int32_t m, cons
   if (new_k) {
     D2C_HIP(c, launch_scatter_rows(D.dtype, new_k, k_cache, new_v, v_cache, idx, m, d_kv(c), st));
   }
+  const bool tiled = attention_is_tiled(c->tun, D.dtype, m);
   D2C_TIMED(c, st, D2C_PROF_ATTENTION, 2.0 * L * d_kv(c) * tsize(c),
             launch_attention_fwd(c->tun, D.dtype, q, k_cache, v_cache, m, L, D.n_heads, D.n_kv_heads, D.head_dim, out, c->lse,
-                                 c->attn_part, c->attn_part_floats, st));
-  if (attn_avg)
+                                 c->attn_part, c->attn_part_floats, st, nullptr, tiled ? attn_avg : nullptr));
+  if (attn_avg && !tiled)
     D2C_TIMED(c, st, D2C_PROF_ATTN_AVG, 0.0,
               launch_attention_avg(c->tun, D.dtype, q, k_cache, c->lse, m, L, D.n_heads, D.n_kv_heads, D.head_dim, attn_avg,
-                                   c->avg_part, c->avg_part_floats, st));
+                                   st));
   return D2C_OK;
 }
 

@@ -509,16 +509,19 @@ size_t attention_scratch_floats(const Tunables& t, int dtype, int max_m, int max
   return dtype == kBF16 ? attention_tiled_scratch_floats(t, max_m, max_L, n_heads, head_dim) : 0;
 }
 
+bool attention_is_tiled(const Tunables& t, int dtype, int m) { return dtype == kBF16 && m >= t.attn_tiled_min_m; }
+
 hipError_t launch_attention_fwd(const Tunables& t, int dtype, const void* q, const void* k_cache, const void* v_cache, int m, int L,
                                 int n_heads, int n_kv_heads, int head_dim, void* out, float* lse, float* scratch,
-                                size_t scratch_floats, hipStream_t st, float* probs) {
+                                size_t scratch_floats, hipStream_t st, float* probs, float* tiled_avg) {
   if (m <= 0) return hipSuccess;
   if (L <= 0 || n_heads % n_kv_heads) return hipErrorInvalidValue;
   if (probs && !attention_fwd_emits_probs(t, dtype, m, L)) return hipErrorInvalidValue;
+  if (attention_is_tiled(t, dtype, m))
+    return launch_attention_tiled(t, q, k_cache, v_cache, m, L, n_heads, n_kv_heads, head_dim, out, lse, tiled_avg,
+                                  scratch, scratch_floats, st);
+  if (tiled_avg) return hipErrorInvalidValue;
   if (dtype == kBF16) {
-    if (m >= t.attn_tiled_min_m)
-      return launch_attention_tiled_fwd(t, q, k_cache, v_cache, m, L, n_heads, n_kv_heads, head_dim, out, lse, scratch,
-                                        scratch_floats, st);
     if (head_dim == 128)
       return launch_fwd_bf16<128>(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, probs, st);
     if (head_dim == 64) return launch_fwd_bf16<64>(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, probs, st);
@@ -532,19 +535,11 @@ hipError_t launch_attention_fwd(const Tunables& t, int dtype, const void* q, con
   return hipGetLastError();
 }
 
-size_t attention_avg_scratch_floats(const Tunables& t, int dtype, int max_m, int max_L, int n_heads) {
-  return dtype == kBF16 ? attention_tiled_avg_scratch_floats(t, max_m, max_L, n_heads) : 0;
-}
-
 hipError_t launch_attention_avg(const Tunables& t, int dtype, const void* q, const void* k_cache, const float* lse, int m, int L,
-                                int n_heads, int n_kv_heads, int head_dim, float* attn_avg, float* scratch,
-                                size_t scratch_floats, hipStream_t st, bool one_group) {
+                                int n_heads, int n_kv_heads, int head_dim, float* attn_avg, hipStream_t st) {
   if (m <= 0) return hipSuccess;
-  if (L <= 0 || n_heads % n_kv_heads) return hipErrorInvalidValue;
+  if (L <= 0 || n_heads % n_kv_heads || attention_is_tiled(t, dtype, m)) return hipErrorInvalidValue;
   if (dtype == kBF16) {
-    if (m >= t.attn_tiled_min_m)
-      return launch_attention_tiled_avg(t, q, k_cache, lse, m, L, n_heads, n_kv_heads, head_dim, attn_avg, scratch,
-                                        scratch_floats, st, one_group);
     if (head_dim == 128) return launch_avg_bf16<128>(q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, st);
     if (head_dim == 64) return launch_avg_bf16<64>(q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, st);
     return hipErrorInvalidValue;

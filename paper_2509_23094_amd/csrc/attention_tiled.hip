@@ -20,6 +20,7 @@
 //             block of each head staged through LDS; exp(s - lse) accumulates in registers.
 #include <algorithm>
 #include <cmath>
+#include <type_traits>
 
 #include "common.h"
 #include "internal.h"
@@ -29,9 +30,13 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kBlockKeys = 64;
+// rows of the unnormalised probabilities are padded by one block: the pitch between heads and rows is then no
+// power of two (the head average reads the same piece of every head at once)
+constexpr int kPtildePad = 64;
 
-__device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
-__device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
+// low halves of (a, b) / high halves of (a, b) in one register: one byte-permute instruction each
+__device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
+__device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
 // two floats -> one register of two bf16 (round to nearest even): a single packed conversion
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -56,16 +61,31 @@ __device__ __forceinline__ TileId tile_of(int bid, int q_blocks, int n_heads, in
   return t;
 }
 
-template <int DH, int QT>
-__global__ __launch_bounds__(kThreads) void attn_tiled_fwd_kernel(
+// EMIT: the kernel also writes what the head average needs, so that no second pass over Q and K is run:
+// the unnormalised probabilities of every block exactly as they enter the matrix cores (bf16,
+// ptilde [H, m, Lp], Lp = L rounded up to whole blocks; inside a block of 64 keys the values of a row sit in
+// operand order: 16-byte piece (ks, g) holds keys 32ks + 4g .. +3, then 32ks + 16 + 4g .. +3) and the base-2
+// reference each block was taken against (refblk [H, blocks, m]).  The head-average kernel turns them into normalised rows once the rows'
+// log-sum-exp is known: p = ptilde * 2^(refblk - lse2).
+//
+// WAVES = 4 or 8 waves per workgroup, each owning 16*QT queries; with 8 waves two waves share a SIMD, so that
+// one wave's matrix-core phase runs beside the other's vector phase (a single wave runs its phases one after
+// the other), and a K/V block staged once serves twice as many queries.
+template <int DH, int QT, int WAVES, bool EMIT>
+__global__ __launch_bounds__(WAVES * 64) void attn_tiled_fwd_kernel(
     const bf16* __restrict__ q, const bf16* __restrict__ k_cache, const bf16* __restrict__ v_cache, int m, int L,
     int n_heads, int n_kv_heads, float scale, int keys_per_split, int n_splits, int q_blocks,
-    bf16* __restrict__ out, float* __restrict__ lse, float* __restrict__ o_part, float* __restrict__ ml_part) {
+    bf16* __restrict__ out, float* __restrict__ lse, float* __restrict__ o_part, float* __restrict__ ml_part,
+    bf16* __restrict__ ptilde, float* __restrict__ refblk) {
+  static_assert(WAVES == 4 || WAVES == 8, "4 or 8 waves");
   constexpr int NS = DH / 32;            // contraction steps of K Q^T
   constexpr int ND = DH / 16;            // head-dim tiles of O^T
   constexpr int NB = DH / 64;            // 64-wide head-dim blocks (one V staging unit covers 64)
+  constexpr int WH = WAVES / 4;          // waves that share the staging of one key tile
+  constexpr int KF = NS / WH;            // K fragments a lane stages per block
+  constexpr int VA = 2 / WH;             // 16-key tiles of its V unit a lane stages
   __shared__ u32x4 k_lds[2][4 * NS * 64];      // [key tile a][step s][lane]
-  __shared__ u32x4 v_lds[2][ND * 2 * 64];      // [head-dim tile][32-key step][lane]
+  __shared__ u32x4 v_lds[2][ND * 2 * 64];      // [head-dim tile][32-key step][slot]; slot = lane ^ (tile & 3)
 
   const TileId id = tile_of(blockIdx.x, q_blocks, n_heads, n_splits);
   if (!id.valid) return;
@@ -77,10 +97,12 @@ __global__ __launch_bounds__(kThreads) void attn_tiled_fwd_kernel(
   const size_t kv_pitch = (size_t)n_kv_heads * DH;
   const bf16* kbase = k_cache + (size_t)kvh * DH;
   const bf16* vbase = v_cache + (size_t)kvh * DH;
-  const int q0 = id.qb * (64 * QT) + wave * (16 * QT);
+  const int q0 = id.qb * (16 * QT * WAVES) + wave * (16 * QT);
   const int key_lo = id.split * keys_per_split;
   const int key_hi = min(L, key_lo + keys_per_split);
   const int n_blocks = (key_hi - key_lo + kBlockKeys - 1) / kBlockKeys;      // >= 1 by the launch plan
+  const int n_blk_total = (L + kBlockKeys - 1) / kBlockKeys;
+  const int Lp = n_blk_total * kBlockKeys + kPtildePad;                      // row pitch of ptilde
 
   // this wave's queries as B operands of S^T = K Q^T (rows past m repeat row m-1 and are not stored)
   Frag<bf16> qf[QT][NS];
@@ -93,57 +115,68 @@ __global__ __launch_bounds__(kThreads) void attn_tiled_fwd_kernel(
   }
 
   // staging registers of the K/V block on its way from global memory to LDS: requested at the top of an
-  // iteration, stored behind its arithmetic.  Wave w brings key tile w of K (its NS fragments) and one
-  // 8-key x 4-value unit of V per lane (unit = 32-key step ks, 64-wide block b).
+  // iteration, stored behind its arithmetic.  Key tile kt = wave % 4 of K: its NS fragments (with 8 waves,
+  // wave / 4 picks which half of them); of V one 8-key x 4-value unit per lane (unit = 32-key step ks,
+  // 64-wide block b; with 8 waves, wave / 4 picks which 16-key tile of the unit).
   struct Stage {
-    u32x4 k[NS];
-    u32x2 v[2][4];
+    u32x4 k[KF];
+    u32x2 v[VA][4];
   };
   Stage stg;
-  const int v_b = wave % NB, v_ks = wave / NB;          // v_ks < 2 only for the waves that stage V
-  const bool stages_v = NB == 2 || v_ks < 2;            // with two 64-wide blocks all four waves stage V
+  const int kt = wave & 3, wh = wave >> 2;
+  const int v_b = kt % NB, v_ks = kt / NB;              // v_ks < 2 only for the waves that stage V
+  const bool stages_v = NB == 2 || v_ks < 2;            // with two 64-wide blocks every wave stages V
   const int last_block = n_blocks - 1;
-  // Row addresses: a block that lies wholly inside [0, L) uses per-lane pointers fixed at launch plus a
-  // uniform block offset; only a ragged last block pays for clamping every row to L-1.
-  const bf16* const kfast = kbase + (size_t)(key_lo + wave * 16 + r) * kv_pitch + g * 8;
-  const bf16* const vfast = vbase + (size_t)(key_lo + 2 * v_ks * 16 + 4 * g) * kv_pitch + v_b * 64 + 4 * r;
+  // Row addresses: a block that lies wholly inside [0, L) uses per-lane byte offsets fixed at launch on top
+  // of a uniform block base; only a ragged last block pays for clamping every row to L-1.
+  const unsigned koff = (unsigned)(((size_t)(kt * 16 + r) * kv_pitch + g * 8 + wh * KF * 32) * sizeof(bf16));
+  const unsigned voff =
+      (unsigned)(((size_t)((2 * v_ks + wh * VA) * 16 + 4 * g) * kv_pitch + v_b * 64 + 4 * r) * sizeof(bf16));
+  const unsigned vrow_bytes = (unsigned)(kv_pitch * sizeof(bf16));
   auto load_block = [&](Stage& sg, int blk_req) {       // past the end: the last block again, never used
     const int blk = min(blk_req, last_block);
     const int key0 = key_lo + blk * kBlockKeys;
     if (key0 + kBlockKeys <= L) {
-      const size_t boff = (size_t)blk * kBlockKeys * kv_pitch;
+      const char* kblk = reinterpret_cast<const char*>(kbase + (size_t)key0 * kv_pitch);     // uniform
+      const char* vblk = reinterpret_cast<const char*>(vbase + (size_t)key0 * kv_pitch);
 #pragma unroll
-      for (int s = 0; s < NS; ++s) sg.k[s] = ld16(kfast + boff + s * 32);
+      for (int s = 0; s < KF; ++s) sg.k[s] = ld16(kblk + koff + s * 64);
       if (stages_v) {
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < VA; ++a)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) sg.v[a][e] = ld8(vfast + boff + (size_t)(a * 16 + e) * kv_pitch);
+          for (int e = 0; e < 4; ++e) sg.v[a][e] = ld8(vblk + voff + (unsigned)(a * 16 + e) * vrow_bytes);
       }
     } else {
-      const int key = min(key0 + wave * 16 + r, L - 1);
-      const bf16* krow = kbase + (size_t)key * kv_pitch + g * 8;
+      const int key = min(key0 + kt * 16 + r, L - 1);
+      const bf16* krow = kbase + (size_t)key * kv_pitch + g * 8 + wh * KF * 32;
 #pragma unroll
-      for (int s = 0; s < NS; ++s) sg.k[s] = ld16(krow + s * 32);
+      for (int s = 0; s < KF; ++s) sg.k[s] = ld16(krow + s * 32);
       if (stages_v) {
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < VA; ++a)
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const int vkey = min(key0 + (2 * v_ks + a) * 16 + 4 * g + e, L - 1);
+            const int vkey = min(key0 + (2 * v_ks + wh * VA + a) * 16 + 4 * g + e, L - 1);
             sg.v[a][e] = ld8(vbase + (size_t)vkey * kv_pitch + v_b * 64 + 4 * r);
           }
       }
     }
   };
+  // Slots of V in LDS.  The value of head-dim index b*64 + 4r + i lives in head-dim tile dt = 4b + r/4 at row
+  // 4(r%4) + i; a fragment's 8 keys are lane group g's 4 keys of tile 2ks, then of tile 2ks+1 (the order P is
+  // packed in).  Reader lane l of tile dt reads slot l ^ (dt & 3): the same 64 slots, so reads stay
+  // conflict-free, while the 64 writers of one store instruction (16 values of r for each g) now spread over
+  // all banks instead of piling 16 deep on a quarter of them.
+  const int v_dt = v_b * 4 + (r >> 2);
   auto store_block = [&](const Stage& sg, int buf) {
 #pragma unroll
-    for (int s = 0; s < NS; ++s) k_lds[buf][(wave * NS + s) * 64 + lane] = sg.k[s];
+    for (int s = 0; s < KF; ++s) k_lds[buf][(kt * NS + wh * KF + s) * 64 + lane] = sg.k[s];
     if (stages_v) {
       // 4x4 transposes: op[a][i] = keys 4g..4g+3 of tile 2ks+a for head-dim value 4r+i of block b
-      u32x2 op[2][4];
+      u32x2 op[VA][4];
 #pragma unroll
-      for (int a = 0; a < 2; ++a) {
+      for (int a = 0; a < VA; ++a) {
         op[a][0] = u32x2{pack_lo(sg.v[a][0].x, sg.v[a][1].x), pack_lo(sg.v[a][2].x, sg.v[a][3].x)};
         op[a][1] = u32x2{pack_hi(sg.v[a][0].x, sg.v[a][1].x), pack_hi(sg.v[a][2].x, sg.v[a][3].x)};
         op[a][2] = u32x2{pack_lo(sg.v[a][0].y, sg.v[a][1].y), pack_lo(sg.v[a][2].y, sg.v[a][3].y)};
@@ -151,22 +184,20 @@ __global__ __launch_bounds__(kThreads) void attn_tiled_fwd_kernel(
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        // head-dim value b*64 + 4r + i lives in tile dt at row 4(r%4)+i; the fragment's 8 keys are
-        // this lane group's 4 keys of tile 2ks, then of tile 2ks+1: the order P is packed in below
-        const int dtile = v_b * 4 + (r >> 2), drow = 4 * (r & 3) + i;
-        v_lds[buf][(dtile * 2 + v_ks) * 64 + g * 16 + drow] = u32x4{op[0][i].x, op[0][i].y, op[1][i].x, op[1][i].y};
+        const int slot = (g * 16 + 4 * (r & 3) + i) ^ (r >> 2);
+        u32x4* dst = &v_lds[buf][(v_dt * 2 + v_ks) * 64 + slot];
+        if constexpr (VA == 2) *dst = u32x4{op[0][i].x, op[0][i].y, op[1][i].x, op[1][i].y};
+        else reinterpret_cast<u32x2*>(dst)[wh] = op[0][i];
       }
     }
   };
 
   // Online softmax in the base-2 domain: p = 2^(s*c - ref) with c = scale*log2(e).  ref is a per-row
-  // reference, not necessarily the running maximum: it is only raised (and O, l rescaled) when a block's
-  // maximum exceeds it by more than kRaise, so p stays below 2^kRaise.  The result is the same softmax
-  // (shift invariance); the decision depends on the data only.  The raise is rare after the first block,
-  // and it is the only vector arithmetic on the O accumulators: it lives OUTSIDE the hot loop (the loop
-  // leaves through a break, the raise is applied, the block is finished, the loop is entered again), so
-  // inside the hot loop the accumulators are touched by matrix-core instructions only and never have to
-  // be copied between the accumulator and the vector register files.
+  // reference, not necessarily the running maximum: it is only raised (and O, l rescaled) when a score
+  // exceeds it by more than kRaise, so p stays below 2^kRaise.  The result is the same softmax (shift
+  // invariance); the decision depends on the data only.  Every lane checks its own 16 scores of a row
+  // against the row's reference; only when some lane of the wave finds one too large do the four lanes that
+  // share a row exchange their maxima and raise the reference (rare after the first block).
   constexpr float kRaise = 8.f;
   const float c2 = scale * 1.44269504088896341f;
   float ref[QT], l_run[QT];
@@ -178,30 +209,30 @@ __global__ __launch_bounds__(kThreads) void attn_tiled_fwd_kernel(
 #pragma unroll
     for (int d = 0; d < ND; ++d) acc[d][t] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
-  constexpr int FB = QT == 1 ? 8 : 16;         // LDS fragments read per batch (one latency per batch)
+  constexpr int FB = 8;                        // LDS fragments read per batch (one latency per batch)
   f32x4 st[4][QT];
-  float tmax2[QT];
+  const int vlane[4] = {lane, lane ^ 1, lane ^ 2, lane ^ 3};
 
-  // scores of block blk (S^T = K Q^T, masked past key_hi) and their scaled row maxima; returns whether any
-  // row of the wave needs its reference raised
-  auto scores = [&](int blk) -> bool {
+  auto block = [&](int blk) {
     const int buf = blk & 1;
     const int key0 = key_lo + blk * kBlockKeys;
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-      for (int t = 0; t < QT; ++t) st[a][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // ---- scores S^T = K Q^T; the first step of every tile starts from a zero accumulator operand
 #pragma unroll
     for (int b0 = 0; b0 < 4 * NS; b0 += FB) {
       Frag<bf16> kf[FB];
 #pragma unroll
       for (int i = 0; i < FB; ++i) kf[i].raw = k_lds[buf][(b0 + i) * 64 + lane];
-      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < FB; ++i)
 #pragma unroll
-        for (int t = 0; t < QT; ++t) mfma16(st[(b0 + i) / NS][t], kf[i], qf[t][(b0 + i) % NS]);
-      __builtin_amdgcn_sched_barrier(0);
+        for (int t = 0; t < QT; ++t) {
+          if ((b0 + i) % NS == 0)
+            st[(b0 + i) / NS][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                __builtin_bit_cast(bf16x8, kf[i].raw), __builtin_bit_cast(bf16x8, qf[t][0].raw),
+                f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+          else
+            mfma16(st[(b0 + i) / NS][t], kf[i], qf[t][(b0 + i) % NS]);
+        }
     }
     if (key0 + kBlockKeys > key_hi) {    // ragged last block of the range: keys past the end score -inf
 #pragma unroll
@@ -213,24 +244,31 @@ __global__ __launch_bounds__(kThreads) void attn_tiled_fwd_kernel(
             for (int t = 0; t < QT; ++t) st[a][t][j] = -INFINITY;
           }
     }
+    // ---- this lane's maxima against the rows' references
+    float tmax[QT];
     bool need = false;
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
-      float tmax = fmaxf(fmaxf(st[0][t][0], st[0][t][1]), fmaxf(st[0][t][2], st[0][t][3]));
+      tmax[t] = fmaxf(fmaxf(st[0][t][0], st[0][t][1]), fmaxf(st[0][t][2], st[0][t][3]));
 #pragma unroll
       for (int a = 1; a < 4; ++a)
-        tmax = fmaxf(tmax, fmaxf(fmaxf(st[a][t][0], st[a][t][1]), fmaxf(st[a][t][2], st[a][t][3])));
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 16, kWave));
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
-      tmax2[t] = tmax * c2;                            // finite: every block holds at least one key
-      need = need || tmax2[t] > ref[t] + kRaise;
+        tmax[t] = fmaxf(tmax[t], fmaxf(fmaxf(st[a][t][0], st[a][t][1]), fmaxf(st[a][t][2], st[a][t][3])));
+      need = need || tmax[t] * c2 > ref[t] + kRaise;
     }
-    return __builtin_amdgcn_ballot_w64(need) != 0;
-  };
-  // probabilities of the block against the current references, O^T += V^T P^T, then the block that was
-  // requested at the top of the iteration goes to the other LDS buffer
-  auto finish = [&](int blk) {
-    const int buf = blk & 1;
+    if (__builtin_amdgcn_ballot_w64(need) != 0) {
+#pragma unroll
+      for (int t = 0; t < QT; ++t) {
+        float rmax = fmaxf(tmax[t], __shfl_xor(tmax[t], 16, kWave));
+        rmax = fmaxf(rmax, __shfl_xor(rmax, 32, kWave)) * c2;       // the row's maximum; -inf only if it has no key yet
+        const float ref_new = rmax > ref[t] + kRaise ? rmax : ref[t];
+        const float alpha = ref_new == ref[t] ? 1.f : __builtin_amdgcn_exp2f(ref[t] - ref_new);   // 0 on the first block
+        l_run[t] *= alpha;
+#pragma unroll
+        for (int d = 0; d < ND; ++d) acc[d][t] *= alpha;
+        ref[t] = ref_new;
+      }
+    }
+    // ---- probabilities against the references, packed as the B operand of O^T += V^T P^T
     Frag<bf16> pf[2][QT];
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
@@ -250,48 +288,41 @@ __global__ __launch_bounds__(kThreads) void attn_tiled_fwd_kernel(
         pf[ks][t].raw = u32x4{pack_bf16(x[2 * ks][0], x[2 * ks][1]), pack_bf16(x[2 * ks][2], x[2 * ks][3]),
                               pack_bf16(x[2 * ks + 1][0], x[2 * ks + 1][1]),
                               pack_bf16(x[2 * ks + 1][2], x[2 * ks + 1][3])};
+      if constexpr (EMIT) {
+        // this lane holds 4 consecutive keys of each of the block's 4 key tiles for query row r of tile t
+        const int row = q0 + t * 16 + r;
+        if (row < m) {
+          const int gblk = (key_lo >> 6) + blk;                     // key_lo is a multiple of the block length
+          // stored as packed: the 64 values of (row, block) in the order [32-key step][lane group][tile, key]
+          bf16* prow = ptilde + ((size_t)head * m + row) * Lp + (size_t)gblk * kBlockKeys + 8 * g;
+#pragma unroll
+          for (int ks = 0; ks < 2; ++ks) *reinterpret_cast<u32x4*>(prow + ks * 32) = pf[ks][t].raw;
+          if (g == 0) refblk[((size_t)head * n_blk_total + gblk) * m + row] = ref[t];
+        }
+      }
     }
+    // ---- O^T += V^T P^T
 #pragma unroll
     for (int b0 = 0; b0 < ND * 2; b0 += FB) {
       Frag<bf16> vf[FB];
 #pragma unroll
-      for (int i = 0; i < FB; ++i) vf[i].raw = v_lds[buf][(b0 + i) * 64 + lane];
-      __builtin_amdgcn_sched_barrier(0);
+      for (int i = 0; i < FB; ++i) vf[i].raw = v_lds[buf][(b0 + i) * 64 + vlane[((b0 + i) / 2) & 3]];
 #pragma unroll
       for (int i = 0; i < FB; ++i)
 #pragma unroll
         for (int t = 0; t < QT; ++t) mfma16(acc[(b0 + i) / 2][t], vf[i], pf[(b0 + i) % 2][t]);
-      __builtin_amdgcn_sched_barrier(0);
     }
-    // the other buffer was last read one iteration ago, before the barrier every wave has passed
-    store_block(stg, buf ^ 1);
-    __syncthreads();
   };
 
   load_block(stg, 0);
   store_block(stg, 0);
   __syncthreads();
-  int blk = 0;
-  for (;;) {
-    for (; blk < n_blocks; ++blk) {                    // hot loop
-      load_block(stg, blk + 1);                        // flies during this block's arithmetic
-      __builtin_amdgcn_sched_barrier(0);
-      if (scores(blk)) break;
-      finish(blk);
-    }
-    if (blk >= n_blocks) break;
-    // a row's reference must go up: rescale its sums, then finish the block as usual
-#pragma unroll
-    for (int t = 0; t < QT; ++t) {
-      const float ref_new = fmaxf(ref[t], tmax2[t] > ref[t] + kRaise ? tmax2[t] : ref[t]);
-      const float alpha = __builtin_amdgcn_exp2f(ref[t] - ref_new);        // 0 on the first block, 1 if unchanged
-      l_run[t] *= alpha;
-#pragma unroll
-      for (int d = 0; d < ND; ++d) acc[d][t] *= alpha;
-      ref[t] = ref_new;
-    }
-    finish(blk);
-    ++blk;
+  for (int blk = 0; blk < n_blocks; ++blk) {
+    load_block(stg, blk + 1);                          // flies during this block's arithmetic
+    block(blk);
+    // the other buffer was last read one iteration ago, before the barrier every wave has passed
+    store_block(stg, (blk & 1) ^ 1);
+    __syncthreads();
   }
 
 #pragma unroll
@@ -301,6 +332,11 @@ __global__ __launch_bounds__(kThreads) void attn_tiled_fwd_kernel(
     l += __shfl_xor(l, 32, kWave);
     const int row = q0 + t * 16 + r;
     if (row >= m) continue;
+    const size_t prow = ((size_t)id.split * n_heads + head) * m + row;
+    if (g == 0 && (EMIT || n_splits > 1)) {
+      ml_part[prow * 2] = ref[t];                        // base-2 reference of this partial
+      ml_part[prow * 2 + 1] = l;
+    }
     if (n_splits == 1) {
       const float inv = 1.0f / l;
       bf16* dst = out + (size_t)row * dq + head * DH + 4 * g;
@@ -312,171 +348,152 @@ __global__ __launch_bounds__(kThreads) void attn_tiled_fwd_kernel(
       }
       if (g == 0) lse[(size_t)head * m + row] = ref[t] * 0.693147180559945309f + __logf(l);
     } else {
-      const size_t prow = ((size_t)id.split * n_heads + head) * m + row;
       float* dst = o_part + prow * DH + 4 * g;
 #pragma unroll
       for (int d = 0; d < ND; ++d) *reinterpret_cast<f32x4*>(dst + d * 16) = acc[d][t];
-      if (g == 0) {
-        ml_part[prow * 2] = ref[t] * 0.693147180559945309f;      // natural-log reference of this partial
-        ml_part[prow * 2 + 1] = l;
-      }
     }
   }
 }
 
-// out[row, head, :] = sum_s e^{m_s - M} O_s / sum_s e^{m_s - M} l_s over the key splits, in split order.
+// Everything that has to wait for all key splits of a row, in one launch with two kinds of workgroups.
+//   merge (the workgroups behind the first avg_blocks, only with several key splits):
+//     out[row, head, :] = sum_s 2^{ref_s - M} O_s / sum_s 2^{ref_s - M} l_s in split order, and the row's log-sum-exp;
+//   head average (the first avg_blocks workgroups): A-bar[i, j] = (1/H) sum_h ptilde[h, i, j] 2^{refblk[h, j / 64, i] - lse2[h, i]}, heads in
+//     order, with lse2[h, i] = M + log2 sum_s l_s 2^{ref_s - M} (M = max_s ref_s) recomputed from the splits' (ref, l).
+//     A workgroup takes kFinRows rows x kFinKeys keys; a thread owns 8 consecutive keys of one row.
+constexpr int kFinRows = 2, kFinKeys = 1024, kFinHeads = 64;
 template <int DH>
-__global__ __launch_bounds__(kThreads) void attn_merge_kernel(const float* __restrict__ o_part,
-                                                              const float* __restrict__ ml_part, int m, int n_heads,
-                                                              int n_splits, bf16* __restrict__ out,
-                                                              float* __restrict__ lse) {
-  constexpr int PER_ROW = DH / 4;                       // threads per (head, row): 4 values each
-  const size_t item = (size_t)blockIdx.x * kThreads + threadIdx.x;
-  const size_t hr = item / PER_ROW;                     // head * m + row
-  const int c = (int)(item - hr * PER_ROW);
-  if (hr >= (size_t)n_heads * m) return;
-  const int head = (int)(hr / m), row = (int)(hr - (size_t)head * m);
-  float mx = -INFINITY;
-  for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, ml_part[((size_t)s * n_heads * m + hr) * 2]);
-  float lsum = 0.f;
-  f32x4 o = {0.f, 0.f, 0.f, 0.f};
-  for (int s = 0; s < n_splits; ++s) {
-    const size_t prow = (size_t)s * n_heads * m + hr;
-    const float f = __expf(ml_part[prow * 2] - mx);
-    lsum += ml_part[prow * 2 + 1] * f;
-    o += *reinterpret_cast<const f32x4*>(o_part + prow * DH + 4 * c) * f;
-  }
-  const float inv = 1.0f / lsum;
-  const u32x2 v = {pack_bf16(o[0] * inv, o[1] * inv), pack_bf16(o[2] * inv, o[3] * inv)};
-  *reinterpret_cast<u32x2*>(out + (size_t)row * n_heads * DH + head * DH + 4 * c) = v;
-  if (c == 0) lse[hr] = mx + __logf(lsum);
-}
-
-// A-bar tile of 64*QT queries x 16*KA keys: loop over the heads, K block of each head through LDS,
-// exp2(s*c - lse*log2e) accumulated in registers.  Every iteration streams its Q and K pieces once
-// (no reuse across heads), so the bytes per tile fall with the tile size: the plan takes the largest
-// tile and restores the workgroup count by dealing the heads to several workgroups per tile.
-template <int DH, int KA, int QT>
-__global__ __launch_bounds__(kThreads) void attn_tiled_avg_kernel(const bf16* __restrict__ q,
-                                                                  const bf16* __restrict__ k_cache,
-                                                                  const float* __restrict__ lse, int m, int L,
-                                                                  int n_heads, int n_kv_heads, float scale,
-                                                                  int heads_per_group,
-                                                                  float* __restrict__ attn_avg) {
-  constexpr int NS = DH / 32;
-  constexpr int NF = KA * NS;                    // K fragments per head
-  constexpr int FW = (NF + 3) / 4;               // of which one wave stages this many
-  __shared__ u32x4 k_lds[2][NF * 64];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int r = lane & 15, g = lane >> 4;
-  const int q0 = blockIdx.x * (64 * QT) + wave * (16 * QT);
-  const int key0 = blockIdx.y * (16 * KA);
-  const int dq = n_heads * DH;
-  const size_t kv_pitch = (size_t)n_kv_heads * DH;
-  const int group = n_heads / n_kv_heads;
-  int row[QT];
-  const bf16* qrow[QT];
-#pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    row[t] = min(q0 + t * 16 + r, m - 1);
-    qrow[t] = q + (size_t)row[t] * dq + g * 8;
-  }
-  // blockIdx.z = head group; with several groups each writes its own [m, L] partial (already divided
-  // by the head count) and a separate launch adds the partials in group order
-  const int head_lo = blockIdx.z * heads_per_group;
-  const int head_hi = min(n_heads, head_lo + heads_per_group);
-  attn_avg += (size_t)blockIdx.z * m * L;
-  const float c2 = scale * 1.44269504088896341f;
-
-  u32x4 kst[FW];
-  Frag<bf16> qf[2][QT][NS];
-  float e[2][QT];                                // lse of the head in flight / in use (raw: any arithmetic on a
-                                                 // value just loaded would wait for every outstanding load)
-  auto load_head = [&](int head, int slot) {
-    const int kvh = head / group;
-#pragma unroll
-    for (int i = 0; i < FW; ++i) {
-      const int f = min(wave + 4 * i, NF - 1);    // fragment (key tile f / NS, step f % NS); surplus waves repeat the last
-      const int key = min(key0 + (f / NS) * 16 + r, L - 1);
-      kst[i] = ld16(k_cache + (size_t)key * kv_pitch + kvh * DH + (f % NS) * 32 + g * 8);
+__global__ __launch_bounds__(kThreads) void attn_finish_kernel(const float* __restrict__ o_part,
+                                                               const float* __restrict__ ml_part,
+                                                               const bf16* __restrict__ ptilde,
+                                                               const float* __restrict__ refblk, int m, int L,
+                                                               int n_heads, int n_splits, int avg_blocks,
+                                                               bf16* __restrict__ out, float* __restrict__ lse,
+                                                               float* __restrict__ attn_avg) {
+  if ((int)blockIdx.x >= avg_blocks) {                    // the head-average workgroups run longest and go first
+    constexpr int PER_ROW = DH / 4;                       // threads per (head, row): 4 values each
+    const size_t item = (size_t)((int)blockIdx.x - avg_blocks) * kThreads + threadIdx.x;
+    const size_t hr = item / PER_ROW;                     // head * m + row
+    const int c = (int)(item - hr * PER_ROW);
+    if (hr >= (size_t)n_heads * m) return;
+    const int head = (int)(hr / m), row = (int)(hr - (size_t)head * m);
+    float mx = -INFINITY;
+    for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, ml_part[((size_t)s * n_heads * m + hr) * 2]);
+    float lsum = 0.f;
+    f32x4 o = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < n_splits; ++s) {
+      const size_t prow = (size_t)s * n_heads * m + hr;
+      const float f = __builtin_amdgcn_exp2f(ml_part[prow * 2] - mx);
+      lsum += ml_part[prow * 2 + 1] * f;
+      o += *reinterpret_cast<const f32x4*>(o_part + prow * DH + 4 * c) * f;
     }
+    const float inv = 1.0f / lsum;
+    const u32x2 v = {pack_bf16(o[0] * inv, o[1] * inv), pack_bf16(o[2] * inv, o[3] * inv)};
+    *reinterpret_cast<u32x2*>(out + (size_t)row * n_heads * DH + head * DH + 4 * c) = v;
+    if (c == 0) lse[hr] = mx * 0.693147180559945309f + __logf(lsum);
+    return;
+  }
+  __shared__ float lse2_s[kFinHeads][kFinRows];
+  const int n_blk = (L + kBlockKeys - 1) / kBlockKeys, Lk = n_blk * kBlockKeys, Lp = Lk + kPtildePad;
+  const int key_tiles = (Lk + kFinKeys - 1) / kFinKeys;
+  const int b = (int)blockIdx.x;
+  const int rb = b / key_tiles, kb = b - rb * key_tiles;
+  const int tid = threadIdx.x, rr = tid / (kFinKeys / 8), c = tid % (kFinKeys / 8);
+  const int row = rb * kFinRows + rr;
+  const int j0 = kb * kFinKeys + c * 8;                    // this thread's 16-byte piece of the row
+  const bool live = row < m && j0 < Lk;
+  const int rowc = min(row, m - 1), j0c = min(j0, Lk - 8);
+  const bf16* pbase = ptilde + (size_t)rowc * Lp + j0c;
+  const float* rbase = refblk + (size_t)(j0c >> 6) * m + rowc;
+  float acc[8];
 #pragma unroll
-    for (int t = 0; t < QT; ++t) {
+  for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+  constexpr int U = 32;                                    // heads per trip: their loads are issued together
+  for (int h0 = 0; h0 < n_heads; h0 += kFinHeads) {
+    const int nh = min(kFinHeads, n_heads - h0);
+    // the first trip's loads are requested before the rows' log-sum-exp is put together, so that the two
+    // latencies overlap (heads past the end repeat the last one and are not added)
+    u32x4 pv[U];
+    float rf[U];
 #pragma unroll
-      for (int s = 0; s < NS; ++s) qf[slot][t][s].raw = ld16(qrow[t] + head * DH + s * 32);
-      e[slot][t] = lse[(size_t)head * m + row[t]];
+    for (int u = 0; u < U; ++u) {
+      const size_t h = (size_t)(h0 + min(u, nh - 1));
+      pv[u] = ld16(pbase + h * m * Lp);
+      rf[u] = rbase[h * n_blk * m];
     }
-  };
-  auto store_head = [&](int buf) {
+    __syncthreads();
+    for (int item = tid; item < kFinHeads * kFinRows; item += kThreads) {
+      const int hh = item / kFinRows, r2 = item - hh * kFinRows;
+      const int row2 = min(rb * kFinRows + r2, m - 1);
+      if (hh < nh) {
+        const size_t hr = (size_t)(h0 + hh) * m + row2;
+        float ms[8], ls[8];                                  // at most 8 key splits
 #pragma unroll
-    for (int i = 0; i < FW; ++i) k_lds[buf][min(wave + 4 * i, NF - 1) * 64 + lane] = kst[i];
-  };
-
-  f32x4 acc[KA][QT];
-#pragma unroll
-  for (int a = 0; a < KA; ++a)
-#pragma unroll
-    for (int t = 0; t < QT; ++t) acc[a][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-  load_head(head_lo, 0);
-  store_head(0);
-  __syncthreads();
-  for (int h0 = head_lo; h0 < head_hi; h0 += 2) {
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int head = h0 + u;                    // a head past the end repeats the last one with zero weight
-      load_head(min(head + 1, head_hi - 1), u ^ 1);
-      const float live = head < head_hi ? 1.f : 0.f;
-#pragma unroll
-      for (int a = 0; a < KA; ++a) {
-        f32x4 st[QT];
-#pragma unroll
-        for (int t = 0; t < QT; ++t) st[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int s = 0; s < NS; ++s) {
-          Frag<bf16> kf;
-          kf.raw = k_lds[u][(a * NS + s) * 64 + lane];
-#pragma unroll
-          for (int t = 0; t < QT; ++t) mfma16(st[t], kf, qf[u][t][s]);
+        for (int s = 0; s < 8; ++s) {
+          const size_t prow = (size_t)min(s, n_splits - 1) * n_heads * m + hr;
+          ms[s] = ml_part[prow * 2];
+          ls[s] = ml_part[prow * 2 + 1];
         }
+        float mx = ms[0];
 #pragma unroll
-        for (int t = 0; t < QT; ++t) {
-          const float ne2 = -1.44269504088896341f * e[u][t];
+        for (int s = 1; s < 8; ++s) mx = fmaxf(mx, ms[s]);
+        float lsum = 0.f;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) acc[a][t][j] += live * __builtin_amdgcn_exp2f(fmaf(st[t][j], c2, ne2));
+        for (int s = 0; s < 8; ++s)
+          if (s < n_splits) lsum += ls[s] * __builtin_amdgcn_exp2f(ms[s] - mx);
+        lse2_s[hh][r2] = mx + __builtin_amdgcn_logf(lsum);      // v_log_f32 is a base-2 logarithm
+      }
+    }
+    __syncthreads();
+    for (int hh = 0; hh < nh; hh += U) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (hh + u < nh) {
+          const float f = __builtin_amdgcn_exp2f(rf[u] - lse2_s[hh + u][rr]);
+          const bf16x8 pb = __builtin_bit_cast(bf16x8, pv[u]);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[e] = fmaf((float)pb[e], f, acc[e]);
         }
       }
-      store_head(u ^ 1);
-      __syncthreads();
-      // nothing of the next head's arithmetic may move up here: anything that touches a value still in
-      // flight would make this half wait for all of its own prefetch loads
-      __builtin_amdgcn_sched_barrier(0);
+      if (hh + U < nh) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const size_t h = (size_t)(h0 + min(hh + U + u, nh - 1));
+          pv[u] = ld16(pbase + h * m * Lp);
+          rf[u] = rbase[h * n_blk * m];
+        }
+      }
     }
   }
+  if (!live) return;
+  // piece (ks, g) of block blk holds keys 64 blk + 32 ks + 4 g .. +3 and the same 16 keys further on
   const float inv_h = 1.0f / (float)n_heads;
+  const int piece = (j0 >> 3) & 7, ks = piece >> 2, g = piece & 3;
+  const int key_a = (j0 & ~63) + 32 * ks + 4 * g, key_b = key_a + 16;
+  float* dst = attn_avg + (size_t)row * L;
+  if ((L & 3) == 0) {                                      // rows start 16-byte aligned
+    if (key_a < L) *reinterpret_cast<f32x4*>(dst + key_a) = f32x4{acc[0] * inv_h, acc[1] * inv_h, acc[2] * inv_h, acc[3] * inv_h};
+    if (key_b < L) *reinterpret_cast<f32x4*>(dst + key_b) = f32x4{acc[4] * inv_h, acc[5] * inv_h, acc[6] * inv_h, acc[7] * inv_h};
+  } else {
 #pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    const int qr = q0 + t * 16 + r;
-    if (qr >= m) continue;
-#pragma unroll
-    for (int a = 0; a < KA; ++a) {
-      float* dst = attn_avg + (size_t)qr * L + key0 + a * 16 + 4 * g;
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (key0 + a * 16 + 4 * g + j < L) dst[j] = acc[a][t][j] * inv_h;
+    for (int e = 0; e < 4; ++e) {
+      if (key_a + e < L) dst[key_a + e] = acc[e] * inv_h;
+      if (key_b + e < L) dst[key_b + e] = acc[4 + e] * inv_h;
     }
   }
 }
-
-constexpr int kTargetWgs = 256;       // one workgroup per compute unit before the key range is split
 
 struct FwdPlan {
-  int qt, q_blocks, n_splits, keys_per_split;
+  int qt, waves, q_blocks, n_splits, keys_per_split;
 };
 FwdPlan plan_fwd(const Tunables& t, int m, int L, int n_heads) {
   FwdPlan p;
   const int want_qt = t.attn_qt;
   p.qt = want_qt == 1 ? 1 : want_qt == 2 ? 2 : (m > 64 ? 2 : 1);
-  p.q_blocks = (m + 64 * p.qt - 1) / (64 * p.qt);
+  // more than 128 rows: 8 waves (two per SIMD) on 256 queries per workgroup
+  p.waves = t.attn_waves == 4 || t.attn_waves == 8 ? t.attn_waves : (p.qt == 2 && m > 128 ? 8 : 4);
+  const int q_per_wg = 16 * p.qt * p.waves;
+  p.q_blocks = (m + q_per_wg - 1) / q_per_wg;
   const int blocks = (L + kBlockKeys - 1) / kBlockKeys;
   int splits = 1;
   const int max_splits = std::max(1, std::min(8, t.attn_max_splits));
@@ -487,128 +504,88 @@ FwdPlan plan_fwd(const Tunables& t, int m, int L, int n_heads) {
   return p;
 }
 
+// Scratch of one call, in floats: partial outputs of the key splits, their (reference, sum) pairs, the
+// unnormalised probabilities (bf16, two per float) and the per-block references.
+struct Scratch {
+  size_t o_part, ml, ptilde, refblk, total;
+};
+Scratch scratch_of(const FwdPlan& p, int m, int L, int n_heads, int head_dim, bool emit) {
+  Scratch s;
+  const size_t hm = (size_t)n_heads * m;
+  const size_t n_blk = (size_t)(L + kBlockKeys - 1) / kBlockKeys;
+  s.o_part = p.n_splits > 1 ? (size_t)p.n_splits * hm * head_dim : 0;
+  s.ml = (size_t)p.n_splits * hm * 2;
+  s.ptilde = emit ? (hm * (n_blk * kBlockKeys + kPtildePad) + 1) / 2 : 0;
+  s.ptilde = (s.ptilde + 3) & ~(size_t)3;                          // keep what follows 16-byte aligned
+  s.refblk = emit ? hm * n_blk : 0;
+  s.total = s.o_part + s.ml + s.ptilde + s.refblk;
+  return s;
+}
+
 template <int DH>
-hipError_t launch_fwd(const Tunables& t, const void* q, const void* k_cache, const void* v_cache, int m, int L, int n_heads,
-                      int n_kv_heads, void* out, float* lse, float* scratch, size_t scratch_floats, hipStream_t st) {
+hipError_t launch_tiled(const Tunables& t, const void* q, const void* k_cache, const void* v_cache, int m, int L,
+                        int n_heads, int n_kv_heads, void* out, float* lse, float* attn_avg, float* scratch,
+                        size_t scratch_floats, hipStream_t st) {
   const FwdPlan p = plan_fwd(t, m, L, n_heads);
-  if (p.n_splits > 1 && (size_t)p.n_splits * n_heads * m * (DH + 2) > scratch_floats) return hipErrorInvalidValue;
+  const bool emit = attn_avg != nullptr;
+  const Scratch sc = scratch_of(p, m, L, n_heads, DH, emit);
+  if ((emit || p.n_splits > 1) && (!scratch || sc.total > scratch_floats)) return hipErrorInvalidValue;
   const float scale = 1.0f / sqrtf((float)DH);
-  float* o_part = scratch;
-  float* ml_part = scratch ? scratch + (size_t)p.n_splits * n_heads * m * DH : nullptr;
-  if (p.n_splits > 1 && !scratch) return hipErrorInvalidValue;
+  float* o_part = scratch;                                         // 16-byte aligned pieces, in this order
+  float* ptilde_f = scratch ? scratch + sc.o_part : nullptr;
+  float* ml_part = scratch ? ptilde_f + sc.ptilde : nullptr;
+  float* refblk = scratch ? ml_part + sc.ml : nullptr;
+  bf16* ptilde = reinterpret_cast<bf16*>(ptilde_f);
   const int groups = (n_heads * p.n_splits + 7) / 8;
   const dim3 grid(groups * 8 * p.q_blocks);
-  if (p.qt == 2)
-    hipLaunchKernelGGL((attn_tiled_fwd_kernel<DH, 2>), grid, dim3(kThreads), 0, st, (const bf16*)q,
-                       (const bf16*)k_cache, (const bf16*)v_cache, m, L, n_heads, n_kv_heads, scale, p.keys_per_split,
-                       p.n_splits, p.q_blocks, (bf16*)out, lse, o_part, ml_part);
-  else
-    hipLaunchKernelGGL((attn_tiled_fwd_kernel<DH, 1>), grid, dim3(kThreads), 0, st, (const bf16*)q,
-                       (const bf16*)k_cache, (const bf16*)v_cache, m, L, n_heads, n_kv_heads, scale, p.keys_per_split,
-                       p.n_splits, p.q_blocks, (bf16*)out, lse, o_part, ml_part);
+#define D2C_TILED_FWD(QT_, WAVES_, EMIT_)                                                                         \
+  hipLaunchKernelGGL((attn_tiled_fwd_kernel<DH, QT_, WAVES_, EMIT_>), grid, dim3(WAVES_ * 64), 0, st, (const bf16*)q, \
+                     (const bf16*)k_cache, (const bf16*)v_cache, m, L, n_heads, n_kv_heads, scale,              \
+                     p.keys_per_split, p.n_splits, p.q_blocks, (bf16*)out, lse, o_part, ml_part, ptilde, refblk)
+  if (p.qt == 2 && p.waves == 8 && emit) D2C_TILED_FWD(2, 8, true);
+  else if (p.qt == 2 && p.waves == 8) D2C_TILED_FWD(2, 8, false);
+  else if (p.qt == 2 && emit) D2C_TILED_FWD(2, 4, true);
+  else if (p.qt == 2) D2C_TILED_FWD(2, 4, false);
+  else if (p.waves == 8) return hipErrorInvalidValue;
+  else if (emit) D2C_TILED_FWD(1, 4, true);
+  else D2C_TILED_FWD(1, 4, false);
+#undef D2C_TILED_FWD
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess || p.n_splits == 1) return e;
+  if (e != hipSuccess || (p.n_splits == 1 && !emit)) return e;
   const size_t items = (size_t)n_heads * m * (DH / 4);
-  hipLaunchKernelGGL(attn_merge_kernel<DH>, dim3((unsigned)((items + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
-                     o_part, ml_part, m, n_heads, p.n_splits, (bf16*)out, lse);
+  const int merge_blocks = p.n_splits > 1 ? (int)((items + kThreads - 1) / kThreads) : 0;
+  const int n_blk = (L + kBlockKeys - 1) / kBlockKeys;
+  const int avg_blocks = emit ? ((m + kFinRows - 1) / kFinRows) * ((n_blk * kBlockKeys + kFinKeys - 1) / kFinKeys) : 0;
+  hipLaunchKernelGGL(attn_finish_kernel<DH>, dim3((unsigned)(merge_blocks + avg_blocks)), dim3(kThreads), 0, st, o_part,
+                     ml_part, ptilde, refblk, m, L, n_heads, p.n_splits, avg_blocks, (bf16*)out, lse, attn_avg);
   return hipGetLastError();
-}
-
-struct AvgPlan {
-  int ka, qt, key_blocks, q_blocks, groups, heads_per_group;
-};
-AvgPlan plan_avg(const Tunables& t, int m, int L, int n_heads, bool one_group = false) {
-  AvgPlan p;
-  // the largest tile the row and key counts fill: 128 x 128, 64 x 128 (m <= 64) or 64 x 32 (L <= 32)
-  p.qt = m > 64 ? 2 : 1;
-  p.ka = L > 32 ? 8 : 2;
-  p.q_blocks = (m + 64 * p.qt - 1) / (64 * p.qt);
-  p.key_blocks = (L + 16 * p.ka - 1) / (16 * p.ka);
-  // The loop over the heads is a chain of dependent load latencies: when the tile grid alone leaves
-  // most of the chip idle, the heads are dealt to several workgroups per tile.
-  // one_group: the caller runs the launch beside other work and wants less total work rather than the
-  // shortest launch: fewer head groups, fewer partials to add
-  int groups = 1;
-  const int max_groups = one_group ? std::max(1, std::min(8, t.attn_side_groups)) : 8;
-  while (groups < max_groups && groups * 2 <= n_heads && (size_t)p.q_blocks * p.key_blocks * groups < 2 * kTargetWgs) groups *= 2;
-  p.heads_per_group = (n_heads + groups - 1) / groups;
-  p.groups = (n_heads + p.heads_per_group - 1) / p.heads_per_group;
-  return p;
-}
-
-template <int DH>
-hipError_t launch_avg(const Tunables& t, const void* q, const void* k_cache, const float* lse, int m, int L, int n_heads,
-                      int n_kv_heads, float* attn_avg, float* scratch, size_t scratch_floats, hipStream_t st,
-                      bool one_group) {
-  const float scale = 1.0f / sqrtf((float)DH);
-  const AvgPlan p = plan_avg(t, m, L, n_heads, one_group);
-  if (p.groups > 1 && (!scratch || (size_t)p.groups * m * L > scratch_floats)) return hipErrorInvalidValue;
-  float* dst = p.groups > 1 ? scratch : attn_avg;
-  const dim3 grid(p.q_blocks, p.key_blocks, p.groups);
-#define D2C_AVG(KA_, QT_)                                                                                      \
-  hipLaunchKernelGGL((attn_tiled_avg_kernel<DH, KA_, QT_>), grid, dim3(kThreads), 0, st, (const bf16*)q,       \
-                     (const bf16*)k_cache, lse, m, L, n_heads, n_kv_heads, scale, p.heads_per_group, dst)
-  if (p.ka == 8 && p.qt == 2) D2C_AVG(8, 2);
-  else if (p.ka == 8) D2C_AVG(8, 1);
-  else if (p.qt == 2) D2C_AVG(2, 2);
-  else D2C_AVG(2, 1);
-#undef D2C_AVG
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess || p.groups == 1) return e;
-  return launch_sum_splits(attn_avg, scratch, p.groups, (size_t)m * L, (size_t)m * L, st);
 }
 
 }  // namespace
 
-// Worst case over every (m <= max_m, L <= max_L): the split count depends on the number of 64-key blocks
-// and shorter sequences can be split as often as longer ones, so both are scanned (L at block boundaries).
+// Worst case over every (m <= max_m, L <= max_L) with the head average wanted: the split count depends on the
+// number of 64-key blocks and shorter sequences can be split as often as longer ones, so both are scanned (L at
+// block boundaries).
 size_t attention_tiled_scratch_floats(const Tunables& t, int max_m, int max_L, int n_heads, int head_dim) {
   size_t worst = 0;
   for (int L = kBlockKeys;; L += kBlockKeys) {
     const int Lc = std::min(L, max_L);
-    for (int m = 1; m <= max_m; ++m) {
-      const FwdPlan p = plan_fwd(t, m, Lc, n_heads);
-      if (p.n_splits > 1) worst = std::max(worst, (size_t)p.n_splits * n_heads * m * (head_dim + 2));
-    }
+    for (int m = 1; m <= max_m; ++m)
+      worst = std::max(worst, scratch_of(plan_fwd(t, m, Lc, n_heads), m, Lc, n_heads, head_dim, true).total);
     if (L >= max_L) break;
   }
   return worst;
 }
 
-hipError_t launch_attention_tiled_fwd(const Tunables& t, const void* q, const void* k_cache, const void* v_cache, int m, int L,
-                                      int n_heads, int n_kv_heads, int head_dim, void* out, float* lse,
-                                      float* scratch, size_t scratch_floats, hipStream_t st) {
+hipError_t launch_attention_tiled(const Tunables& t, const void* q, const void* k_cache, const void* v_cache, int m,
+                                  int L, int n_heads, int n_kv_heads, int head_dim, void* out, float* lse,
+                                  float* attn_avg, float* scratch, size_t scratch_floats, hipStream_t st) {
   if (head_dim == 128)
-    return launch_fwd<128>(t, q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, scratch, scratch_floats, st);
+    return launch_tiled<128>(t, q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, attn_avg, scratch,
+                             scratch_floats, st);
   if (head_dim == 64)
-    return launch_fwd<64>(t, q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, scratch, scratch_floats, st);
-  return hipErrorInvalidValue;
-}
-
-// Worst case over every (m <= max_m, L <= max_L): a short sequence has few key tiles and therefore more
-// head groups, so the product groups * m * L does not peak at max_L; L is scanned at tile boundaries.
-size_t attention_tiled_avg_scratch_floats(const Tunables& t, int max_m, int max_L, int n_heads) {
-  size_t worst = 0;
-  for (int L = 32;; L += 32) {
-    const int Lc = std::min(L, max_L);
-    for (int m = 1; m <= max_m; ++m) {
-      const AvgPlan p = plan_avg(t, m, Lc, n_heads);
-      if (p.groups > 1) worst = std::max(worst, (size_t)p.groups * m * Lc);
-    }
-    if (L >= max_L) break;
-  }
-  return worst;
-}
-
-hipError_t launch_attention_tiled_avg(const Tunables& t, const void* q, const void* k_cache, const float* lse, int m, int L,
-                                      int n_heads, int n_kv_heads, int head_dim, float* attn_avg, float* scratch,
-                                      size_t scratch_floats, hipStream_t st, bool one_group) {
-  if (head_dim == 128)
-    return launch_avg<128>(t, q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, scratch, scratch_floats, st,
-                           one_group);
-  if (head_dim == 64)
-    return launch_avg<64>(t, q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, scratch, scratch_floats, st,
-                          one_group);
+    return launch_tiled<64>(t, q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, attn_avg, scratch,
+                            scratch_floats, st);
   return hipErrorInvalidValue;
 }
 

@@ -15,7 +15,6 @@ inline size_t dtype_size(int dt) { return dt == kBF16 ? 2 : 4; }
 struct Tunables {
   int gemm_target_wgs = 384;   // aim for at least this many groups of 4 waves per GEMM
   int gemm_max_splits = 8;
-  int attn_side_groups = 4;    // most head groups of the head average when it runs beside other work (d2c_step)
   int gemm_wide_min_rows = 257; // the wide instantiation from this many rows on (3 row chunks)
   int gemm_tall_chunk = 1;      // 129-192 bf16 rows as ONE row chunk of 10 or 12 row tiles
   int gemm_wide_tiles = 1;     // more than 128 rows in bf16: 128 x 64 outputs per wave, 4 waves per workgroup
@@ -27,6 +26,7 @@ struct Tunables {
   int attn_tiled_min_m = 96;   // bf16 attention: from this many query rows on, the LDS-tiled kernels
   int attn_max_splits = 8;     // key-range splits of one attention launch (1..8)
   int attn_qt = 0;             // 16-row query tiles per wave in the tiled forward kernel: 1, 2; 0 = by m
+  int attn_waves = 0;          // waves per workgroup of the tiled forward kernel: 4, 8; 0 = by m
   int attn_target_wgs = 256;   // split the key range until the forward grid has this many workgroups
   bool side_stream = true;     // d2c_step: head average + rollout on a second stream
 };
@@ -88,38 +88,40 @@ hipError_t launch_sum_splits(float* dst, const float* P, int n_splits, size_t sp
 // cos/sin table [max_pos, head_dim/2], angles evaluated in fp64
 hipError_t launch_rope_table(float* cos_t, float* sin_t, int max_pos, int head_dim, float theta, hipStream_t st);
 
-// ---- attention of m query rows against all L cached keys, no mask, in two launches
+// ---- attention of m query rows against all L cached keys, no mask
+// Two kernel families.  Few query rows (fp32, or bf16 below attn_tiled_min_m rows): a forward launch and, for
+// the head average, either per-head probability rows written by the forward launch itself (probs, see
+// attention_fwd_emits_probs) or a second launch (launch_attention_avg) that needs the forward's lse.  Many
+// rows in bf16 (attention_is_tiled): K/V blocks staged through LDS, key range split over workgroups; the
+// forward launch also leaves what the head average needs, and one finishing launch merges the splits and
+// writes the average, so tiled_avg is given to launch_attention_fwd itself.
 // fwd: out T [m, H*dh] and the log-sum-exp per (head, row), lse float [H, m]
-// scratch: attention_scratch_floats(...) floats (partials of a split key range), may be null for fp32
+// scratch: attention_scratch_floats(...) floats, may be null for fp32
+bool attention_is_tiled(const Tunables& t, int dtype, int m);
 size_t attention_scratch_floats(const Tunables& t, int dtype, int max_m, int max_L, int n_heads, int head_dim);
 // probs (optional, only where attention_fwd_emits_probs): float [H, m, L], the normalised attention rows of
 // every head, written by the same launch; launch_head_mean turns them into the head average.
 bool attention_fwd_emits_probs(const Tunables& t, int dtype, int m, int L);
 size_t attention_probs_floats(int dtype, int n_heads, int max_L);      // capacity one (layer, sequence) needs
+// tiled_avg: float [m, L] or null; only read where attention_is_tiled (elsewhere it must be null)
 hipError_t launch_attention_fwd(const Tunables& t, int dtype, const void* q, const void* k_cache, const void* v_cache, int m, int L,
                                 int n_heads, int n_kv_heads, int head_dim, void* out, float* lse, float* scratch,
-                                size_t scratch_floats, hipStream_t st, float* probs = nullptr);
+                                size_t scratch_floats, hipStream_t st, float* probs = nullptr,
+                                float* tiled_avg = nullptr);
 // abar[l] (at abar + l * abar_layer_stride, [m, L]) = mean over heads of probs[l] (at probs + l * stride, [H, m, L])
 hipError_t launch_head_mean(const float* probs, size_t probs_layer_stride, float* abar, size_t abar_layer_stride,
                             int n_layers, int n_heads, int m, int L, hipStream_t st);
-// avg: attn_avg float [m, L] = mean over heads of exp(q k / sqrt(dh) - lse); needs fwd's lse
-// scratch: attention_avg_scratch_floats(...) floats (per-head-group partials), may be null for fp32
-size_t attention_avg_scratch_floats(const Tunables& t, int dtype, int max_m, int max_L, int n_heads);
-// one_group: least total work (no head groups, no partials) instead of the shortest launch, for a caller
-// that runs the head average beside other work
+// the second launch of the few-row kernels: attn_avg float [m, L] = mean over heads of
+// exp(q k / sqrt(dh) - lse); needs fwd's lse.  Not for attention_is_tiled shapes.
 hipError_t launch_attention_avg(const Tunables& t, int dtype, const void* q, const void* k_cache, const float* lse, int m, int L,
-                                int n_heads, int n_kv_heads, int head_dim, float* attn_avg, float* scratch,
-                                size_t scratch_floats, hipStream_t st, bool one_group = false);
+                                int n_heads, int n_kv_heads, int head_dim, float* attn_avg, hipStream_t st);
 
-// the bf16 kernels for many query rows (K/V blocks staged through LDS, optional key split + merge)
+// the bf16 kernels for many query rows: forward over a split key range, then one launch that merges the
+// splits and (attn_avg != null) writes the head average
 size_t attention_tiled_scratch_floats(const Tunables& t, int max_m, int max_L, int n_heads, int head_dim);
-hipError_t launch_attention_tiled_fwd(const Tunables& t, const void* q, const void* k_cache, const void* v_cache, int m, int L,
-                                      int n_heads, int n_kv_heads, int head_dim, void* out, float* lse,
-                                      float* scratch, size_t scratch_floats, hipStream_t st);
-size_t attention_tiled_avg_scratch_floats(const Tunables& t, int max_m, int max_L, int n_heads);
-hipError_t launch_attention_tiled_avg(const Tunables& t, const void* q, const void* k_cache, const float* lse, int m, int L,
-                                      int n_heads, int n_kv_heads, int head_dim, float* attn_avg, float* scratch,
-                                      size_t scratch_floats, hipStream_t st, bool one_group = false);
+hipError_t launch_attention_tiled(const Tunables& t, const void* q, const void* k_cache, const void* v_cache, int m,
+                                  int L, int n_heads, int n_kv_heads, int head_dim, void* out, float* lse,
+                                  float* attn_avg, float* scratch, size_t scratch_floats, hipStream_t st);
 
 // ---- rollout on the compact block: c_out = (A[:,S] c_in + A[:,notS] + c_in) / 2; first: c_in = one-hot rows
 hipError_t launch_rollout(const float* attn_avg, const float* c_in, float* c_out, const int32_t* idx, int m, int L,
