@@ -253,6 +253,19 @@ int layer_impl(d2c_ctx* c, int layer, float* hidden, const Seg* segs, int n_seg,
     D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
               launch_add_norm(dt, hidden, nullptr, 0, 0, d, M, d, c->attn_norm[layer], D.rms_eps, c->a_norm, st));
   if ((rc = project(c, c->a_norm, d, c->wqkv[layer], M, dq + 2 * dkv, d, &pl, &stride, st)) != D2C_OK) return rc;
+  // RoPE and cache update per sequence; the few-row attention per sequence as well, the LDS-tiled attention of
+  // the sequences with many rows in batched launches (they write the head average themselves, on this stream)
+  std::vector<TiledCall> tiled;
+  double tiled_bytes = 0.0;
+  auto flush_tiled = [&]() -> int {
+    if (tiled.empty()) return D2C_OK;
+    D2C_TIMED(c, st, D2C_PROF_ATTENTION, tiled_bytes,
+              launch_attention_tiled(c->tun, tiled.data(), (int)tiled.size(), D.n_heads, D.n_kv_heads, D.head_dim,
+                                     c->attn_part, c->attn_part_floats, st));
+    tiled.clear();
+    tiled_bytes = 0.0;
+    return D2C_OK;
+  };
   for (int b = 0; b < n_seg; ++b) {
     const Seg& g = segs[b];
     if (g.m <= 0) continue;
@@ -262,13 +275,19 @@ int layer_impl(d2c_ctx* c, int layer, float* hidden, const Seg* segs, int n_seg,
                                       dq + 2 * dkv, c->bqkv.empty() ? nullptr : c->bqkv[layer], g.idx, g.m,
                                       D.n_heads, D.n_kv_heads, D.head_dim, c->rope_cos, c->rope_sin, qb, g.k_cache,
                                       g.v_cache, st));
-    // many rows: the LDS-tiled kernels write the head average themselves, on this stream, right behind the forward
-    const bool tiled = attention_is_tiled(c->tun, dt, g.m);
-    D2C_TIMED(c, st, D2C_PROF_ATTENTION, 2.0 * g.L * dkv * ts,
-              launch_attention_fwd(c->tun, dt, qb, g.k_cache, g.v_cache, g.m, g.L, D.n_heads, D.n_kv_heads, D.head_dim,
-                                   (char*)c->attn_o + (size_t)g.off * dq * ts, lse + (size_t)D.n_heads * g.off,
-                                   c->attn_part, c->attn_part_floats, st, g.probs, tiled ? g.abar : nullptr));
+    void* ob = (char*)c->attn_o + (size_t)g.off * dq * ts;
+    float* lb = lse + (size_t)D.n_heads * g.off;
+    if (attention_is_tiled(c->tun, dt, g.m)) {
+      tiled.push_back(TiledCall{qb, g.k_cache, g.v_cache, g.m, g.L, ob, lb, g.abar});
+      tiled_bytes += 2.0 * g.L * dkv * ts;
+      if ((int)tiled.size() == attention_tiled_max_batch() && (rc = flush_tiled())) return rc;
+    } else {
+      D2C_TIMED(c, st, D2C_PROF_ATTENTION, 2.0 * g.L * dkv * ts,
+                launch_attention_fwd(c->tun, dt, qb, g.k_cache, g.v_cache, g.m, g.L, D.n_heads, D.n_kv_heads, D.head_dim,
+                                     ob, lb, c->attn_part, c->attn_part_floats, st, g.probs, nullptr));
+    }
   }
+  if ((rc = flush_tiled())) return rc;
   // what is left for the second stream: the second pass of the few-row kernels and the rollout update
   bool any_side = false;
   for (int b = 0; b < n_seg; ++b)
@@ -345,7 +364,9 @@ WsNeeds ws_needs(const d2c_dims& D, size_t max_rows, const Tunables& t) {
       const GemmPlan pl = plan_gemm(t, D.dtype, m, s[0], s[1]);
       n.partial = std::max(n.partial, (size_t)(m <= 128 ? 8 : pl.splits) * m * s[0]);
     }
-  n.attn_part = attention_scratch_floats(t, D.dtype, D.max_seq, D.max_seq, D.n_heads, D.head_dim);
+  // one piece per sequence of a batched attention launch
+  const int batch = std::max(1, std::min((int)(max_rows / (size_t)D.max_seq), attention_tiled_max_batch()));
+  n.attn_part = (size_t)batch * attention_scratch_floats(t, D.dtype, D.max_seq, D.max_seq, D.n_heads, D.head_dim);
   return n;
 }
 

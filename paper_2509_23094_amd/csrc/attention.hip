@@ -505,6 +505,7 @@ hipError_t launch_head_mean(const float* probs, size_t probs_layer_stride, float
   return hipGetLastError();
 }
 
+// per sequence of a batch; a caller that batches n sequences provides n times as much
 size_t attention_scratch_floats(const Tunables& t, int dtype, int max_m, int max_L, int n_heads, int head_dim) {
   return dtype == kBF16 ? attention_tiled_scratch_floats(t, max_m, max_L, n_heads, head_dim) : 0;
 }
@@ -517,9 +518,10 @@ hipError_t launch_attention_fwd(const Tunables& t, int dtype, const void* q, con
   if (m <= 0) return hipSuccess;
   if (L <= 0 || n_heads % n_kv_heads) return hipErrorInvalidValue;
   if (probs && !attention_fwd_emits_probs(t, dtype, m, L)) return hipErrorInvalidValue;
-  if (attention_is_tiled(t, dtype, m))
-    return launch_attention_tiled(t, q, k_cache, v_cache, m, L, n_heads, n_kv_heads, head_dim, out, lse, tiled_avg,
-                                  scratch, scratch_floats, st);
+  if (attention_is_tiled(t, dtype, m)) {
+    const TiledCall call{q, k_cache, v_cache, m, L, out, lse, tiled_avg};
+    return launch_attention_tiled(t, &call, 1, n_heads, n_kv_heads, head_dim, scratch, scratch_floats, st);
+  }
   if (tiled_avg) return hipErrorInvalidValue;
   if (dtype == kBF16) {
     if (head_dim == 128)

@@ -20,7 +20,7 @@
 //             block of each head staged through LDS; exp(s - lse) accumulates in registers.
 #include <algorithm>
 #include <cmath>
-#include <type_traits>
+#include <cstring>
 
 #include "common.h"
 #include "internal.h"
@@ -43,6 +43,19 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, bf16x2));
 }
+
+// One sequence of a batched launch (blockIdx.y picks it): its tensors, sizes, launch plan and scratch pieces.
+struct SeqArgs {
+  const bf16 *q, *k_cache, *v_cache;
+  bf16* out;
+  float *lse, *attn_avg, *o_part, *ml_part, *refblk;
+  bf16* ptilde;
+  int m, L, keys_per_split, n_splits, q_blocks, avg_blocks;
+};
+constexpr int kMaxBatch = 8;             // sequences per launch (the arguments travel by value)
+struct BatchArgs {
+  SeqArgs seq[kMaxBatch];
+};
 
 // Workgroup id -> (query block, head, key split).  Ids are dealt round-robin to the 8 XCDs; the query
 // blocks that share one (head, split), i.e. the same K and V bytes, get consecutive slots of ONE XCD.
@@ -72,11 +85,8 @@ __device__ __forceinline__ TileId tile_of(int bid, int q_blocks, int n_heads, in
 // one wave's matrix-core phase runs beside the other's vector phase (a single wave runs its phases one after
 // the other), and a K/V block staged once serves twice as many queries.
 template <int DH, int QT, int WAVES, bool EMIT>
-__global__ __launch_bounds__(WAVES * 64) void attn_tiled_fwd_kernel(
-    const bf16* __restrict__ q, const bf16* __restrict__ k_cache, const bf16* __restrict__ v_cache, int m, int L,
-    int n_heads, int n_kv_heads, float scale, int keys_per_split, int n_splits, int q_blocks,
-    bf16* __restrict__ out, float* __restrict__ lse, float* __restrict__ o_part, float* __restrict__ ml_part,
-    bf16* __restrict__ ptilde, float* __restrict__ refblk) {
+__global__ __launch_bounds__(WAVES * 64) void attn_tiled_fwd_kernel(const BatchArgs batch, int n_heads, int n_kv_heads,
+                                                                    float scale) {
   static_assert(WAVES == 4 || WAVES == 8, "4 or 8 waves");
   constexpr int NS = DH / 32;            // contraction steps of K Q^T
   constexpr int ND = DH / 16;            // head-dim tiles of O^T
@@ -87,8 +97,19 @@ __global__ __launch_bounds__(WAVES * 64) void attn_tiled_fwd_kernel(
   __shared__ u32x4 k_lds[2][4 * NS * 64];      // [key tile a][step s][lane]
   __shared__ u32x4 v_lds[2][ND * 2 * 64];      // [head-dim tile][32-key step][slot]; slot = lane ^ (tile & 3)
 
+  const SeqArgs& sq = batch.seq[blockIdx.y];
+  const bf16* __restrict__ q = sq.q;
+  const bf16* __restrict__ k_cache = sq.k_cache;
+  const bf16* __restrict__ v_cache = sq.v_cache;
+  bf16* __restrict__ out = sq.out;
+  float* __restrict__ lse = sq.lse;
+  float* __restrict__ o_part = sq.o_part;
+  float* __restrict__ ml_part = sq.ml_part;
+  bf16* __restrict__ ptilde = sq.ptilde;
+  float* __restrict__ refblk = sq.refblk;
+  const int m = sq.m, L = sq.L, keys_per_split = sq.keys_per_split, n_splits = sq.n_splits, q_blocks = sq.q_blocks;
   const TileId id = tile_of(blockIdx.x, q_blocks, n_heads, n_splits);
-  if (!id.valid) return;
+  if (!id.valid || id.qb >= q_blocks) return;          // the grid is sized for the largest sequence of the batch
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 15, g = lane >> 4;
   const int head = id.head;
@@ -291,7 +312,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_tiled_fwd_kernel(
       if constexpr (EMIT) {
         // this lane holds 4 consecutive keys of each of the block's 4 key tiles for query row r of tile t
         const int row = q0 + t * 16 + r;
-        if (row < m) {
+        if (row < m && ptilde != nullptr) {      // null: a sequence of the batch whose average is not wanted
           const int gblk = (key_lo >> 6) + blk;                     // key_lo is a multiple of the block length
           // stored as packed: the 64 values of (row, block) in the order [32-key step][lane group][tile, key]
           bf16* prow = ptilde + ((size_t)head * m + row) * Lp + (size_t)gblk * kBlockKeys + 8 * g;
@@ -333,7 +354,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_tiled_fwd_kernel(
     const int row = q0 + t * 16 + r;
     if (row >= m) continue;
     const size_t prow = ((size_t)id.split * n_heads + head) * m + row;
-    if (g == 0 && (EMIT || n_splits > 1)) {
+    if (g == 0 && ml_part != nullptr && (EMIT || n_splits > 1)) {
       ml_part[prow * 2] = ref[t];                        // base-2 reference of this partial
       ml_part[prow * 2 + 1] = l;
     }
@@ -363,14 +384,18 @@ __global__ __launch_bounds__(WAVES * 64) void attn_tiled_fwd_kernel(
 //     A workgroup takes kFinRows rows x kFinKeys keys; a thread owns 8 consecutive keys of one row.
 constexpr int kFinRows = 2, kFinKeys = 1024, kFinHeads = 64;
 template <int DH>
-__global__ __launch_bounds__(kThreads) void attn_finish_kernel(const float* __restrict__ o_part,
-                                                               const float* __restrict__ ml_part,
-                                                               const bf16* __restrict__ ptilde,
-                                                               const float* __restrict__ refblk, int m, int L,
-                                                               int n_heads, int n_splits, int avg_blocks,
-                                                               bf16* __restrict__ out, float* __restrict__ lse,
-                                                               float* __restrict__ attn_avg) {
+__global__ __launch_bounds__(kThreads) void attn_finish_kernel(const BatchArgs batch, int n_heads) {
+  const SeqArgs& sq = batch.seq[blockIdx.y];
+  const float* __restrict__ o_part = sq.o_part;
+  const float* __restrict__ ml_part = sq.ml_part;
+  const bf16* __restrict__ ptilde = sq.ptilde;
+  const float* __restrict__ refblk = sq.refblk;
+  bf16* __restrict__ out = sq.out;
+  float* __restrict__ lse = sq.lse;
+  float* __restrict__ attn_avg = sq.attn_avg;
+  const int m = sq.m, L = sq.L, n_splits = sq.n_splits, avg_blocks = sq.avg_blocks;
   if ((int)blockIdx.x >= avg_blocks) {                    // the head-average workgroups run longest and go first
+    if (n_splits <= 1) return;                            // nothing to merge (the grid is sized for the whole batch)
     constexpr int PER_ROW = DH / 4;                       // threads per (head, row): 4 values each
     const size_t item = (size_t)((int)blockIdx.x - avg_blocks) * kThreads + threadIdx.x;
     const size_t hr = item / PER_ROW;                     // head * m + row
@@ -523,70 +548,107 @@ Scratch scratch_of(const FwdPlan& p, int m, int L, int n_heads, int head_dim, bo
 }
 
 template <int DH>
-hipError_t launch_tiled(const Tunables& t, const void* q, const void* k_cache, const void* v_cache, int m, int L,
-                        int n_heads, int n_kv_heads, void* out, float* lse, float* attn_avg, float* scratch,
-                        size_t scratch_floats, hipStream_t st) {
-  const FwdPlan p = plan_fwd(t, m, L, n_heads);
-  const bool emit = attn_avg != nullptr;
-  const Scratch sc = scratch_of(p, m, L, n_heads, DH, emit);
-  if ((emit || p.n_splits > 1) && (!scratch || sc.total > scratch_floats)) return hipErrorInvalidValue;
+hipError_t launch_tiled(const Tunables& t, const TiledCall* calls, int n_calls, int n_heads, int n_kv_heads,
+                        float* scratch, size_t scratch_floats, hipStream_t st) {
+  // one plan for the batch: tile shape by the largest row count, key splits so that all sequences together
+  // give every compute unit a workgroup
+  int max_m = 0, max_L = 0;
+  bool emit = false;
+  for (int i = 0; i < n_calls; ++i) {
+    max_m = std::max(max_m, calls[i].m);
+    max_L = std::max(max_L, calls[i].L);
+    emit = emit || calls[i].attn_avg != nullptr;
+  }
+  const FwdPlan shape = plan_fwd(t, max_m, max_L, n_heads);
+  const int q_per_wg = 16 * shape.qt * shape.waves;
+  int wgs_unsplit = 0;
+  for (int i = 0; i < n_calls; ++i) wgs_unsplit += ((calls[i].m + q_per_wg - 1) / q_per_wg) * n_heads;
+  int splits = 1;
+  const int max_splits = std::max(1, std::min(8, t.attn_max_splits));
+  const int min_blocks = (std::max(1, max_L) + kBlockKeys - 1) / kBlockKeys;
+  while (splits < max_splits && wgs_unsplit * splits < t.attn_target_wgs && min_blocks / (splits * 2) >= 1) splits *= 2;
   const float scale = 1.0f / sqrtf((float)DH);
-  float* o_part = scratch;                                         // 16-byte aligned pieces, in this order
-  float* ptilde_f = scratch ? scratch + sc.o_part : nullptr;
-  float* ml_part = scratch ? ptilde_f + sc.ptilde : nullptr;
-  float* refblk = scratch ? ml_part + sc.ml : nullptr;
-  bf16* ptilde = reinterpret_cast<bf16*>(ptilde_f);
-  const int groups = (n_heads * p.n_splits + 7) / 8;
-  const dim3 grid(groups * 8 * p.q_blocks);
+  BatchArgs args;
+  memset(&args, 0, sizeof(args));
+  size_t used = 0;
+  int max_tiles = 0, max_fin = 0;
+  for (int i = 0; i < n_calls; ++i) {
+    const TiledCall& c = calls[i];
+    FwdPlan p = shape;
+    p.q_blocks = (c.m + q_per_wg - 1) / q_per_wg;
+    const int blocks = (c.L + kBlockKeys - 1) / kBlockKeys;
+    const int s_i = std::max(1, std::min(splits, blocks));
+    p.keys_per_split = ((blocks + s_i - 1) / s_i) * kBlockKeys;
+    p.n_splits = (c.L + p.keys_per_split - 1) / p.keys_per_split;
+    const bool emit_i = c.attn_avg != nullptr;
+    const Scratch sc = scratch_of(p, c.m, c.L, n_heads, DH, emit_i);
+    if (sc.total > 0 && (!scratch || used + sc.total > scratch_floats)) return hipErrorInvalidValue;
+    float* base = scratch ? scratch + used : nullptr;
+    used += (sc.total + 3) & ~(size_t)3;
+    SeqArgs& a = args.seq[i];
+    a.q = (const bf16*)c.q; a.k_cache = (const bf16*)c.k_cache; a.v_cache = (const bf16*)c.v_cache;
+    a.out = (bf16*)c.out; a.lse = c.lse; a.attn_avg = c.attn_avg;
+    a.o_part = base;                                               // 16-byte aligned pieces, in this order
+    a.ptilde = reinterpret_cast<bf16*>(base && emit_i ? base + sc.o_part : nullptr);
+    a.ml_part = base ? base + sc.o_part + sc.ptilde : nullptr;
+    a.refblk = base && emit_i ? a.ml_part + sc.ml : nullptr;
+    a.m = c.m; a.L = c.L; a.keys_per_split = p.keys_per_split; a.n_splits = p.n_splits; a.q_blocks = p.q_blocks;
+    a.avg_blocks = emit_i ? ((c.m + kFinRows - 1) / kFinRows) * ((blocks * kBlockKeys + kFinKeys - 1) / kFinKeys) : 0;
+    const int groups = (n_heads * p.n_splits + 7) / 8;
+    max_tiles = std::max(max_tiles, groups * 8 * p.q_blocks);
+    const size_t items = (size_t)n_heads * c.m * (DH / 4);
+    const int merge_blocks = p.n_splits > 1 ? (int)((items + kThreads - 1) / kThreads) : 0;
+    max_fin = std::max(max_fin, a.avg_blocks + merge_blocks);
+  }
+  const dim3 grid(max_tiles, n_calls);
 #define D2C_TILED_FWD(QT_, WAVES_, EMIT_)                                                                         \
-  hipLaunchKernelGGL((attn_tiled_fwd_kernel<DH, QT_, WAVES_, EMIT_>), grid, dim3(WAVES_ * 64), 0, st, (const bf16*)q, \
-                     (const bf16*)k_cache, (const bf16*)v_cache, m, L, n_heads, n_kv_heads, scale,              \
-                     p.keys_per_split, p.n_splits, p.q_blocks, (bf16*)out, lse, o_part, ml_part, ptilde, refblk)
-  if (p.qt == 2 && p.waves == 8 && emit) D2C_TILED_FWD(2, 8, true);
-  else if (p.qt == 2 && p.waves == 8) D2C_TILED_FWD(2, 8, false);
-  else if (p.qt == 2 && emit) D2C_TILED_FWD(2, 4, true);
-  else if (p.qt == 2) D2C_TILED_FWD(2, 4, false);
-  else if (p.waves == 8) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((attn_tiled_fwd_kernel<DH, QT_, WAVES_, EMIT_>), grid, dim3(WAVES_ * 64), 0, st, args, n_heads, \
+                     n_kv_heads, scale)
+  if (shape.qt == 2 && shape.waves == 8 && emit) D2C_TILED_FWD(2, 8, true);
+  else if (shape.qt == 2 && shape.waves == 8) D2C_TILED_FWD(2, 8, false);
+  else if (shape.qt == 2 && emit) D2C_TILED_FWD(2, 4, true);
+  else if (shape.qt == 2) D2C_TILED_FWD(2, 4, false);
+  else if (shape.waves == 8) return hipErrorInvalidValue;
   else if (emit) D2C_TILED_FWD(1, 4, true);
   else D2C_TILED_FWD(1, 4, false);
 #undef D2C_TILED_FWD
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess || (p.n_splits == 1 && !emit)) return e;
-  const size_t items = (size_t)n_heads * m * (DH / 4);
-  const int merge_blocks = p.n_splits > 1 ? (int)((items + kThreads - 1) / kThreads) : 0;
-  const int n_blk = (L + kBlockKeys - 1) / kBlockKeys;
-  const int avg_blocks = emit ? ((m + kFinRows - 1) / kFinRows) * ((n_blk * kBlockKeys + kFinKeys - 1) / kFinKeys) : 0;
-  hipLaunchKernelGGL(attn_finish_kernel<DH>, dim3((unsigned)(merge_blocks + avg_blocks)), dim3(kThreads), 0, st, o_part,
-                     ml_part, ptilde, refblk, m, L, n_heads, p.n_splits, avg_blocks, (bf16*)out, lse, attn_avg);
+  if (e != hipSuccess || max_fin == 0) return e;
+  hipLaunchKernelGGL(attn_finish_kernel<DH>, dim3((unsigned)max_fin, n_calls), dim3(kThreads), 0, st, args, n_heads);
   return hipGetLastError();
 }
 
 }  // namespace
 
-// Worst case over every (m <= max_m, L <= max_L) with the head average wanted: the split count depends on the
-// number of 64-key blocks and shorter sequences can be split as often as longer ones, so both are scanned (L at
-// block boundaries).
+// Most scratch ONE sequence of a batch can need, over every (m <= max_m, L <= max_L), with the head average
+// wanted.  Inside a batch the tile shape follows the largest sequence and the split count the whole batch, so
+// a sequence can be split whenever its workgroups in the largest tile shape alone would not fill the chip.
 size_t attention_tiled_scratch_floats(const Tunables& t, int max_m, int max_L, int n_heads, int head_dim) {
   size_t worst = 0;
+  const int max_splits = std::max(1, std::min(8, t.attn_max_splits));
   for (int L = kBlockKeys;; L += kBlockKeys) {
     const int Lc = std::min(L, max_L);
-    for (int m = 1; m <= max_m; ++m)
-      worst = std::max(worst, scratch_of(plan_fwd(t, m, Lc, n_heads), m, Lc, n_heads, head_dim, true).total);
+    const int blocks = (Lc + kBlockKeys - 1) / kBlockKeys;
+    for (int m = 1; m <= max_m; ++m) {
+      FwdPlan p = plan_fwd(t, m, Lc, n_heads);
+      const bool can_split = ((m + 255) / 256) * n_heads < t.attn_target_wgs;
+      p.n_splits = can_split ? std::min(max_splits, blocks) : 1;
+      worst = std::max(worst, (scratch_of(p, m, Lc, n_heads, head_dim, true).total + 3) & ~(size_t)3);
+    }
     if (L >= max_L) break;
   }
   return worst;
 }
 
-hipError_t launch_attention_tiled(const Tunables& t, const void* q, const void* k_cache, const void* v_cache, int m,
-                                  int L, int n_heads, int n_kv_heads, int head_dim, void* out, float* lse,
-                                  float* attn_avg, float* scratch, size_t scratch_floats, hipStream_t st) {
-  if (head_dim == 128)
-    return launch_tiled<128>(t, q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, attn_avg, scratch,
-                             scratch_floats, st);
-  if (head_dim == 64)
-    return launch_tiled<64>(t, q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, attn_avg, scratch,
-                            scratch_floats, st);
+hipError_t launch_attention_tiled(const Tunables& t, const TiledCall* calls, int n_calls, int n_heads, int n_kv_heads,
+                                  int head_dim, float* scratch, size_t scratch_floats, hipStream_t st) {
+  if (n_calls <= 0) return hipSuccess;
+  if (n_calls > kMaxBatch) return hipErrorInvalidValue;
+  if (head_dim == 128) return launch_tiled<128>(t, calls, n_calls, n_heads, n_kv_heads, scratch, scratch_floats, st);
+  if (head_dim == 64) return launch_tiled<64>(t, calls, n_calls, n_heads, n_kv_heads, scratch, scratch_floats, st);
   return hipErrorInvalidValue;
 }
+
+int attention_tiled_max_batch() { return kMaxBatch; }
 
 }  // namespace d2c

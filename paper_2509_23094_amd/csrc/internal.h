@@ -117,11 +117,20 @@ hipError_t launch_attention_avg(const Tunables& t, int dtype, const void* q, con
                                 int n_heads, int n_kv_heads, int head_dim, float* attn_avg, hipStream_t st);
 
 // the bf16 kernels for many query rows: forward over a split key range, then one launch that merges the
-// splits and (attn_avg != null) writes the head average
+// splits and (attn_avg != null) writes the head average.  Several sequences (up to attention_tiled_max_batch)
+// share the two launches: together they fill the chip with fewer key splits, i.e. fewer partials to merge.
+// The scratch is cut into one piece per sequence: it must hold the sum of their needs.
+struct TiledCall {
+  const void *q, *k_cache, *v_cache;
+  int m, L;
+  void* out;          // T [m, H*dh]
+  float* lse;         // [H, m]
+  float* attn_avg;    // [m, L] or null
+};
+int attention_tiled_max_batch();
 size_t attention_tiled_scratch_floats(const Tunables& t, int max_m, int max_L, int n_heads, int head_dim);
-hipError_t launch_attention_tiled(const Tunables& t, const void* q, const void* k_cache, const void* v_cache, int m,
-                                  int L, int n_heads, int n_kv_heads, int head_dim, void* out, float* lse,
-                                  float* attn_avg, float* scratch, size_t scratch_floats, hipStream_t st);
+hipError_t launch_attention_tiled(const Tunables& t, const TiledCall* calls, int n_calls, int n_heads, int n_kv_heads,
+                                  int head_dim, float* scratch, size_t scratch_floats, hipStream_t st);
 
 // ---- rollout on the compact block: c_out = (A[:,S] c_in + A[:,notS] + c_in) / 2; first: c_in = one-hot rows
 hipError_t launch_rollout(const float* attn_avg, const float* c_in, float* c_out, const int32_t* idx, int m, int L,
