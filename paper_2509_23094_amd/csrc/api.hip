@@ -266,15 +266,34 @@ int layer_impl(d2c_ctx* c, int layer, float* hidden, const Seg* segs, int n_seg,
     tiled_bytes = 0.0;
     return D2C_OK;
   };
+  // RoPE + cache update of consecutive non-empty slices in one launch (their rows are consecutive in the
+  // compact buffers; an empty slice in between does not break the run)
+  {
+    std::vector<RopeCall> ropes;
+    auto flush_rope = [&]() -> int {
+      if (ropes.empty()) return D2C_OK;
+      const int off0 = ropes[0].off;
+      for (auto& rcall : ropes) rcall.off -= off0;
+      D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
+                launch_qkv_rope_scatter(dt, c->partial + (size_t)off0 * (dq + 2 * dkv), pl.splits, stride, dq + 2 * dkv,
+                                        c->bqkv.empty() ? nullptr : c->bqkv[layer], ropes.data(), (int)ropes.size(),
+                                        D.n_heads, D.n_kv_heads, D.head_dim, c->rope_cos, c->rope_sin,
+                                        q + (size_t)off0 * dq * ts, st));
+      ropes.clear();
+      return D2C_OK;
+    };
+    for (int b = 0; b < n_seg; ++b) {
+      const Seg& g = segs[b];
+      if (g.m <= 0) continue;
+      ropes.push_back(RopeCall{g.idx, g.k_cache, g.v_cache, g.off, g.m});
+      if ((int)ropes.size() == rope_max_batch() && (rc = flush_rope())) return rc;
+    }
+    if ((rc = flush_rope())) return rc;
+  }
   for (int b = 0; b < n_seg; ++b) {
     const Seg& g = segs[b];
     if (g.m <= 0) continue;
     void* qb = q + (size_t)g.off * dq * ts;
-    D2C_TIMED(c, st, D2C_PROF_ROWWISE, 0.0,
-              launch_qkv_rope_scatter(dt, c->partial + (size_t)g.off * (dq + 2 * dkv), pl.splits, stride,
-                                      dq + 2 * dkv, c->bqkv.empty() ? nullptr : c->bqkv[layer], g.idx, g.m,
-                                      D.n_heads, D.n_kv_heads, D.head_dim, c->rope_cos, c->rope_sin, qb, g.k_cache,
-                                      g.v_cache, st));
     void* ob = (char*)c->attn_o + (size_t)g.off * dq * ts;
     float* lb = lse + (size_t)D.n_heads * g.off;
     if (attention_is_tiled(c->tun, dt, g.m)) {

@@ -69,12 +69,20 @@ hipError_t launch_add_norm(int dtype, float* h, const float* P, int n_splits, si
 // a[i,:] = T(rmsnorm(h[rows[i],:]) * gain)
 hipError_t launch_gather_norm(int dtype, const float* h, const int32_t* rows, int n_rows, int d, const float* gain,
                               float eps, void* a, hipStream_t st);
-// split sums of the QKV projection (+bias), RoPE on q and k at positions idx[r];
-// q -> q_out[r,:], k -> k_cache[idx[r],:], v -> v_cache[idx[r],:]
+// split sums of the QKV projection (+bias), RoPE on q and k at the rows' positions; q -> q_out[r,:],
+// k -> k_cache[pos,:], v -> v_cache[pos,:].  The compact rows are the concatenation of up to rope_max_batch
+// sequences' slices (off = first row of the slice; slices consecutive and non-empty), each with its own
+// index set (pos = idx[r - off]) and caches.
+struct RopeCall {
+  const int32_t* idx;
+  void *k_cache, *v_cache;
+  int off, m;
+};
+int rope_max_batch();
 hipError_t launch_qkv_rope_scatter(int dtype, const float* P, int n_splits, size_t split_stride, int ldp,
-                                   const float* bias, const int32_t* idx, int m, int n_heads, int n_kv_heads,
+                                   const float* bias, const RopeCall* calls, int n_calls, int n_heads, int n_kv_heads,
                                    int head_dim, const float* rope_cos, const float* rope_sin, void* q_out,
-                                   void* k_cache, void* v_cache, hipStream_t st);
+                                   hipStream_t st);
 // act[r,f] = T(silu(g) * u), g/u = split sums of columns f and F+f
 hipError_t launch_swiglu(int dtype, const float* P, int n_splits, size_t split_stride, int ldp, int m, int F,
                          void* act, hipStream_t st);

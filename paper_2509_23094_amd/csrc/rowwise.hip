@@ -3,6 +3,8 @@
 // RoPE + K/V cache update ("updates their KV states", Sec. 4 overview), SwiGLU.
 // All of them are HBM/L2-bound copies with a little arithmetic: one workgroup
 // per row, 16-byte coalesced accesses where the layout allows.
+#include <cstring>
+
 #include "common.h"
 #include "internal.h"
 
@@ -121,16 +123,35 @@ __global__ __launch_bounds__(kThreads) void gather_norm_kernel(const float* __re
   for (int c = threadIdx.x; c < d; c += kThreads) ar[c] = from_f32<T>(hr[c] * inv * gain[c]);
 }
 
+// The sequences whose rows one RoPE / cache-update launch covers: rows off .. off+m of the compact buffers
+// belong to a sequence with its own index set and caches.
+constexpr int kRopeMaxSeqs = 8;
+struct RopeSeqs {
+  const int32_t* idx[kRopeMaxSeqs];
+  void* k_cache[kRopeMaxSeqs];
+  void* v_cache[kRopeMaxSeqs];
+  int off[kRopeMaxSeqs + 1];          // off[n] = total rows
+  int n;
+};
+__device__ __forceinline__ int rope_seq_of(const RopeSeqs& sq, int r) {
+  int s = 0;
+  while (s + 1 < sq.n && r >= sq.off[s + 1]) ++s;
+  return s;
+}
+
 // One workgroup per selected row.  Columns of the fused projection: n_heads
 // query heads, then n_kv_heads key heads, then n_kv_heads value heads.
 // Rotate-half RoPE pairs element i with i + head_dim/2 inside a head.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void qkv_rope_scatter_kernel(
     const float* __restrict__ P, int n_splits, size_t split_stride, int ldp, const float* __restrict__ bias,
-    const int32_t* __restrict__ idx, int n_heads, int n_kv_heads, int head_dim, const float* __restrict__ rope_cos,
-    const float* __restrict__ rope_sin, T* __restrict__ q_out, T* __restrict__ k_cache, T* __restrict__ v_cache) {
+    const RopeSeqs seqs, int n_heads, int n_kv_heads, int head_dim, const float* __restrict__ rope_cos,
+    const float* __restrict__ rope_sin, T* __restrict__ q_out) {
   const int r = blockIdx.x;
-  const int pos = idx[r];
+  const int sq = rope_seq_of(seqs, r);
+  const int pos = seqs.idx[sq][r - seqs.off[sq]];
+  T* __restrict__ k_cache = static_cast<T*>(seqs.k_cache[sq]);
+  T* __restrict__ v_cache = static_cast<T*>(seqs.v_cache[sq]);
   const int half = head_dim >> 1;
   const int dq = n_heads * head_dim, dkv = n_kv_heads * head_dim;
   const float* pr = P + (size_t)r * ldp;
@@ -166,10 +187,13 @@ __global__ __launch_bounds__(kThreads) void qkv_rope_scatter_kernel(
 template <typename T>
 __global__ __launch_bounds__(kThreads) void qkv_rope_scatter_vec_kernel(
     const float* __restrict__ P, int n_splits, size_t split_stride, int ldp, const float* __restrict__ bias,
-    const int32_t* __restrict__ idx, int n_heads, int n_kv_heads, int head_dim, const float* __restrict__ rope_cos,
-    const float* __restrict__ rope_sin, T* __restrict__ q_out, T* __restrict__ k_cache, T* __restrict__ v_cache) {
+    const RopeSeqs seqs, int n_heads, int n_kv_heads, int head_dim, const float* __restrict__ rope_cos,
+    const float* __restrict__ rope_sin, T* __restrict__ q_out) {
   const int r = blockIdx.x;
-  const int pos = idx[r];
+  const int sq = rope_seq_of(seqs, r);
+  const int pos = seqs.idx[sq][r - seqs.off[sq]];
+  T* __restrict__ k_cache = static_cast<T*>(seqs.k_cache[sq]);
+  T* __restrict__ v_cache = static_cast<T*>(seqs.v_cache[sq]);
   const int half = head_dim >> 1, q4 = half >> 2;            // 4-wide items per half head
   const int dq = n_heads * head_dim, dkv = n_kv_heads * head_dim;
   const float* pr = P + (size_t)r * ldp;
@@ -322,11 +346,24 @@ hipError_t launch_gather_norm(int dtype, const float* h, const int32_t* rows, in
 }
 
 hipError_t launch_qkv_rope_scatter(int dtype, const float* P, int n_splits, size_t split_stride, int ldp,
-                                   const float* bias, const int32_t* idx, int m, int n_heads, int n_kv_heads,
+                                   const float* bias, const RopeCall* calls, int n_calls, int n_heads, int n_kv_heads,
                                    int head_dim, const float* rope_cos, const float* rope_sin, void* q_out,
-                                   void* k_cache, void* v_cache, hipStream_t st) {
-  if (m <= 0) return hipSuccess;
-  if (head_dim % 2) return hipErrorInvalidValue;
+                                   hipStream_t st) {
+  if (n_calls <= 0) return hipSuccess;
+  if (n_calls > kRopeMaxSeqs || head_dim % 2) return hipErrorInvalidValue;
+  RopeSeqs sq;
+  memset(&sq, 0, sizeof(sq));
+  int m = 0;
+  for (int i = 0; i < n_calls; ++i) {
+    if (calls[i].m <= 0 || calls[i].off != m) return hipErrorInvalidValue;      // consecutive, non-empty slices
+    sq.idx[i] = calls[i].idx;
+    sq.k_cache[i] = calls[i].k_cache;
+    sq.v_cache[i] = calls[i].v_cache;
+    sq.off[i] = m;
+    m += calls[i].m;
+  }
+  sq.off[n_calls] = m;
+  sq.n = n_calls;
   // the vector kernel reads P, the bias and the RoPE table in 16-byte pieces
   if (head_dim % 8 == 0 && ldp % 4 == 0 && split_stride % 4 == 0 && (uintptr_t)P % 16 == 0 &&
       (bias == nullptr || (uintptr_t)bias % 16 == 0)) {
@@ -334,22 +371,24 @@ hipError_t launch_qkv_rope_scatter(int dtype, const float* P, int n_splits, size
     const dim3 grid(m, (items + 2 * kThreads - 1) / (2 * kThreads));
     D2C_DISPATCH(dtype,
                  hipLaunchKernelGGL(qkv_rope_scatter_vec_kernel<bf16>, grid, dim3(kThreads), 0, st, P, n_splits,
-                                    split_stride, ldp, bias, idx, n_heads, n_kv_heads, head_dim, rope_cos, rope_sin,
-                                    (bf16*)q_out, (bf16*)k_cache, (bf16*)v_cache),
+                                    split_stride, ldp, bias, sq, n_heads, n_kv_heads, head_dim, rope_cos, rope_sin,
+                                    (bf16*)q_out),
                  hipLaunchKernelGGL(qkv_rope_scatter_vec_kernel<float>, grid, dim3(kThreads), 0, st, P, n_splits,
-                                    split_stride, ldp, bias, idx, n_heads, n_kv_heads, head_dim, rope_cos, rope_sin,
-                                    (float*)q_out, (float*)k_cache, (float*)v_cache));
+                                    split_stride, ldp, bias, sq, n_heads, n_kv_heads, head_dim, rope_cos, rope_sin,
+                                    (float*)q_out));
     return hipGetLastError();
   }
   D2C_DISPATCH(dtype,
                hipLaunchKernelGGL(qkv_rope_scatter_kernel<bf16>, dim3(m), dim3(kThreads), 0, st, P, n_splits,
-                                  split_stride, ldp, bias, idx, n_heads, n_kv_heads, head_dim, rope_cos, rope_sin,
-                                  (bf16*)q_out, (bf16*)k_cache, (bf16*)v_cache),
+                                  split_stride, ldp, bias, sq, n_heads, n_kv_heads, head_dim, rope_cos, rope_sin,
+                                  (bf16*)q_out),
                hipLaunchKernelGGL(qkv_rope_scatter_kernel<float>, dim3(m), dim3(kThreads), 0, st, P, n_splits,
-                                  split_stride, ldp, bias, idx, n_heads, n_kv_heads, head_dim, rope_cos, rope_sin,
-                                  (float*)q_out, (float*)k_cache, (float*)v_cache));
+                                  split_stride, ldp, bias, sq, n_heads, n_kv_heads, head_dim, rope_cos, rope_sin,
+                                  (float*)q_out));
   return hipGetLastError();
 }
+
+int rope_max_batch() { return kRopeMaxSeqs; }
 
 hipError_t launch_swiglu(int dtype, const float* P, int n_splits, size_t split_stride, int ldp, int m, int F,
                          void* act, hipStream_t st) {
