@@ -231,13 +231,68 @@ def bench_attention_op(args, B, W, torch, np, tune=None):
     }
 
 
+def bench_parallel_decoding(args, B, W, torch, np, tune=None):
+    """Whole generations at the LLaDA-8B shape with parallel decoding (appendix, parallel decoding settings):
+    besides the best-scored token every stage-1 candidate whose confidence exceeds 0.9 is unmasked in the same
+    step, so a generation takes fewer steps than tokens.  Random-init weights give near-uniform predictions
+    (confidence ~1e-4), so the LM-head weights are scaled up until the confidences spread around the threshold;
+    the timed quantity is generated tokens per second, step 0 included (the paper's throughput definition)."""
+    dims, su = W.DIMS["C3"], W.SETUP["C3"]
+    if args.layers:
+        dims = W.with_layers(dims, args.layers)
+    mdl = device_model(W, dims, 0, torch)
+    mdl["lm_head"] = (mdl["lm_head"].float() * args.head_scale).to(mdl["lm_head"].dtype).contiguous()
+    ctx = B.Context(dims, mdl, su.seq_len, device_weights=True, max_batch=1, tunables=tune)
+    out = {}
+    for name, thr in (("threshold_0.9", 0.9), ("one_token_per_step", 0.0)):
+        prm = B.make_params(su.sigma, su.k, su.p, su.block_len, su.n_unmask, 0, threshold=thr,
+                            rollout_layers=args.rollout_layers)
+        n_gen = 1 + max(1, min(4, args.steps // 64))               # the first generation is the warm-up
+        tokens = steps = 0
+        elapsed = 0.0
+        for gidx in range(n_gen):
+            seqs = fresh_sequences(B, W, ctx, dims, su, gidx)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            n = 0
+            while seqs[0].n_masked > 0 and n < 4 * su.gen_len:
+                ctx.d2c_step(prm, seqs)
+                n += 1
+            torch.cuda.synchronize()
+            if gidx > 0:
+                elapsed += time.perf_counter() - t0
+                tokens += su.gen_len - seqs[0].n_masked
+                steps += n
+        out[name] = {"tokens_per_sec": round(tokens / elapsed, 2), "tokens_per_step": round(tokens / steps, 3),
+                     "steps": steps, "tokens": tokens, "ms_per_step": round(1e3 * elapsed / steps, 4),
+                     "generations": n_gen - 1}
+    ctx.close()
+    main_r = out["threshold_0.9"]
+    return {
+        "metric": "generated_tokens_per_sec", "value": main_r["tokens_per_sec"], "unit": "tokens/s", "n_gpus": 1,
+        "steps": main_r["steps"], "warmup": 1, "ms_per_step": main_r["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": dims.dtype, "data": "synthetic",
+        "config": {"workload": "parallel decoding at the C3 shape (LLaDA-8B geometry, prompt %d + gen %d, block %d): "
+                               "confidence threshold 0.9, LM-head weights x %g, whole generations incl. step 0"
+                               % (su.prompt_len, su.gen_len, su.block_len, args.head_scale)},
+        "variants": out, "speedup_over_one_token_per_step": round(main_r["tokens_per_sec"] /
+                                                                    out["one_token_per_step"]["tokens_per_sec"], 3),
+        "roofline": None, "cpu_baseline": None,
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=128)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="C3", choices=["C3", "C4", "C5", "C6", "C2", "select"],
-                    help="C3 (default, the metric's workload), C4, or C2 = the isolated selective-refresh attention op")
+    ap.add_argument("--workload", default="C3", choices=["C3", "C4", "C5", "C6", "C2", "select", "parallel"],
+                    help="C3 (default, the metric's workload), C4, C5, C6 (other model shapes / lengths), C2 = the isolated "
+                         "selective-refresh attention op, select = the isolated selection, parallel = whole generations "
+                         "at the C3 shape with parallel decoding by confidence threshold 0.9")
+    ap.add_argument("--head-scale", type=float, default=12.0,
+                    help="parallel workload: factor on the random LM-head weights, so that the confidences of a "
+                         "random-init model spread around the threshold")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (the result is then not the metric)")
     ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
                     help="library tunable of the context (include/d2c_tools.h), e.g. --tune gemm_target_wgs=768")
@@ -278,6 +333,9 @@ def main():
         return
     if args.workload == "select":
         print(json.dumps(bench_select_op(args, B, W, torch, np)))
+        return
+    if args.workload == "parallel":
+        print(json.dumps(bench_parallel_decoding(args, B, W, torch, np, tune)))
         return
     dims, su = W.DIMS[args.workload], W.SETUP[args.workload]
     if args.layers:

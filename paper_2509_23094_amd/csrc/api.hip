@@ -630,7 +630,7 @@ int d2c_select(d2c_ctx* c, const d2c_params* p, const float* logits, const int32
   SelectArgs a{p->sigma, p->k, p->p, p->block_len, p->n_unmask, p->cand_mode, p->threshold, p->conf_decode,
                tokens, is_masked, L, prompt_len,
                conf, pred, influence, mstar, u_set, decode_idx, s_next, s_rows_next, counts, score_out};
-  D2C_HIP(c, launch_select(a, st));
+  D2C_HIP(c, launch_select(&a, 1, st));
   return D2C_OK;
 }
 
@@ -661,7 +661,7 @@ int d2c_select_static(const d2c_params* p, int32_t vocab, const float* logits, c
   SelectArgs a{p->sigma, p->k, p->p, p->block_len, p->n_unmask, p->cand_mode, p->threshold, p->conf_decode,
                tokens, is_masked, L, prompt_len,
                conf, pred, influence, mstar, u_set, decode_idx, s_next, s_rows_next, counts, score_out};
-  D2C_HIP(nullptr, launch_select(a, st));
+  D2C_HIP(nullptr, launch_select(&a, 1, st));
   return D2C_OK;
 }
 
@@ -880,13 +880,21 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
       }
     }
     if ((rc = flush())) return rc;
+    // the selections of the group's sequences share launches (one workgroup per sequence)
+    std::vector<SelectArgs> sel;
     for (int i = 0; i < n_seg; ++i) {
       d2c_seq_state& s = seqs[group[i]];
-      SelectArgs a{p->sigma, p->k, p->p, p->block_len, p->n_unmask, p->cand_mode, p->threshold, p->conf_decode,
-                   s.tokens, s.is_masked, s.L,
-                   s.prompt_len, s.conf, s.pred, s.influence, s.mstar, s.u_set, s.decode_idx, s.s_idx, s.s_rows,
-                   s.counts, s.score};
-      D2C_TIMED(c, st, D2C_PROF_SELECT, 0.0, launch_select(a, st));
+      sel.push_back(SelectArgs{p->sigma, p->k, p->p, p->block_len, p->n_unmask, p->cand_mode, p->threshold, p->conf_decode,
+                               s.tokens, s.is_masked, s.L,
+                               s.prompt_len, s.conf, s.pred, s.influence, s.mstar, s.u_set, s.decode_idx, s.s_idx, s.s_rows,
+                               s.counts, s.score});
+      if ((int)sel.size() == select_max_batch() || i + 1 == n_seg) {
+        D2C_TIMED(c, st, D2C_PROF_SELECT, 0.0, launch_select(sel.data(), (int)sel.size(), st));
+        sel.clear();
+      }
+    }
+    for (int i = 0; i < n_seg; ++i) {
+      d2c_seq_state& s = seqs[group[i]];
       D2C_HIP(c, hipMemcpyAsync(c->counts_host + (size_t)group[i] * D2C_N_COUNTS, s.counts,
                                 sizeof(int32_t) * D2C_N_COUNTS, hipMemcpyDeviceToHost, st));
     }

@@ -168,7 +168,9 @@ struct SelectArgs {
   float* score_out;   // nullable: D(i) * s^i of the stage-1 candidates, 0 elsewhere
 };
 int select_max_len();
-hipError_t launch_select(const SelectArgs& a, hipStream_t st);
+// n independent sequences (n <= select_max_batch), one workgroup each
+int select_max_batch();
+hipError_t launch_select(const SelectArgs* args, int n, hipStream_t st);
 hipError_t launch_seq_reset(const uint8_t* is_masked, int L, int32_t* s_idx, int32_t* s_rows, float* conf,
                             int32_t* pred, int32_t* counts, hipStream_t st);
 

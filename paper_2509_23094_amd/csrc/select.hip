@@ -7,6 +7,8 @@
 // top-k ranks 64-bit keys (float bits of the non-negative score, then lower
 // index first); top-p sorts such keys with a bitonic network in LDS and scans
 // fixed-point masses floor(c * 2^32) in uint64.  Ties always go to the lowest index.
+#include <algorithm>
+
 #include "common.h"
 #include "internal.h"
 
@@ -315,9 +317,18 @@ __device__ __forceinline__ unsigned long long key_mass(unsigned long long key) {
   return (unsigned long long)(__uint_as_float((unsigned)(key >> 32)) * 4294967296.0f);
 }
 
-__global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a, int NP) {
+constexpr int kSelMaxBatch = 8;
+struct SelectBatch {
+  SelectArgs seq[kSelMaxBatch];
+};
+
+// One workgroup per sequence (blockIdx.x); the sequences are independent.
+__global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectBatch batch) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const SelectArgs& a = batch.seq[blockIdx.x];
   const int L = a.L;
+  int NP = 2;
+  while (NP < L) NP <<= 1;
   unsigned long long* keys = reinterpret_cast<unsigned long long*>(smem);            // [NP]
   unsigned long long* keys1 = keys + NP;                                             // [L]
   unsigned long long* scan_a = keys1 + L;                                            // [kSelThreads]
@@ -595,12 +606,23 @@ hipError_t launch_influence_chain(const float* abar, size_t layer_stride, int n_
   return hipGetLastError();
 }
 
-hipError_t launch_select(const SelectArgs& a, hipStream_t st) {
-  if (a.L <= 0 || a.L > kSelMaxL || a.block_len <= 0 || a.prompt_len < 0 || a.prompt_len > a.L)
-    return hipErrorInvalidValue;
-  int NP = 2;
-  while (NP < a.L) NP <<= 1;
-  const size_t smem = select_smem_bytes(a.L, NP);
+int select_max_batch() { return kSelMaxBatch; }
+
+hipError_t launch_select(const SelectArgs* args, int n, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  if (n > kSelMaxBatch) return hipErrorInvalidValue;
+  SelectBatch batch;
+  size_t smem = 0;
+  for (int i = 0; i < n; ++i) {
+    const SelectArgs& a = args[i];
+    if (a.L <= 0 || a.L > kSelMaxL || a.block_len <= 0 || a.prompt_len < 0 || a.prompt_len > a.L)
+      return hipErrorInvalidValue;
+    int NP = 2;
+    while (NP < a.L) NP <<= 1;
+    smem = std::max(smem, select_smem_bytes(a.L, NP));
+    batch.seq[i] = a;
+  }
+  for (int i = n; i < kSelMaxBatch; ++i) batch.seq[i] = args[0];        // never read: the grid has n workgroups
   static int lds_limit = 0;
   if (lds_limit == 0) {
     int dev = 0, optin = 0;
@@ -613,7 +635,7 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t st) {
     lds_limit = optin;
   }
   if (smem > (size_t)lds_limit) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(select_kernel, dim3(1), dim3(kSelThreads), smem, st, a, NP);
+  hipLaunchKernelGGL(select_kernel, dim3(n), dim3(kSelThreads), smem, st, batch);
   return hipGetLastError();
 }
 
