@@ -230,30 +230,41 @@ __global__ __launch_bounds__(WAVES * 64) void attn_tiled_fwd_kernel(const BatchA
 #pragma unroll
     for (int d = 0; d < ND; ++d) acc[d][t] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
-  constexpr int FB = 8;                        // LDS fragments read per batch (one latency per batch)
+  constexpr int kRing = 4;                     // LDS fragments in flight ahead of the matrix-core step that uses them
   f32x4 st[4][QT];
   const int vlane[4] = {lane, lane ^ 1, lane ^ 2, lane ^ 3};
 
   auto block = [&](int blk) {
     const int buf = blk & 1;
     const int key0 = key_lo + blk * kBlockKeys;
-    // ---- scores S^T = K Q^T; the first step of every tile starts from a zero accumulator operand
+    // ---- scores S^T = K Q^T; the first step of every tile starts from a zero accumulator operand.
+    // The K fragments come from LDS through a ring of kRing registers: fragment i + kRing is requested right
+    // behind the matrix-core steps of fragment i, so one LDS latency is paid per block, not one per fragment
+    // (the scheduler is told to keep this order; left alone it waits for every pair of reads).
+    {
+      constexpr int NF = 4 * NS;
+      Frag<bf16> kf[kRing];
 #pragma unroll
-    for (int b0 = 0; b0 < 4 * NS; b0 += FB) {
-      Frag<bf16> kf[FB];
+      for (int i = 0; i < kRing; ++i) kf[i].raw = k_lds[buf][i * 64 + lane];
 #pragma unroll
-      for (int i = 0; i < FB; ++i) kf[i].raw = k_lds[buf][(b0 + i) * 64 + lane];
-#pragma unroll
-      for (int i = 0; i < FB; ++i)
+      for (int i = 0; i < NF; ++i) {
 #pragma unroll
         for (int t = 0; t < QT; ++t) {
-          if ((b0 + i) % NS == 0)
-            st[(b0 + i) / NS][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                __builtin_bit_cast(bf16x8, kf[i].raw), __builtin_bit_cast(bf16x8, qf[t][0].raw),
+          if (i % NS == 0)
+            st[i / NS][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                __builtin_bit_cast(bf16x8, kf[i % kRing].raw), __builtin_bit_cast(bf16x8, qf[t][0].raw),
                 f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
           else
-            mfma16(st[(b0 + i) / NS][t], kf[i], qf[t][(b0 + i) % NS]);
+            mfma16(st[i / NS][t], kf[i % kRing], qf[t][i % NS]);
         }
+        if (i + kRing < NF) kf[i % kRing].raw = k_lds[buf][(i + kRing) * 64 + lane];
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, kRing, 0);
+#pragma unroll
+      for (int i = 0; i < NF; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, QT, 0);
+        if (i + kRing < NF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
     }
     if (key0 + kBlockKeys > key_hi) {    // ragged last block of the range: keys past the end score -inf
 #pragma unroll
@@ -322,16 +333,24 @@ __global__ __launch_bounds__(WAVES * 64) void attn_tiled_fwd_kernel(const BatchA
         }
       }
     }
-    // ---- O^T += V^T P^T
+    // ---- O^T += V^T P^T, the V fragments through the same kind of ring
+    {
+      constexpr int NF = ND * 2;
+      Frag<bf16> vf[kRing];
 #pragma unroll
-    for (int b0 = 0; b0 < ND * 2; b0 += FB) {
-      Frag<bf16> vf[FB];
+      for (int i = 0; i < kRing; ++i) vf[i].raw = v_lds[buf][i * 64 + vlane[(i / 2) & 3]];
 #pragma unroll
-      for (int i = 0; i < FB; ++i) vf[i].raw = v_lds[buf][(b0 + i) * 64 + vlane[((b0 + i) / 2) & 3]];
+      for (int i = 0; i < NF; ++i) {
 #pragma unroll
-      for (int i = 0; i < FB; ++i)
+        for (int t = 0; t < QT; ++t) mfma16(acc[i / 2][t], vf[i % kRing], pf[i % 2][t]);
+        if (i + kRing < NF) vf[i % kRing].raw = v_lds[buf][(i + kRing) * 64 + vlane[((i + kRing) / 2) & 3]];
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, kRing, 0);
 #pragma unroll
-        for (int t = 0; t < QT; ++t) mfma16(acc[(b0 + i) / 2][t], vf[i], pf[(b0 + i) % 2][t]);
+      for (int i = 0; i < NF; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, QT, 0);
+        if (i + kRing < NF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
     }
   };
 
@@ -559,14 +578,26 @@ hipError_t launch_tiled(const Tunables& t, const TiledCall* calls, int n_calls, 
     max_L = std::max(max_L, calls[i].L);
     emit = emit || calls[i].attn_avg != nullptr;
   }
-  const FwdPlan shape = plan_fwd(t, max_m, max_L, n_heads);
-  const int q_per_wg = 16 * shape.qt * shape.waves;
-  int wgs_unsplit = 0;
-  for (int i = 0; i < n_calls; ++i) wgs_unsplit += ((calls[i].m + q_per_wg - 1) / q_per_wg) * n_heads;
-  int splits = 1;
+  FwdPlan shape = plan_fwd(t, max_m, max_L, n_heads);
   const int max_splits = std::max(1, std::min(8, t.attn_max_splits));
   const int min_blocks = (std::max(1, max_L) + kBlockKeys - 1) / kBlockKeys;
-  while (splits < max_splits && wgs_unsplit * splits < t.attn_target_wgs && min_blocks / (splits * 2) >= 1) splits *= 2;
+  auto splits_for = [&](int q_per_wg) {
+    int wgs_unsplit = 0;
+    for (int i = 0; i < n_calls; ++i) wgs_unsplit += ((calls[i].m + q_per_wg - 1) / q_per_wg) * n_heads;
+    int sp = 1;
+    while (sp < max_splits && wgs_unsplit * sp < t.attn_target_wgs && min_blocks / (sp * 2) >= 1) sp *= 2;
+    return sp;
+  };
+  int splits = splits_for(16 * shape.qt * shape.waves);
+  // 8-wave workgroups halve the K/V traffic per query and overlap two waves per SIMD, but also halve the
+  // workgroup count, i.e. double the key splits a small problem needs; with fewer than 8 blocks left per
+  // split the partial outputs (written, then merged) cost more than the loop gains (measured at 256 rows x
+  // 2048 keys x 32 heads: 43 vs 47 us per call)
+  if (shape.waves == 8 && t.attn_waves == 0 && min_blocks / splits < 8) {
+    shape.waves = 4;
+    splits = splits_for(16 * shape.qt * shape.waves);
+  }
+  const int q_per_wg = 16 * shape.qt * shape.waves;
   const float scale = 1.0f / sqrtf((float)DH);
   BatchArgs args;
   memset(&args, 0, sizeof(args));
