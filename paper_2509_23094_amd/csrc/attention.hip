@@ -36,15 +36,15 @@ __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a 
 
 // Operands of one pair of 16-key tiles (32 keys), loaded ahead of their use: per tile the K rows for S^T
 // (DH/32 fragments) and, per 64-wide head-dim block, four keys x four head-dim values of V.
-template <int DH>
+template <int DH, int NBL>
 struct KvPair {
   Frag<bf16> k[2][DH / 32];
-  u32x2 v[2][DH / 64][4];
+  u32x2 v[2][NBL][4];           // NBL 64-wide head-dim blocks of V (the workgroup's share of the output columns)
 };
 
 // Unconditional: rows past the end are clamped to the last key (their scores are masked by the consumer).
-template <int DH>
-__device__ __forceinline__ void load_kv_pair(KvPair<DH>& t, const bf16* __restrict__ kbase,
+template <int DH, int NBL>
+__device__ __forceinline__ void load_kv_pair(KvPair<DH, NBL>& t, const bf16* __restrict__ kbase,
                                              const bf16* __restrict__ vbase, size_t pitch, int key0, int L, int r,
                                              int g) {
 #pragma unroll
@@ -61,7 +61,7 @@ __device__ __forceinline__ void load_kv_pair(KvPair<DH>& t, const bf16* __restri
       const int vkey = min(key0 + a * 16 + 4 * g + e, L - 1);
       const bf16* vrow = vbase + (size_t)vkey * pitch + 4 * r;
 #pragma unroll
-      for (int b = 0; b < DH / 64; ++b) t.v[a][b][e] = ld8(vrow + b * 64);
+      for (int b = 0; b < NBL; ++b) t.v[a][b][e] = ld8(vrow + b * 64);
     }
 }
 
@@ -75,13 +75,15 @@ constexpr int kXcds = 8;          // workgroup i of a launch runs on XCD i % 8 (
 struct FwdMap {
   int mode;          // 0: plain, 1: n_kv_heads % 8 == 0, 2: 8 % n_kv_heads == 0
   int n_qt, group;   // query tiles, query heads per kv head
+  int dparts;        // workgroups that share a (query tile, head), each with its own part of the output columns
   int n_wgs;
 };
-__host__ __device__ inline FwdMap fwd_map(int m, int n_heads, int n_kv_heads) {
+__host__ __device__ inline FwdMap fwd_map(int m, int n_heads, int n_kv_heads, int dparts) {
   FwdMap f;
   f.n_qt = (m + 15) / 16;
   f.group = n_heads / n_kv_heads;
-  const int items = f.group * f.n_qt;                 // workgroups per kv head
+  f.dparts = dparts;
+  const int items = f.group * f.n_qt * dparts;        // workgroups per kv head
   if (n_kv_heads % kXcds == 0) {
     f.mode = 1;
     f.n_wgs = n_kv_heads * items;
@@ -96,9 +98,10 @@ __host__ __device__ inline FwdMap fwd_map(int m, int n_heads, int n_kv_heads) {
   return f;
 }
 // false: this workgroup has nothing to do (padding of mode 2)
-__device__ __forceinline__ bool fwd_map_decode(const FwdMap& f, int n_kv_heads, int wg, int& head, int& qt) {
+__device__ __forceinline__ bool fwd_map_decode(const FwdMap& f, int n_kv_heads, int wg, int& head, int& qt,
+                                               int& dpart) {
   int kvh, item;
-  const int items = f.group * f.n_qt;
+  const int items = f.group * f.n_qt * f.dparts;
   if (f.mode == 1) {
     const int xcd = wg % kXcds, j = wg / kXcds;
     kvh = xcd + kXcds * (j / items);
@@ -113,6 +116,8 @@ __device__ __forceinline__ bool fwd_map_decode(const FwdMap& f, int n_kv_heads, 
     kvh = wg / items;
     item = wg % items;
   }
+  dpart = item % f.dparts;
+  item /= f.dparts;
   head = kvh * f.group + item / f.n_qt;
   qt = item % f.n_qt;
   return true;
@@ -123,27 +128,32 @@ __device__ __forceinline__ bool fwd_map_decode(const FwdMap& f, int n_kv_heads, 
 // KEEP > 0: the wave also keeps the scaled scores of its first 2*KEEP pairs (all of them when
 // L <= 512*KEEP) and, once the workgroup knows the rows' log-sum-exp, writes the normalised probabilities
 // of this head to probs [H, m, L]: the head average then needs no second pass over Q and K.
-template <int DH, int KEEP>
+// DPARTS = 1 or DH / 64: with DPARTS > 1 a (query tile, head) is shared by DPARTS workgroups; each computes all
+// scores (and the same softmax) but accumulates only its 64 output columns, so it pulls all of K and only its
+// part of V through its compute unit: less per workgroup, more workgroups, nothing to merge.  Part 0 writes
+// the log-sum-exp and the probability rows.
+template <int DH, int KEEP, int DPARTS>
 __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
     const bf16* __restrict__ q, const bf16* __restrict__ k_cache, const bf16* __restrict__ v_cache, int m, int L,
     int n_heads, int n_kv_heads, float scale, bf16* __restrict__ out, float* __restrict__ lse,
     float* __restrict__ probs) {
   constexpr int NS = DH / 32;     // contraction steps of Q K^T
-  constexpr int NB = DH / 64;     // 64-wide head-dim blocks of the output
-  __shared__ float o_lds[kFwdWaves][16][DH + 1];
+  constexpr int NB = DH / 64 / DPARTS;     // 64-wide head-dim blocks of the output this workgroup owns
+  constexpr int DW = NB * 64;              // its output columns
+  __shared__ float o_lds[kFwdWaves][16][DW + 1];
   __shared__ float m_lds[kFwdWaves][16], l_lds[kFwdWaves][16], f_lds[kFwdWaves][16];
   __shared__ float lse_lds[16];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 15, g = lane >> 4;
-  int head, qt;
-  if (!fwd_map_decode(fwd_map(m, n_heads, n_kv_heads), n_kv_heads, blockIdx.x, head, qt)) return;
+  int head, qt, dpart;
+  if (!fwd_map_decode(fwd_map(m, n_heads, n_kv_heads, DPARTS), n_kv_heads, blockIdx.x, head, qt, dpart)) return;
   const int q0 = qt * 16;
   const int kvh = head / (n_heads / n_kv_heads);
   const int dq = n_heads * DH;
   const size_t kv_pitch = (size_t)n_kv_heads * DH;
   const bf16* kbase = k_cache + (size_t)kvh * DH;
-  const bf16* vbase = v_cache + (size_t)kvh * DH;
+  const bf16* vbase = v_cache + (size_t)kvh * DH + dpart * DW;
 
   Frag<bf16> qf[NS];
   {
@@ -163,7 +173,7 @@ __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
   // S^T of both tiles, one online-softmax update for the 32 keys, then O^T += V^T P^T with K = 32:
   // contraction slot (g, j) of the matrix-core step stands for key 16*(j/4) + 4g + j%4 of the pair, which
   // is how the two accumulators of S^T hold the probabilities, so P never leaves registers.
-  auto consume = [&](const KvPair<DH>& t, int key0, f32x4* keep) {
+  auto consume = [&](const KvPair<DH, NB>& t, int key0, f32x4* keep) {
     float x[2][4];
     float tmax = -INFINITY;
 #pragma unroll
@@ -224,9 +234,9 @@ __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
   // strides ahead as soon as it has been consumed.  Loads are unconditional (a pair past the end reads the
   // last key again and is never consumed), so no wait separates them.
   const int n_pairs = (L + 31) / 32;
-  KvPair<DH> ring[2];
+  KvPair<DH, NB> ring[2];
 #pragma unroll
-  for (int u = 0; u < 2; ++u) load_kv_pair<DH>(ring[u], kbase, vbase, kv_pitch, (wave + u * kFwdWaves) * 32, L, r, g);
+  for (int u = 0; u < 2; ++u) load_kv_pair<DH, NB>(ring[u], kbase, vbase, kv_pitch, (wave + u * kFwdWaves) * 32, L, r, g);
   f32x4 kept[KEEP > 0 ? 4 * KEEP : 1];
   if constexpr (KEEP > 0) {
     // all of the wave's pairs in 2*KEEP statically indexed slots (the launcher guarantees L <= 512*KEEP)
@@ -236,7 +246,7 @@ __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
       for (int u = 0; u < 2; ++u) {
         const int t = wave + (it * 2 + u) * kFwdWaves;
         if (t < n_pairs) consume(ring[u], t * 32, &kept[(it * 2 + u) * 2]);
-        if (it + 1 < KEEP) load_kv_pair<DH>(ring[u], kbase, vbase, kv_pitch, (t + 2 * kFwdWaves) * 32, L, r, g);
+        if (it + 1 < KEEP) load_kv_pair<DH, NB>(ring[u], kbase, vbase, kv_pitch, (t + 2 * kFwdWaves) * 32, L, r, g);
       }
   } else {
     for (int t0 = wave; t0 < n_pairs; t0 += 2 * kFwdWaves) {
@@ -244,7 +254,7 @@ __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
       for (int u = 0; u < 2; ++u) {
         const int t = t0 + u * kFwdWaves;
         if (t < n_pairs) consume(ring[u], t * 32, nullptr);
-        load_kv_pair<DH>(ring[u], kbase, vbase, kv_pitch, (t + 2 * kFwdWaves) * 32, L, r, g);
+        load_kv_pair<DH, NB>(ring[u], kbase, vbase, kv_pitch, (t + 2 * kFwdWaves) * 32, L, r, g);
       }
     }
   }
@@ -275,19 +285,19 @@ __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
     if (w == 0) {
       const float e = mx + __logf(lsum);
       lse_lds[qi] = e;
-      if (q0 + qi < m) lse[(size_t)head * m + q0 + qi] = e;
+      if (q0 + qi < m && dpart == 0) lse[(size_t)head * m + q0 + qi] = e;
     }
   }
   __syncthreads();
-  for (int o = tid; o < 16 * DH; o += kFwdThreads) {
-    const int qi = o / DH, dcol = o - qi * DH;
+  for (int o = tid; o < 16 * DW; o += kFwdThreads) {
+    const int qi = o / DW, dcol = o - qi * DW;
     float osum = 0.f;
 #pragma unroll
     for (int w = 0; w < kFwdWaves; ++w) osum += o_lds[w][qi][dcol] * f_lds[w][qi];
-    if (q0 + qi < m) out[(size_t)(q0 + qi) * dq + head * DH + dcol] = (bf16)osum;
+    if (q0 + qi < m) out[(size_t)(q0 + qi) * dq + head * DH + dpart * DW + dcol] = (bf16)osum;
   }
   if constexpr (KEEP > 0) {
-    if (q0 + r >= m) return;
+    if (q0 + r >= m || dpart != 0) return;
     const float e = lse_lds[r];
     float* prow = probs + ((size_t)head * m + q0 + r) * L;
 #pragma unroll
@@ -461,14 +471,25 @@ template <int DH>
 hipError_t launch_fwd_bf16(const void* q, const void* k_cache, const void* v_cache, int m, int L, int n_heads,
                            int n_kv_heads, void* out, float* lse, float* probs, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)DH);
-  const dim3 grid(fwd_map(m, n_heads, n_kv_heads).n_wgs);
-#define D2C_FWD(KEEP_)                                                                                          \
-  hipLaunchKernelGGL((attn_fwd_bf16_kernel<DH, KEEP_>), grid, dim3(kFwdThreads), 0, st, (const bf16*)q,         \
-                     (const bf16*)k_cache, (const bf16*)v_cache, m, L, n_heads, n_kv_heads, scale, (bf16*)out, \
-                     lse, probs)
-  if (!probs) D2C_FWD(0);
-  else if (L <= 512) D2C_FWD(1);
-  else if (L <= 1024) D2C_FWD(2);
+  // split the output columns over two workgroups when that still fits one round of workgroups on the chip
+  constexpr int kUnits = 256;
+  const bool split = DH == 128 && fwd_map(m, n_heads, n_kv_heads, 2).n_wgs <= kUnits;
+#define D2C_FWD(KEEP_, DP_)                                                                                     \
+  hipLaunchKernelGGL((attn_fwd_bf16_kernel<DH, KEEP_, DP_>), dim3(fwd_map(m, n_heads, n_kv_heads, DP_).n_wgs),  \
+                     dim3(kFwdThreads), 0, st, (const bf16*)q, (const bf16*)k_cache, (const bf16*)v_cache, m, L, \
+                     n_heads, n_kv_heads, scale, (bf16*)out, lse, probs)
+  if constexpr (DH == 128) {
+    if (split) {
+      if (!probs) D2C_FWD(0, 2);
+      else if (L <= 512) D2C_FWD(1, 2);
+      else if (L <= 1024) D2C_FWD(2, 2);
+      else return hipErrorInvalidValue;
+      return hipGetLastError();
+    }
+  }
+  if (!probs) D2C_FWD(0, 1);
+  else if (L <= 512) D2C_FWD(1, 1);
+  else if (L <= 1024) D2C_FWD(2, 1);
   else return hipErrorInvalidValue;
 #undef D2C_FWD
   return hipGetLastError();
