@@ -296,7 +296,7 @@ int layer_impl(d2c_ctx* c, int layer, float* hidden, const Seg* segs, int n_seg,
     void* qb = q + (size_t)g.off * dq * ts;
     void* ob = (char*)c->attn_o + (size_t)g.off * dq * ts;
     float* lb = lse + (size_t)D.n_heads * g.off;
-    if (attention_is_tiled(c->tun, dt, g.m)) {
+    if (attention_is_tiled(c->tun, dt, g.m, g.L)) {
       tiled.push_back(TiledCall{qb, g.k_cache, g.v_cache, g.m, g.L, ob, lb, g.abar});
       tiled_bytes += 2.0 * g.L * dkv * ts;
       if ((int)tiled.size() == attention_tiled_max_batch() && (rc = flush_tiled())) return rc;
@@ -311,7 +311,7 @@ int layer_impl(d2c_ctx* c, int layer, float* hidden, const Seg* segs, int n_seg,
   bool any_side = false;
   for (int b = 0; b < n_seg; ++b)
     any_side = any_side || (segs[b].m > 0 && segs[b].abar &&
-                            (!attention_is_tiled(c->tun, dt, segs[b].m) || segs[b].roll_out));
+                            (!attention_is_tiled(c->tun, dt, segs[b].m, segs[b].L) || segs[b].roll_out));
   if (record_fwd && !any_side && side != st) D2C_HIP(c, hipEventRecord(c->fwd_done[layer], st));
   if (any_side) {
     if (side != st) {
@@ -321,7 +321,7 @@ int layer_impl(d2c_ctx* c, int layer, float* hidden, const Seg* segs, int n_seg,
     for (int b = 0; b < n_seg; ++b) {
       const Seg& g = segs[b];
       if (g.m <= 0 || !g.abar) continue;
-      if (!attention_is_tiled(c->tun, dt, g.m))
+      if (!attention_is_tiled(c->tun, dt, g.m, g.L))
         D2C_TIMED(c, side, D2C_PROF_ATTN_AVG, 0.0,
                   launch_attention_avg(c->tun, dt, q + (size_t)g.off * dq * ts, g.k_cache, lse + (size_t)D.n_heads * g.off,
                                        g.m, g.L, D.n_heads, D.n_kv_heads, D.head_dim, g.abar, side));
@@ -698,7 +698,7 @@ int d2c_attention(d2c_ctx* c, const void* q, const int32_t* idx, int32_t m, cons
   if (new_k) {
     D2C_HIP(c, launch_scatter_rows(D.dtype, new_k, k_cache, new_v, v_cache, idx, m, d_kv(c), st));
   }
-  const bool tiled = attention_is_tiled(c->tun, D.dtype, m);
+  const bool tiled = attention_is_tiled(c->tun, D.dtype, m, L);
   D2C_TIMED(c, st, D2C_PROF_ATTENTION, 2.0 * L * d_kv(c) * tsize(c),
             launch_attention_fwd(c->tun, D.dtype, q, k_cache, v_cache, m, L, D.n_heads, D.n_kv_heads, D.head_dim, out, c->lse,
                                  c->attn_part, c->attn_part_floats, st, nullptr, tiled ? attn_avg : nullptr));

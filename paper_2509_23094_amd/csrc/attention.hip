@@ -510,7 +510,7 @@ hipError_t launch_avg_bf16(const void* q, const void* k_cache, const float* lse,
 constexpr int kProbsMaxM = 128, kProbsMaxL = 1024;
 
 bool attention_fwd_emits_probs(const Tunables& t, int dtype, int m, int L) {
-  return dtype == kBF16 && m > 0 && m < t.attn_tiled_min_m && m <= kProbsMaxM && L <= kProbsMaxL;
+  return dtype == kBF16 && m > 0 && !attention_is_tiled(t, dtype, m, L) && m <= kProbsMaxM && L <= kProbsMaxL;
 }
 
 size_t attention_probs_floats(int dtype, int n_heads, int max_L) {
@@ -531,7 +531,12 @@ size_t attention_scratch_floats(const Tunables& t, int dtype, int max_m, int max
   return dtype == kBF16 ? attention_tiled_scratch_floats(t, max_m, max_L, n_heads, head_dim) : 0;
 }
 
-bool attention_is_tiled(const Tunables& t, int dtype, int m) { return dtype == kBF16 && m >= t.attn_tiled_min_m; }
+// From kLongMinM rows on the tiled kernels also take the key ranges too long for the per-head probability
+// rows: there the few-row kernels would need their second Q K^T launch for the head average.
+constexpr int kLongMinM = 48;
+bool attention_is_tiled(const Tunables& t, int dtype, int m, int L) {
+  return dtype == kBF16 && (m >= t.attn_tiled_min_m || (m >= std::min(kLongMinM, t.attn_tiled_min_m) && L > kProbsMaxL));
+}
 
 hipError_t launch_attention_fwd(const Tunables& t, int dtype, const void* q, const void* k_cache, const void* v_cache, int m, int L,
                                 int n_heads, int n_kv_heads, int head_dim, void* out, float* lse, float* scratch,
@@ -539,7 +544,7 @@ hipError_t launch_attention_fwd(const Tunables& t, int dtype, const void* q, con
   if (m <= 0) return hipSuccess;
   if (L <= 0 || n_heads % n_kv_heads) return hipErrorInvalidValue;
   if (probs && !attention_fwd_emits_probs(t, dtype, m, L)) return hipErrorInvalidValue;
-  if (attention_is_tiled(t, dtype, m)) {
+  if (attention_is_tiled(t, dtype, m, L)) {
     const TiledCall call{q, k_cache, v_cache, m, L, out, lse, tiled_avg};
     return launch_attention_tiled(t, &call, 1, n_heads, n_kv_heads, head_dim, scratch, scratch_floats, st);
   }
@@ -561,7 +566,7 @@ hipError_t launch_attention_fwd(const Tunables& t, int dtype, const void* q, con
 hipError_t launch_attention_avg(const Tunables& t, int dtype, const void* q, const void* k_cache, const float* lse, int m, int L,
                                 int n_heads, int n_kv_heads, int head_dim, float* attn_avg, hipStream_t st) {
   if (m <= 0) return hipSuccess;
-  if (L <= 0 || n_heads % n_kv_heads || attention_is_tiled(t, dtype, m)) return hipErrorInvalidValue;
+  if (L <= 0 || n_heads % n_kv_heads || attention_is_tiled(t, dtype, m, L)) return hipErrorInvalidValue;
   if (dtype == kBF16) {
     if (head_dim == 128) return launch_avg_bf16<128>(q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, st);
     if (head_dim == 64) return launch_avg_bf16<64>(q, k_cache, lse, m, L, n_heads, n_kv_heads, attn_avg, st);

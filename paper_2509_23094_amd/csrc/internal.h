@@ -100,12 +100,13 @@ hipError_t launch_rope_table(float* cos_t, float* sin_t, int max_pos, int head_d
 // Two kernel families.  Few query rows (fp32, or bf16 below attn_tiled_min_m rows): a forward launch and, for
 // the head average, either per-head probability rows written by the forward launch itself (probs, see
 // attention_fwd_emits_probs) or a second launch (launch_attention_avg) that needs the forward's lse.  Many
-// rows in bf16 (attention_is_tiled): K/V blocks staged through LDS, key range split over workgroups; the
+// rows in bf16 (attention_is_tiled: attn_tiled_min_m rows, or 48 already when the key range is too long
+// for the probability rows): K/V blocks staged through LDS, key range split over workgroups; the
 // forward launch also leaves what the head average needs, and one finishing launch merges the splits and
 // writes the average, so tiled_avg is given to launch_attention_fwd itself.
 // fwd: out T [m, H*dh] and the log-sum-exp per (head, row), lse float [H, m]
 // scratch: attention_scratch_floats(...) floats, may be null for fp32
-bool attention_is_tiled(const Tunables& t, int dtype, int m);
+bool attention_is_tiled(const Tunables& t, int dtype, int m, int L);
 size_t attention_scratch_floats(const Tunables& t, int dtype, int max_m, int max_L, int n_heads, int head_dim);
 // probs (optional, only where attention_fwd_emits_probs): float [H, m, L], the normalised attention rows of
 // every head, written by the same launch; launch_head_mean turns them into the head average.

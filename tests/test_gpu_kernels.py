@@ -66,7 +66,8 @@ def test_linear_parity_every_workgroup_width(B, waves, dtype, m, N, K):
 
 # ------------------------------------------------------------------ attention (config "C2" and edge shapes)
 ATTN_CASES = [
-    # dtype, H, Hkv, dh, L, m, kernels ("few": the few-row kernels, "tiled": the LDS-tiled ones, "": fp32)
+    # dtype, H, Hkv, dh, L, m, kernels ("few": the few-row kernels, "tiled": the LDS-tiled ones, "default":
+    # the library's own choice, "": fp32)
     ("bf16", 32, 32, 128, 2048, 256, "tiled"),    # the isolated selective-refresh attention workload, full size
     ("bf16", 32, 32, 128, 2048, 256, "few"),
     ("bf16", 28, 4, 128, 768, 83, "few"),         # Dream geometry (GQA 28/4), ragged m
@@ -83,6 +84,9 @@ ATTN_CASES = [
     ("bf16", 16, 2, 128, 600, 50, "few"),         # 4 XCDs per kv head, 8 query heads each; L above 512
     ("bf16", 32, 32, 128, 512, 46, "few"),        # the LLaDA-8B decode step: 96 (tile, head) pairs
     ("bf16", 5, 5, 128, 300, 16, "few"),          # 5 kv heads: plain placement
+    ("bf16", 28, 4, 128, 1824, 93, "default"),    # the long-generation decode step late on: too long for the
+                                                  # per-head probability rows, so the tiled kernels from 48 rows on
+    ("bf16", 28, 4, 128, 1824, 40, "default"),    # same length, fewer rows: few-row kernels and their second launch
     ("f32", 4, 4, 64, 128, 73, ""),               # the small fp32 model's geometry
     ("f32", 4, 2, 8, 19, 5, ""),
 ]
@@ -91,7 +95,7 @@ ATTN_CASES = [
 @pytest.mark.parametrize("dtype,H,Hkv,dh,L,m,kernels", ATTN_CASES)
 def test_attention_parity(B, dtype, H, Hkv, dh, L, m, kernels):
     say(f"attention dtype={dtype} H={H} Hkv={Hkv} dh={dh} L={L} m={m} kernels={kernels}")
-    tun = {"attn_tiled_min_m": 1 if kernels == "tiled" else 1 << 30} if kernels else None
+    tun = {"attn_tiled_min_m": 1 if kernels == "tiled" else 1 << 30} if kernels in ("tiled", "few") else None
     _attention_parity(B, dtype, H, Hkv, dh, L, m, tunables=tun)
 
 
