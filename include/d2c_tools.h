@@ -35,6 +35,7 @@ int d2c_profile_end(d2c_ctx* ctx, double* ms, int64_t* launches, double* bytes);
  * projection kernel: "gemm_waves" (waves per workgroup: 4, 6, 8, 10; 0 = chosen by shape together with the
  * split count), "gemm_max_splits" (1..8), "gemm_target_wgs" (workgroups aimed at where the shape search does
  * not apply), "gemm_nt_big_n", "gemm_wide_tiles" (0/1: 128 x 64 outputs per wave for many bf16 rows),
+ * "gemm_wide_mt" (6, 7, 8 row tiles per workgroup of that shape; 0 = by shape),
  * "gemm_wide_min_rows" (that instantiation from this many rows on), "gemm_tall_chunk" (0/1: 129-192 bf16 rows
  * as one row chunk), "gemm_preshuffle" (0/1: pre-tiled weight copies; only at d2c_init_tuned), "gemm_rot";
  * attention: "attn_tiled_min_m" (bf16 attention switches to the LDS-tiled kernels from this many query rows

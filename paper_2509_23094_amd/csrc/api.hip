@@ -21,6 +21,7 @@ bool d2c::set_tunable(Tunables& t, const char* name, int value) {
   else if (!strcmp(name, "gemm_max_splits")) t.gemm_max_splits = std::max(1, std::min(8, value));
   else if (!strcmp(name, "gemm_nt_big_n")) t.gemm_nt_big_n = value;
   else if (!strcmp(name, "gemm_wide_tiles")) t.gemm_wide_tiles = value;
+  else if (!strcmp(name, "gemm_wide_mt")) t.gemm_wide_mt = (value >= 6 && value <= 8) ? value : 0;
   else if (!strcmp(name, "gemm_wide_min_rows")) t.gemm_wide_min_rows = value;
   else if (!strcmp(name, "gemm_tall_chunk")) t.gemm_tall_chunk = value;
   else if (!strcmp(name, "gemm_waves")) t.gemm_waves = (value == 8 || value == 4 || value == 6 || value == 10) ? value : 0;

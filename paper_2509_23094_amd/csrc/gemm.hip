@@ -374,8 +374,11 @@ hipError_t launch_nt(const GemmPlan& pl, const void* A, int lda, const void* W, 
     // 128 rows x 64 columns per wave, one wave per SIMD: only for full row chunks in bf16
     if constexpr (sizeof(T) == 2) {
       const int kc = 256 / (int)sizeof(T);
-      if (pl.mt == 8 && pl.waves == 4 && K % kc == 0 && pl.k_per_split % (2 * kc) == 0 && K % (2 * kc) == 0)
-        return launch_t<T, 8, 4, 4, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+      if (pl.waves == 4 && K % kc == 0 && pl.k_per_split % (2 * kc) == 0 && K % (2 * kc) == 0) {
+        if (pl.mt == 8) return launch_t<T, 8, 4, 4, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+        if (pl.mt == 7) return launch_t<T, 7, 4, 4, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+        if (pl.mt == 6) return launch_t<T, 6, 4, 4, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+      }
     }
     return hipErrorInvalidValue;
   }
@@ -470,9 +473,31 @@ GemmPlan plan_gemm(const Tunables& t, int dtype, int m, int N, int K, bool singl
       }
     }
   }
+  if (wide) {
+    // Rows per workgroup: 8 row tiles unless fewer do the same job better.  Measured at the LLaDA widths,
+    // 288-2048 rows: (a) fewer tiles in the SAME number of row chunks are always a gain (less matrix-core and
+    // LDS work per weight pull: 288 rows as 3 x 6 tiles -14 %); (b) MORE row chunks gain only when their count
+    // becomes a multiple of 8, the rows of the block of workgroups that shares an XCD's L2 (700 rows as
+    // 8 x 6 tiles instead of 6 x 8: -16 %; 856 rows as 8 x 7 instead of 7 x 8: -7 %; 1500 rows as 16 x 6
+    // instead of 12 x 8: -7 %), every other count lost 10-40 %.
+    const int rc8 = (tiles + 7) / 8;
+    int mt = 8;
+    if (t.gemm_wide_mt != 0) {
+      mt = t.gemm_wide_mt;
+    } else {
+      if (rc8 % kSuperRows != 0)
+        for (int c : {7, 6})
+          if (mt == 8 && ((tiles + c - 1) / c) % kSuperRows == 0) mt = c;
+      if (mt == 8)
+        for (int c : {6, 7})
+          if (mt == 8 && (tiles + c - 1) / c == rc8) mt = c;
+    }
+    pl.mt = mt;
+    pl.row_chunks = (tiles + mt - 1) / mt;
+  }
   if (wide && !single_split) {
-    // Many rows: the same count of rounds, with +7 % per additional split (the partials are as large as
-    // the output and there are hundreds of rows of them)
+    // the same count of rounds, with +7 % per additional split (the partials are as large as the output and
+    // there are hundreds of rows of them)
     double best = 1e30;
     for (int s = 1; s <= max_splits; s *= 2) {
       int cps = (chunks + s - 1) / s;

@@ -18,6 +18,7 @@ struct Tunables {
   int gemm_wide_min_rows = 257; // the wide instantiation from this many rows on (3 row chunks)
   int gemm_tall_chunk = 1;      // 129-192 bf16 rows as ONE row chunk of 10 or 12 row tiles
   int gemm_wide_tiles = 1;     // more than 128 rows in bf16: 128 x 64 outputs per wave, 4 waves per workgroup
+  int gemm_wide_mt = 0;        // row tiles per workgroup of the wide instantiation: 6, 7, 8; 0 = by shape
   int gemm_nt_big_n = 1 << 30; // N above this uses two column tiles per wave even for few rows (measured slower);
                                // more than 128 rows always do
   int gemm_waves = 0;          // waves per workgroup sharing one activation chunk in LDS: 4, 6, 8, 10; 0 = by shape

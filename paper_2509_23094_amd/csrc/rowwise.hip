@@ -12,6 +12,7 @@ namespace d2c {
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kManyRows = 256;       // from this many rows on a launch is bound by throughput, not by one memory latency
 
 // Sum over the workgroup, same value in every thread, fixed order.
 __device__ __forceinline__ float block_sum(float v, float* red) {
@@ -75,35 +76,49 @@ __device__ __forceinline__ void store4(bf16* dst, const f32x4& v) {
   *reinterpret_cast<bf16x4*>(dst) = o;
 }
 
-// Same as add_norm_kernel for d <= 4*THREADS, d % 4 == 0: one 16-byte piece of the row per thread, kept in
-// registers; a thread's loads (the row piece and one piece per split) are all independent, and a
-// 4096-wide row is spread over 16 waves, so the kernel is about one memory latency long.
-template <typename T, int THREADS>
+// Same as add_norm_kernel for d <= 4*THREADS*PIECES, d % 4 == 0: PIECES 16-byte pieces of the row per thread,
+// kept in registers; a thread's loads (the row pieces and one piece per split) are all independent.  With one
+// piece per thread a 4096-wide row is spread over 16 waves and the kernel is about one memory latency long (a
+// handful of rows); with four pieces per thread more rows are resident per compute unit, which is what many
+// rows need.
+template <typename T, int THREADS, int PIECES>
 __global__ __launch_bounds__(THREADS) void add_norm_vec_kernel(float* __restrict__ h, const float* __restrict__ P,
                                                                int n_splits, size_t split_stride, int ldp, int d,
                                                                const float* __restrict__ gain, float eps,
                                                                T* __restrict__ a) {
   __shared__ float red[THREADS / 64];
   const int r = blockIdx.x;
-  const int c = threadIdx.x * 4;
-  const bool live = c < d;
   float* hr = h + (size_t)r * d;
   const float* pr = P + (size_t)r * ldp;
-  f32x4 v = {0.f, 0.f, 0.f, 0.f};
-  if (live) {
-    v = *reinterpret_cast<const f32x4*>(hr + c);
-    if (n_splits > 0) {
+  f32x4 v[PIECES];
+#pragma unroll
+  for (int p = 0; p < PIECES; ++p) {
+    const int c = (threadIdx.x + p * THREADS) * 4;
+    v[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (c < d) v[p] = *reinterpret_cast<const f32x4*>(hr + c);
+  }
+  if (n_splits > 0) {
+#pragma unroll
+    for (int p = 0; p < PIECES; ++p) {
+      const int c = (threadIdx.x + p * THREADS) * 4;
+      if (c >= d) continue;
       f32x4 add = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 8
       for (int s = 0; s < n_splits; ++s) add += *reinterpret_cast<const f32x4*>(pr + (size_t)s * split_stride + c);
-      v += add;
-      store4(hr + c, v);
+      v[p] += add;
+      store4(hr + c, v[p]);
     }
   }
   if (a == nullptr) return;
-  const float ss = v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  float ss = 0.f;
+#pragma unroll
+  for (int p = 0; p < PIECES; ++p) ss += v[p].x * v[p].x + v[p].y * v[p].y + v[p].z * v[p].z + v[p].w * v[p].w;
   const float inv = 1.0f / sqrtf(block_sum(ss, red) / (float)d + eps);
-  if (live) store4(a + (size_t)r * d + c, v * inv * *reinterpret_cast<const f32x4*>(gain + c));
+#pragma unroll
+  for (int p = 0; p < PIECES; ++p) {
+    const int c = (threadIdx.x + p * THREADS) * 4;
+    if (c < d) store4(a + (size_t)r * d + c, v[p] * inv * *reinterpret_cast<const f32x4*>(gain + c));
+  }
 }
 
 template <typename T>
@@ -311,19 +326,20 @@ hipError_t launch_add_norm(int dtype, float* h, const float* P, int n_splits, si
                            int d, const float* gain, float eps, void* a, hipStream_t st) {
   if (m <= 0) return hipSuccess;
   if (d % 4 == 0 && d <= 4096 && ldp % 4 == 0 && split_stride % 4 == 0) {
-    if (d > 1024) {
-      D2C_DISPATCH(dtype,
-                   hipLaunchKernelGGL((add_norm_vec_kernel<bf16, 1024>), dim3(m), dim3(1024), 0, st, h, P, n_splits,
-                                      split_stride, ldp, d, gain, eps, (bf16*)a),
-                   hipLaunchKernelGGL((add_norm_vec_kernel<float, 1024>), dim3(m), dim3(1024), 0, st, h, P, n_splits,
-                                      split_stride, ldp, d, gain, eps, (float*)a));
+#define D2C_ADD_NORM_VEC(THREADS, PIECES)                                                                          \
+  D2C_DISPATCH(dtype,                                                                                             \
+               hipLaunchKernelGGL((add_norm_vec_kernel<bf16, THREADS, PIECES>), dim3(m), dim3(THREADS), 0, st, h, P,   \
+                                  n_splits, split_stride, ldp, d, gain, eps, (bf16*)a),                           \
+               hipLaunchKernelGGL((add_norm_vec_kernel<float, THREADS, PIECES>), dim3(m), dim3(THREADS), 0, st, h, P,  \
+                                  n_splits, split_stride, ldp, d, gain, eps, (float*)a))
+    if (d <= 1024) {
+      D2C_ADD_NORM_VEC(256, 1);
+    } else if (m >= kManyRows) {
+      D2C_ADD_NORM_VEC(256, 4);
     } else {
-      D2C_DISPATCH(dtype,
-                   hipLaunchKernelGGL((add_norm_vec_kernel<bf16, 256>), dim3(m), dim3(256), 0, st, h, P, n_splits,
-                                      split_stride, ldp, d, gain, eps, (bf16*)a),
-                   hipLaunchKernelGGL((add_norm_vec_kernel<float, 256>), dim3(m), dim3(256), 0, st, h, P, n_splits,
-                                      split_stride, ldp, d, gain, eps, (float*)a));
+      D2C_ADD_NORM_VEC(1024, 1);
     }
+#undef D2C_ADD_NORM_VEC
     return hipGetLastError();
   }
   D2C_DISPATCH(dtype,

@@ -154,8 +154,8 @@ LAYER_CASES = [
     ("bf16-185-rows", W.ModelDims(1, 512, 4, 4, 128, 1408, 64, dtype="bf16"), 260, 185),   # 12 row tiles in one chunk
     ("C3-width", W.DIMS["C3"], 512, 83),     # one LLaDA-8B-shaped layer at full width
     ("C4-width", W.DIMS["C4"], 768, 100),    # one Dream-7B-shaped layer at full width
-
-
+    # more than 256 rows: 128 x 64 outputs per wave in every projection (all widths are whole chunk pairs)
+    ("bf16-330-rows", W.ModelDims(1, 512, 4, 4, 128, 1536, 64, dtype="bf16"), 400, 330),
     ("tiny-f32-odd-ffn", W.ModelDims(1, 64, 4, 4, 16, 72, 64, dtype="f32"), 40, 9),   # FFN width not a multiple of 16
 ]
 # the same block with the caller's row-major weights (no pre-tiled copies, separate SwiGLU launch)
@@ -180,6 +180,13 @@ def test_refresh_layer_parity_forced_workgroup_width(B, name, waves):
     the planner would not pick them by itself."""
     case = [c for c in LAYER_CASES if c[0] == name][0]
     _refresh_layer_parity(B, *case, tunables={"gemm_waves": waves})
+
+
+@pytest.mark.parametrize("mt", [6, 7, 8])
+def test_refresh_layer_parity_forced_rows_per_workgroup(B, mt):
+    """Many rows: 6, 7 or 8 row tiles per workgroup of the wide projection shape, whatever the planner's choice."""
+    case = [c for c in LAYER_CASES if c[0] == "bf16-330-rows"][0]
+    _refresh_layer_parity(B, *case, tunables={"gemm_wide_mt": mt})
 
 
 def _refresh_layer_parity(B, name, wd, L, m, tunables=None):
