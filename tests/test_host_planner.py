@@ -40,15 +40,27 @@ def test_plan_covers_rows_and_contraction_and_keeps_the_kernel_assumptions(dtype
         cols = 16 * p["col_tiles_per_wave"] * p["waves"]
         assert p["workgroups"] == -(-N // cols) * p["splits"] * p["row_chunks"], where
         if p["col_tiles_per_wave"] == 4:
-            # the hand-pipelined loop for many rows: bf16, full 8-tile row chunks, 4 waves, chunks taken in pairs
-            assert dtype == "bf16" and p["row_tiles"] == 8 and p["waves"] == 4 and m >= 257, where
+            # the hand-pipelined loop for many rows: bf16, 6-8 row tiles per chunk, 4 waves, chunks taken in pairs
+            assert dtype == "bf16" and p["row_tiles"] in (6, 7, 8) and p["waves"] == 4 and m >= 257, where
             assert K % 256 == 0 and p["k_per_split"] % 256 == 0, where
+            # fewer than 8 tiles only with as many row chunks as 8 tiles need, or with whole blocks of 8 chunks
+            tiles = -(-m // 16)
+            assert p["row_tiles"] == 8 or p["row_chunks"] == -(-tiles // 8) or p["row_chunks"] % 8 == 0, where
         if p["row_tiles"] > 8:
             # the tall single chunk: bf16 only, even tile counts up to 12, 8 waves, one column tile per wave
             assert dtype == "bf16" and p["row_tiles"] in (10, 12) and p["row_chunks"] == 1, where
             assert p["waves"] == 8 and p["col_tiles_per_wave"] == 1 and 129 <= m <= 192, where
         if p["row_chunks"] == 1 and p["row_tiles"] <= 8:
             assert p["row_tiles"] == -(-m // 16), where
+
+
+def test_plan_rows_per_workgroup_for_many_rows():
+    """The measured cases of the rows-per-workgroup rule (LLaDA widths)."""
+    for m, tiles, chunks in ((288, 6, 3), (400, 7, 4), (512, 8, 4), (700, 6, 8), (856, 7, 8), (1000, 8, 8),
+                             (1100, 8, 9), (1500, 6, 16), (2048, 8, 16), (12288, 8, 96)):
+        for (N, K) in ((12288, 4096), (4096, 12288)):
+            p = _plan("bf16", m, N, K)
+            assert (p["row_tiles"], p["row_chunks"]) == (tiles, chunks), (m, N, K, p)
 
 
 def test_plan_at_the_benchmark_shapes():
@@ -69,7 +81,7 @@ def test_plan_at_the_benchmark_shapes():
     p = _plan("bf16", 200, 12288, 4096)
     assert (p["row_chunks"], p["col_tiles_per_wave"]) == (2, 2)
     p = _plan("bf16", 856, 12288, 4096)
-    assert (p["row_chunks"], p["col_tiles_per_wave"], p["waves"]) == (7, 4, 4)
+    assert (p["row_tiles"], p["row_chunks"], p["col_tiles_per_wave"], p["waves"]) == (7, 8, 4, 4)
     p = _plan("f32", 856, 768, 256)
     assert p["col_tiles_per_wave"] == 2 and p["row_chunks"] == 7
 
