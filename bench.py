@@ -212,7 +212,7 @@ def bench_attention_op(args, B, W, torch, np, tune=None):
         wall = time.perf_counter() - t0
         us = 1e3 * e0.elapsed_time(e1) / K
         by = base_bytes + (4 * m * L if ab is not None else 0)
-        # the head average recomputes Q K^T in a second pass: those flops are overhead, not counted
+        # the head average comes out of the forward pass (unnormalised probabilities kept per key block): no extra flops
         res[name] = {"us_per_call": round(us, 2), "wall_us_per_call": round(1e6 * wall / K, 2),
                      "tflops": round(flops / us / 1e6, 1), "mfma_frac": round(flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
                      "gbs": round(by / us / 1e3, 1), "hbm_frac": round(by / us / 1e3 / HBM_PEAK_GBS, 4)}

@@ -3,23 +3,28 @@
 // heads of the normalised attention rows (A^(l) in R^{H x |y*| x L} averaged over
 // heads, Sec. 4.2 of the d2Cache paper), which the rollout (Eq. 6-8) consumes.
 //
-// bf16 path, two launches, no atomics (bit-reproducible):
-//   pass 1  one workgroup per (16-query tile, head), placed so that the readers of
-//           one kv head share an L2; its 8 waves take 32-key pairs of tiles
-//           round-robin (the next pair's loads in flight while one is consumed), run
-//           an online softmax each and merge through LDS.  Scores are
-//           computed transposed, S^T = K Q^T, so that the 16x16 accumulator layout
-//           (4 consecutive keys per lane for one query), taken for both tiles of a
-//           pair, IS the B operand of the 16x16x32 matrix-core step of
-//           O^T = V^T P^T: P never leaves registers.
-//           V rows are read straight from global memory (8 bytes = 4 head-dim
-//           values per lane and key) and 4x4 in-register transposes turn them
-//           into the A operand (4+4 keys per lane for one head-dim value).
-//           Writes O (bf16) and the log-sum-exp per (head, row).
-//   pass 2  one workgroup per (16-query tile, 16-key tile); its 4 waves split the
-//           heads, recompute S^T and accumulate exp(s - lse) in registers, then add
-//           their partial sums in a fixed order through LDS.
-// fp32 path (small test model only): the same two passes, one workgroup per query row, plain FMA.
+// This file: the kernels for FEW query rows in bf16 and the fp32 path; the LDS-tiled kernels for many rows
+// are in attention_tiled.hip.  No atomics anywhere (bit-reproducible).
+//   forward   one workgroup per (16-query tile, head, part of the output columns), placed so that the
+//             readers of one kv head share an L2; its 8 waves take 32-key pairs of tiles
+//             round-robin (the next pair's loads in flight while one is consumed), run
+//             an online softmax each and merge through LDS.  Scores are
+//             computed transposed, S^T = K Q^T, so that the 16x16 accumulator layout
+//             (4 consecutive keys per lane for one query), taken for both tiles of a
+//             pair, IS the B operand of the 16x16x32 matrix-core step of
+//             O^T = V^T P^T: P never leaves registers.
+//             V rows are read straight from global memory (8 bytes = 4 head-dim
+//             values per lane and key) and 4x4 in-register transposes turn them
+//             into the A operand (4+4 keys per lane for one head-dim value).
+//             Writes O (bf16), the log-sum-exp per (head, row) and, up to 1024 keys, the
+//             normalised probability rows of its head (the waves keep their scaled scores
+//             in registers until the row's log-sum-exp is known).
+//   head mean one launch per step: A-bar of every layer = mean over the heads of those rows.
+//   second pass (more than 1024 keys and too few rows for the tiled kernels): one workgroup per
+//             (16-query tile, 16-key tile); its 4 waves split the heads, recompute S^T and
+//             accumulate exp(s - lse) in registers, then add their partial sums in a fixed
+//             order through LDS.
+// fp32 path (small test model only): forward and second pass, one workgroup per query row, plain FMA.
 #include <algorithm>
 
 #include "common.h"
@@ -305,8 +310,9 @@ __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
       const int key0 = (wave + (o >> 1) * kFwdWaves) * 32 + (o & 1) * 16 + 4 * g;
       if ((L & 3) == 0) {                       // rows start 16-byte aligned: one store per tile
         if (key0 < L)
-          *reinterpret_cast<f32x4*>(prow + key0) = f32x4{__expf(kept[o][0] - e), __expf(kept[o][1] - e),
-                                                         __expf(kept[o][2] - e), __expf(kept[o][3] - e)};
+          __builtin_nontemporal_store(f32x4{__expf(kept[o][0] - e), __expf(kept[o][1] - e), __expf(kept[o][2] - e),
+                                            __expf(kept[o][3] - e)},
+                                      reinterpret_cast<f32x4*>(prow + key0));
       } else {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -324,7 +330,7 @@ __global__ __launch_bounds__(kThreads) void head_mean_kernel(const float* __rest
   if (i >= n_elems) return;
   const float* p = probs + (size_t)blockIdx.y * probs_layer_stride + i;
   float sum = 0.f;
-  for (int h = 0; h < n_heads; ++h) sum += p[(size_t)h * n_elems];
+  for (int h = 0; h < n_heads; ++h) sum += __builtin_nontemporal_load(p + (size_t)h * n_elems);   // read once
   abar[(size_t)blockIdx.y * abar_layer_stride + i] = sum * (1.0f / (float)n_heads);
 }
 

@@ -138,6 +138,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_rows_kernel(
       *reinterpret_cast<u32x4*>(&lds[buf][(f >> 4) * kRowStride + (f & 15) * 16]) = a[i].raw;
     }
   };
+  // One column tile per wave means one row chunk: every weight byte is read by exactly one workgroup of the
+  // launch, so its loads carry the streaming hint and leave the L2 to the activations and partial sums.
+  auto ldw16 = [](const T* p) {
+    if constexpr (NT == 1) return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    else return ld16(p);
+  };
   auto load_b = [&](Frag<T> (&b)[NT][kSteps], int chunk) {
     const int kc = chunk_k(chunk);
     if (PRE) {
@@ -146,13 +152,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_rows_kernel(
 #pragma unroll
       for (int s = 0; s < kSteps; ++s)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) b[nt][s].raw = ld16(wrow[nt] + off + s * 64 * E);
+        for (int nt = 0; nt < NT; ++nt) b[nt][s].raw = ldw16(wrow[nt] + off + s * 64 * E);
     } else {
 #pragma unroll
       for (int s = 0; s < kSteps; ++s) {
         const int k = min(kc + s * KS + g * E, k_end - E);
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) b[nt][s].raw = ld16(wrow[nt] + k);
+        for (int nt = 0; nt < NT; ++nt) b[nt][s].raw = ldw16(wrow[nt] + k);
       }
     }
   };
