@@ -12,7 +12,8 @@ roofline = algorithmic weight bytes of the projection launches / their HIP-event
 (a second pass over the same steps with an event pair around every launch), against 8 TB/s;
 full_recompute = the same engine with every row selected; generation = one whole generation timed
 from before step 0 to the last token (generated tokens per second); cpu_baseline = the CPU oracle on a
-bounded sample of the same workload.  --workload C4 / C5 / C6 / C2 / select run the other configurations.
+bounded sample of the same workload.  --workload C4 / C5 / C6 / C2 / select / parallel run the other
+configurations; memory = device bytes the library holds beside the caller's buffers.
 """
 import argparse
 import json

@@ -42,6 +42,9 @@ the HIP path takes too):
       (equal to M* u U whenever I_t is inside M*, i.e. without R15/R16).
   R18 lightweight rollout (appendix, "lightweight variants of attention
       rollout"): only the first r layers' A-bar enter Eq. 6-8.
+  R19 blocks are counted from the end of the prompt by floor division; a masked
+      position left of prompt_len (legal input, never produced by the method)
+      falls into a block that is clipped at position 0.
 
 Parity status: every function below is pinned by tests/test_oracle_*.py to
 closed forms, invariants, library witnesses or brute force.  Agreement with the
