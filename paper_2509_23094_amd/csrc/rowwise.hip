@@ -121,6 +121,36 @@ __global__ __launch_bounds__(THREADS) void add_norm_vec_kernel(float* __restrict
   }
 }
 
+// Four consecutive elements of a row of T as floats (the row start and c are multiples of 4 elements).
+__device__ __forceinline__ f32x4 load4(const float* p) { return *reinterpret_cast<const f32x4*>(p); }
+__device__ __forceinline__ f32x4 load4(const bf16* p) {
+  const bf16x4 v = *reinterpret_cast<const bf16x4*>(p);
+  return f32x4{(float)v.x, (float)v.y, (float)v.z, (float)v.w};
+}
+
+// embed_norm_kernel / gather_norm_kernel for d <= 4*THREADS, d % 4 == 0: the row stays in registers, one
+// 4-element piece per thread (src: the embedding row of T, or the fp32 hidden row; h_out may be null).
+template <typename T, typename S, int THREADS>
+__global__ __launch_bounds__(THREADS) void row_norm_vec_kernel(const S* __restrict__ src_base,
+                                                               const int32_t* __restrict__ tokens,
+                                                               const int32_t* __restrict__ rows, int d,
+                                                               const float* __restrict__ gain, float eps,
+                                                               float* __restrict__ h_out, T* __restrict__ a) {
+  __shared__ float red[THREADS / 64];
+  const int r = blockIdx.x;
+  const int src_row = tokens ? tokens[rows[r]] : rows[r];
+  const int c = threadIdx.x * 4;
+  const bool live = c < d;
+  f32x4 v = {0.f, 0.f, 0.f, 0.f};
+  if (live) {
+    v = load4(src_base + (size_t)src_row * d + c);
+    if (h_out) store4(h_out + (size_t)r * d + c, v);
+  }
+  const float ss = v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  const float inv = 1.0f / sqrtf(block_sum(ss, red) / (float)d + eps);
+  if (live) store4(a + (size_t)r * d + c, v * inv * *reinterpret_cast<const f32x4*>(gain + c));
+}
+
 template <typename T>
 __global__ __launch_bounds__(kThreads) void gather_norm_kernel(const float* __restrict__ h,
                                                                const int32_t* __restrict__ rows, int d,
@@ -314,6 +344,14 @@ __global__ void rope_table_kernel(float* __restrict__ cos_t, float* __restrict__
 hipError_t launch_embed_norm(int dtype, const void* emb, const int32_t* tokens, const int32_t* idx, int m, int d,
                              const float* gain, float eps, float* h, void* a, hipStream_t st) {
   if (m <= 0) return hipSuccess;
+  if (d % 4 == 0 && d <= 4096) {                  // whole 4-element pieces, the row in one workgroup's registers
+    D2C_DISPATCH(dtype,
+                 hipLaunchKernelGGL((row_norm_vec_kernel<bf16, bf16, 1024>), dim3(m), dim3(1024), 0, st,
+                                    (const bf16*)emb, tokens, idx, d, gain, eps, h, (bf16*)a),
+                 hipLaunchKernelGGL((row_norm_vec_kernel<float, float, 1024>), dim3(m), dim3(1024), 0, st,
+                                    (const float*)emb, tokens, idx, d, gain, eps, h, (float*)a));
+    return hipGetLastError();
+  }
   D2C_DISPATCH(dtype,
                hipLaunchKernelGGL(embed_norm_kernel<bf16>, dim3(m), dim3(kThreads), 0, st, (const bf16*)emb, tokens,
                                   idx, d, gain, eps, h, (bf16*)a),
@@ -353,6 +391,14 @@ hipError_t launch_add_norm(int dtype, float* h, const float* P, int n_splits, si
 hipError_t launch_gather_norm(int dtype, const float* h, const int32_t* rows, int n_rows, int d, const float* gain,
                               float eps, void* a, hipStream_t st) {
   if (n_rows <= 0) return hipSuccess;
+  if (d % 4 == 0 && d <= 4096) {
+    D2C_DISPATCH(dtype,
+                 hipLaunchKernelGGL((row_norm_vec_kernel<bf16, float, 1024>), dim3(n_rows), dim3(1024), 0, st, h,
+                                    (const int32_t*)nullptr, rows, d, gain, eps, (float*)nullptr, (bf16*)a),
+                 hipLaunchKernelGGL((row_norm_vec_kernel<float, float, 1024>), dim3(n_rows), dim3(1024), 0, st, h,
+                                    (const int32_t*)nullptr, rows, d, gain, eps, (float*)nullptr, (float*)a));
+    return hipGetLastError();
+  }
   D2C_DISPATCH(dtype,
                hipLaunchKernelGGL(gather_norm_kernel<bf16>, dim3(n_rows), dim3(kThreads), 0, st, h, rows, d, gain,
                                   eps, (bf16*)a),

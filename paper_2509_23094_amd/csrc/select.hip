@@ -68,6 +68,68 @@ __global__ __launch_bounds__(kConfThreads) void confidence_chunk_kernel(const fl
   }
 }
 
+// The same for chunks of exactly 8192 entries of 16-byte aligned rows (vocab % 4 == 0): a thread keeps its 32
+// entries in registers (eight 16-byte loads issued together), so the row is read once and the kernel is one
+// memory latency long.  Entry order per thread is ascending (piece, then element), as the tie rule needs.
+__global__ __launch_bounds__(kConfThreads) void confidence_chunk_vec_kernel(const float* __restrict__ logits,
+                                                                            int vocab, int n_chunks,
+                                                                            float* __restrict__ part) {
+  constexpr int kChunk = 8192, kPieces = kChunk / (4 * kConfThreads);
+  __shared__ float s_val[kConfThreads / 64];
+  __shared__ int s_idx[kConfThreads / 64];
+  __shared__ float s_sum[kConfThreads / 64];
+  const int row = blockIdx.y, ck = blockIdx.x;
+  const float* x = logits + (size_t)row * vocab;
+  const int lo = ck * kChunk;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  f32x4 val[kPieces];
+#pragma unroll
+  for (int p = 0; p < kPieces; ++p) {
+    const int v = lo + (p * kConfThreads + tid) * 4;
+    val[p] = *reinterpret_cast<const f32x4*>(x + min(v, vocab - 4));       // past the end: re-read, masked below
+  }
+  float best = -INFINITY;
+  int bidx = 0x7fffffff;
+#pragma unroll
+  for (int p = 0; p < kPieces; ++p) {
+    const int v = lo + (p * kConfThreads + tid) * 4;
+    if (v >= vocab) val[p] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (val[p][e] > best) { best = val[p][e]; bidx = v + e; }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ob = __shfl_xor(best, o, kWave);
+    const int oi = __shfl_xor(bidx, o, kWave);
+    if (ob > best || (ob == best && oi < bidx)) { best = ob; bidx = oi; }
+  }
+  if (lane == 0) { s_val[wave] = best; s_idx[wave] = bidx; }
+  __syncthreads();
+  best = s_val[0]; bidx = s_idx[0];
+  for (int w = 1; w < kConfThreads / 64; ++w) {
+    const float ob = s_val[w];
+    const int oi = s_idx[w];
+    if (ob > best || (ob == best && oi < bidx)) { best = ob; bidx = oi; }
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int p = 0; p < kPieces; ++p)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) sum += expf(val[p][e] - best);              // exp(-inf) = 0 past the end
+  sum = wave_sum(sum);
+  if (lane == 0) s_sum[wave] = sum;
+  __syncthreads();
+  if (tid == 0) {
+    float t = 0.f;
+    for (int w = 0; w < kConfThreads / 64; ++w) t += s_sum[w];
+    float* o = part + ((size_t)row * n_chunks + ck) * 3;
+    o[0] = best;
+    o[1] = __int_as_float(bidx);
+    o[2] = t;
+  }
+}
+
 __global__ void confidence_merge_kernel(const float* __restrict__ part, int n_rows, int n_chunks,
                                         const int32_t* __restrict__ pos, const int32_t* __restrict__ via,
                                         float* __restrict__ conf, int32_t* __restrict__ pred) {
@@ -556,8 +618,12 @@ hipError_t launch_confidence(const float* logits, const int32_t* pos, const int3
   int chunk = 8192;
   while ((vocab + chunk - 1) / chunk > kConfMaxChunks) chunk *= 2;
   const int n_chunks = (vocab + chunk - 1) / chunk;
-  hipLaunchKernelGGL(confidence_chunk_kernel, dim3(n_chunks, n_rows), dim3(kConfThreads), 0, st, logits, vocab, chunk,
-                     n_chunks, scratch);
+  if (chunk == 8192 && vocab % 4 == 0 && vocab >= 4 && (uintptr_t)logits % 16 == 0)
+    hipLaunchKernelGGL(confidence_chunk_vec_kernel, dim3(n_chunks, n_rows), dim3(kConfThreads), 0, st, logits, vocab,
+                       n_chunks, scratch);
+  else
+    hipLaunchKernelGGL(confidence_chunk_kernel, dim3(n_chunks, n_rows), dim3(kConfThreads), 0, st, logits, vocab, chunk,
+                       n_chunks, scratch);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(confidence_merge_kernel, dim3((n_rows + 63) / 64), dim3(64), 0, st, scratch, n_rows, n_chunks,
