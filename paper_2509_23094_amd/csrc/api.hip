@@ -821,22 +821,43 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
       }
       if (side != st) D2C_HIP(c, hipStreamWaitEvent(side, c->fwd_done[roll_layers - 1], 0));
     }
-    // Eq. 9 per sequence on the side stream, behind the last head average: v = ones, then the layers in
-    // reverse order, one launch per sequence.  It runs beside the last layer's FFN and the LM head.
+    // Eq. 9 on the side stream, behind the last head average: v = ones, then the layers in reverse order.
+    // It runs beside the last layer's FFN, the LM head and Eq. 1.
     for (int i = 0; i < n_seg; ++i) {
       d2c_seq_state& s = seqs[group[i]];
       if (attention_fwd_emits_probs(c->tun, dt, segs[i].m, s.L))
         D2C_TIMED(c, side, D2C_PROF_ATTN_AVG, 0.0,
                   launch_head_mean(probs_slot(i, 0), c->probs_floats, abar_slot(i, 0), abar_stride, roll_layers,
                                    D.n_heads, segs[i].m, s.L, side));
-      D2C_TIMED(c, side, D2C_PROF_ROLLOUT, 0.0,
-                launch_influence_chain(abar_slot(i, 0), abar_stride, roll_layers, s.s_idx, segs[i].m, s.L,
-                                       c->chain_u, c->chain_g, s.influence, side));
     }
-    if (side != st) {                         // join: the selection needs the influence scores
-      D2C_HIP(c, hipEventRecord(c->side_done, side));
-      D2C_HIP(c, hipStreamWaitEvent(st, c->side_done, 0));
+    {
+      // the chains of as many sequences as fit the scratch buffers together (sized for one sequence with
+      // every row selected) share their three launches
+      const size_t Lm = (size_t)D.max_seq;
+      std::vector<ChainCall> chain;
+      size_t sum_m = 0, sum_mm = 0;
+      auto flush_chain = [&]() -> int {
+        if (chain.empty()) return D2C_OK;
+        D2C_TIMED(c, side, D2C_PROF_ROLLOUT, 0.0,
+                  launch_influence_chain(chain.data(), (int)chain.size(), abar_stride, roll_layers, c->chain_u,
+                                         c->chain_g, side));
+        chain.clear();
+        sum_m = sum_mm = 0;
+        return D2C_OK;
+      };
+      for (int i = 0; i < n_seg; ++i) {
+        d2c_seq_state& s = seqs[group[i]];
+        const size_t m = (size_t)segs[i].m;
+        if (!chain.empty() && ((int)chain.size() == chain_max_batch() || sum_m + m > Lm || sum_mm + m * m > Lm * Lm) &&
+            (rc = flush_chain()))
+          return rc;
+        chain.push_back(ChainCall{abar_slot(i, 0), s.s_idx, segs[i].m, s.L, s.influence});
+        sum_m += m;
+        sum_mm += m * m;
+      }
+      if ((rc = flush_chain())) return rc;
     }
+    if (side != st) D2C_HIP(c, hipEventRecord(c->side_done, side));
     for (int i = 0; i < n_seg; ++i) {
       d2c_seq_state& s = seqs[group[i]];
       const float* hid = c->hidden + (size_t)segs[i].off * d;
@@ -881,6 +902,9 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
       }
     }
     if ((rc = flush())) return rc;
+    // join: the selection is the first consumer of the influence scores, so the chain also runs beside the
+    // LM head and Eq. 1
+    if (side != st) D2C_HIP(c, hipStreamWaitEvent(st, c->side_done, 0));
     // the selections of the group's sequences share launches (one workgroup per sequence)
     std::vector<SelectArgs> sel;
     for (int i = 0; i < n_seg; ++i) {

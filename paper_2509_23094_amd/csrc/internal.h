@@ -148,13 +148,21 @@ hipError_t launch_rollout(const float* attn_avg, const float* c_in, float* c_out
 hipError_t launch_influence(const float* c_block, const int32_t* idx, int m, int L, float* influence,
                             hipStream_t st);
 
-// ---- Eq. 9 as a row-vector chain: c = 1^T W^(n_layers) ... W^(1) with W^(l) built from abar_l (Eq. 6-7).
-// abar: layer l at abar + l * layer_stride, [m, L] floats.  u_scratch: n_layers * m floats, g_scratch:
-// n_layers * m * m floats.  Three launches (the m x m blocks made dense, the sequential m x m part in one
-// workgroup, then all columns in parallel); L <= the selection kernel's limit.
+// ---- Eq. 9 as a row-vector chain: c = 1^T W^(n_layers) ... W^(1) with W^(l) built from abar_l (Eq. 6-7),
+// for up to chain_max_batch() independent sequences at once.  abar: layer l of a sequence at abar + l *
+// layer_stride, [m, L] floats.  u_scratch: n_layers * (sum of m) floats, g_scratch: n_layers * (sum of m * m)
+// floats.  Three launches (the m x m blocks made dense, the sequential m x m part in one workgroup per
+// sequence, then all columns in parallel); L <= the selection kernel's limit.
 // m == 0 or n_layers == 0: all ones.
-hipError_t launch_influence_chain(const float* abar, size_t layer_stride, int n_layers, const int32_t* idx, int m,
-                                  int L, float* u_scratch, float* g_scratch, float* influence, hipStream_t st);
+struct ChainCall {
+  const float* abar;
+  const int32_t* idx;
+  int m, L;
+  float* influence;
+};
+int chain_max_batch();
+hipError_t launch_influence_chain(const ChainCall* calls, int n_calls, size_t layer_stride, int n_layers,
+                                  float* u_scratch, float* g_scratch, hipStream_t st);
 
 // ---- selection
 // Eq. 1 per logits row; the row's position is via ? via[pos[row]] : pos[row]

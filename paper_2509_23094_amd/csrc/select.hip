@@ -8,6 +8,7 @@
 // index first); top-p sorts such keys with a bitonic network in LDS and scans
 // fixed-point masses floor(c * 2^32) in uint64.  Ties always go to the lowest index.
 #include <algorithm>
+#include <cstring>
 
 #include "common.h"
 #include "internal.h"
@@ -228,25 +229,45 @@ __global__ void influence_kernel(const float* __restrict__ c_block, const int32_
 constexpr int kChainThreads = 1024;
 constexpr int kChainMaxLen = 4096;           // = the selection kernel's length limit
 
+// The sequences one chain covers (independent: own A-bar slots, index set and influence vector); their dense
+// blocks and per-layer vectors sit one after the other in the scratch buffers.
+constexpr int kChainMaxSeqs = 8;
+struct ChainSeq {
+  const float* abar;
+  const int32_t* idx;
+  float* influence;
+  int m, L;
+  size_t g_off, u_off;          // in floats: n_layers * (sum of m^2, resp. of m, over the sequences before)
+};
+struct ChainSeqs {
+  ChainSeq seq[kChainMaxSeqs];
+};
+
 // G[l][i, k] = abar[l][i, S_k]: the m x m blocks the sequential part reads, made dense first (all layers in
 // one launch) so that the one workgroup that walks the layers reads consecutive floats.
-__global__ __launch_bounds__(256) void chain_gather_kernel(const float* __restrict__ abar, size_t layer_stride,
-                                                           const int32_t* __restrict__ idx, int m, int L,
-                                                           float* __restrict__ G) {
+__global__ __launch_bounds__(256) void chain_gather_kernel(const ChainSeqs seqs, size_t layer_stride,
+                                                           float* __restrict__ g_scratch) {
+  const ChainSeq& q = seqs.seq[blockIdx.z];
+  const int m = q.m, L = q.L;
   const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
   const size_t mm = (size_t)m * m;
   if (e >= mm) return;
   const int i = (int)(e / m), k = (int)(e - (size_t)i * m);
-  G[(size_t)blockIdx.y * mm + e] = abar[(size_t)blockIdx.y * layer_stride + (size_t)i * L + idx[k]];
+  g_scratch[q.g_off + (size_t)blockIdx.y * mm + e] = q.abar[(size_t)blockIdx.y * layer_stride + (size_t)i * L + q.idx[k]];
 }
 
-// Sequential part, one workgroup: u through the layers in reverse order; writes U[l][i] = u^(l)_i (the
+// Sequential part, one workgroup per sequence: u through the layers in reverse order; writes U[l][i] = u^(l)_i (the
 // vector entering layer l) for the parallel part and c at the positions of S.  Items of 64 entries of S x
 // one of RG row groups keep all 16 waves busy for short S; fixed summation order.
-__global__ __launch_bounds__(kChainThreads) void chain_rows_kernel(const float* __restrict__ G, int n_layers,
-                                                                   const int32_t* __restrict__ idx, int m,
-                                                                   float* __restrict__ U,
-                                                                   float* __restrict__ influence) {
+__global__ __launch_bounds__(kChainThreads) void chain_rows_kernel(const ChainSeqs seqs, int n_layers,
+                                                                   const float* __restrict__ g_scratch,
+                                                                   float* __restrict__ u_scratch) {
+  const ChainSeq& q = seqs.seq[blockIdx.x];
+  const float* __restrict__ G = g_scratch + q.g_off;
+  float* __restrict__ U = u_scratch + q.u_off;
+  const int32_t* __restrict__ idx = q.idx;
+  float* __restrict__ influence = q.influence;
+  const int m = q.m;
   __shared__ float u[2][kChainMaxLen];
   __shared__ float part[kChainMaxLen];                 // [RG][padded m], RG * padded m <= max(padded m, 1024)
   __shared__ int32_t s_idx[kChainMaxLen];
@@ -296,11 +317,16 @@ __global__ __launch_bounds__(kChainThreads) void chain_rows_kernel(const float* 
 // Parallel part: 64 columns per workgroup, its 16 waves take the layers round-robin (wave w: layers w,
 // w + 16, ..), a lane owns one column and adds u^(l)_i A-bar^(l)[i, j] over the rows in order with eight
 // loads in flight; the waves' sums are added in wave order.  Columns inside S are left alone.
-__global__ __launch_bounds__(kChainThreads) void chain_cols_kernel(const float* __restrict__ abar,
-                                                                   size_t layer_stride, int n_layers,
-                                                                   const int32_t* __restrict__ idx, int m, int L,
-                                                                   const float* __restrict__ U,
-                                                                   float* __restrict__ influence) {
+__global__ __launch_bounds__(kChainThreads) void chain_cols_kernel(const ChainSeqs seqs, size_t layer_stride,
+                                                                   int n_layers,
+                                                                   const float* __restrict__ u_scratch) {
+  const ChainSeq& q = seqs.seq[blockIdx.y];
+  const float* __restrict__ abar = q.abar;
+  const int32_t* __restrict__ idx = q.idx;
+  const float* __restrict__ U = u_scratch + q.u_off;
+  float* __restrict__ influence = q.influence;
+  const int m = q.m, L = q.L;
+  if ((int)blockIdx.x * 64 >= L) return;                  // the grid follows the longest sequence
   __shared__ float red[kChainThreads / 64][64];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int col = blockIdx.x * 64 + lane;
@@ -651,24 +677,42 @@ hipError_t launch_influence(const float* c_block, const int32_t* idx, int m, int
   return hipGetLastError();
 }
 
-hipError_t launch_influence_chain(const float* abar, size_t layer_stride, int n_layers, const int32_t* idx, int m,
-                                  int L, float* u_scratch, float* g_scratch, float* influence, hipStream_t st) {
-  if (L <= 0 || L > kChainMaxLen || m < 0 || m > L || n_layers < 0) return hipErrorInvalidValue;
-  if (m == 0 || n_layers == 0) {           // nothing was refreshed: C = I, every c_j = 1
-    hipLaunchKernelGGL(ones_kernel, dim3((L + 255) / 256), dim3(256), 0, st, influence, L);
-    return hipGetLastError();
+int chain_max_batch() { return kChainMaxSeqs; }
+
+hipError_t launch_influence_chain(const ChainCall* calls, int n_calls, size_t layer_stride, int n_layers,
+                                  float* u_scratch, float* g_scratch, hipStream_t st) {
+  if (n_calls <= 0) return hipSuccess;
+  if (n_calls > kChainMaxSeqs || n_layers < 0) return hipErrorInvalidValue;
+  ChainSeqs seqs;
+  std::memset(&seqs, 0, sizeof(seqs));
+  int n = 0, max_m = 0, max_L = 0;
+  size_t g_off = 0, u_off = 0;
+  for (int i = 0; i < n_calls; ++i) {
+    const ChainCall& c = calls[i];
+    if (c.L <= 0 || c.L > kChainMaxLen || c.m < 0 || c.m > c.L) return hipErrorInvalidValue;
+    if (c.m == 0 || n_layers == 0) {         // nothing was refreshed: C = I, every c_j = 1
+      hipLaunchKernelGGL(ones_kernel, dim3((c.L + 255) / 256), dim3(256), 0, st, c.influence, c.L);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+      continue;
+    }
+    seqs.seq[n++] = ChainSeq{c.abar, c.idx, c.influence, c.m, c.L, g_off, u_off};
+    g_off += (size_t)n_layers * c.m * c.m;
+    u_off += (size_t)n_layers * c.m;
+    max_m = std::max(max_m, c.m);
+    max_L = std::max(max_L, c.L);
   }
-  const size_t mm = (size_t)m * m;
-  hipLaunchKernelGGL(chain_gather_kernel, dim3((unsigned)((mm + 255) / 256), n_layers), dim3(256), 0, st, abar,
-                     layer_stride, idx, m, L, g_scratch);
+  if (n == 0) return hipSuccess;
+  const size_t mm = (size_t)max_m * max_m;
+  hipLaunchKernelGGL(chain_gather_kernel, dim3((unsigned)((mm + 255) / 256), n_layers, n), dim3(256), 0, st, seqs,
+                     layer_stride, g_scratch);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(chain_rows_kernel, dim3(1), dim3(kChainThreads), 0, st, g_scratch, n_layers, idx, m, u_scratch,
-                     influence);
+  hipLaunchKernelGGL(chain_rows_kernel, dim3(n), dim3(kChainThreads), 0, st, seqs, n_layers, g_scratch, u_scratch);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(chain_cols_kernel, dim3((L + 63) / 64), dim3(kChainThreads), 0, st, abar, layer_stride, n_layers,
-                     idx, m, L, u_scratch, influence);
+  hipLaunchKernelGGL(chain_cols_kernel, dim3((max_L + 63) / 64, n), dim3(kChainThreads), 0, st, seqs, layer_stride,
+                     n_layers, u_scratch);
   return hipGetLastError();
 }
 
