@@ -32,7 +32,7 @@ int d2c_profile_begin(d2c_ctx* ctx);
 int d2c_profile_end(d2c_ctx* ctx, double* ms, int64_t* launches, double* bytes);
 
 /* Launch-shape tunables.  Every context has its own set; two contexts may differ.  Names:
- * projection kernel: "gemm_waves" (waves per workgroup: 4, 6, 8, 10; 0 = chosen by shape together with the
+ * projection kernel: "gemm_waves" (waves per workgroup: 4, 6, 7, 8, 10; 0 = chosen by shape together with the
  * split count), "gemm_max_splits" (1..8), "gemm_target_wgs" (workgroups aimed at where the shape search does
  * not apply), "gemm_nt_big_n", "gemm_wide_tiles" (0/1: 128 x 64 outputs per wave for many bf16 rows),
  * "gemm_wide_mt" (6, 7, 8 row tiles per workgroup of that shape; 0 = by shape),

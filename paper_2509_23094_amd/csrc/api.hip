@@ -24,7 +24,7 @@ bool d2c::set_tunable(Tunables& t, const char* name, int value) {
   else if (!strcmp(name, "gemm_wide_mt")) t.gemm_wide_mt = (value >= 6 && value <= 8) ? value : 0;
   else if (!strcmp(name, "gemm_wide_min_rows")) t.gemm_wide_min_rows = value;
   else if (!strcmp(name, "gemm_tall_chunk")) t.gemm_tall_chunk = value;
-  else if (!strcmp(name, "gemm_waves")) t.gemm_waves = (value == 8 || value == 4 || value == 6 || value == 10) ? value : 0;
+  else if (!strcmp(name, "gemm_waves")) t.gemm_waves = (value == 8 || value == 4 || value == 6 || value == 7 || value == 10) ? value : 0;
   else if (!strcmp(name, "gemm_preshuffle")) t.gemm_preshuffle = value != 0;
   else if (!strcmp(name, "gemm_rot")) t.gemm_rot = value < 0 ? 0 : value;
   else if (!strcmp(name, "attn_tiled_min_m")) t.attn_tiled_min_m = value < 1 ? 1 : value;

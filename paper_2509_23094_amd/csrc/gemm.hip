@@ -374,6 +374,10 @@ hipError_t launch_nt(const GemmPlan& pl, const void* A, int lda, const void* W, 
     if (pl.waves == 8) return launch_mt<T, 1, 8, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
     if (pl.waves == 6) return launch_mt<T, 1, 6, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
     if (pl.waves == 10) return launch_mt<T, 1, 10, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+    if (pl.waves == 7) {
+      if constexpr (MODE != kPreSwiglu) return launch_mt<T, 1, 7, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
+      return hipErrorInvalidValue;
+    }
     return launch_mt<T, 1, 4, MODE>(pl, A, lda, W, ldw, P, ldp, ss, m, N, K, st, act);
   }
   if (pl.nt == 4) {
@@ -439,7 +443,11 @@ GemmPlan plan_gemm(const Tunables& t, int dtype, int m, int N, int K, bool singl
   pl.rot = t.gemm_rot;
   // 8 waves share one activation chunk in LDS: fewer, fatter workgroups (about 1.5 per compute unit) with
   // fewer k splits measured faster than 4-wave groups at every projection shape of the two models
-  pl.waves = wide ? 4 : (t.gemm_waves == 4 || t.gemm_waves == 6 || t.gemm_waves == 10) ? t.gemm_waves : 8;
+  // (7 waves only where no gated epilogue can follow: it pairs neighbouring waves)
+  pl.waves = wide ? 4
+             : (t.gemm_waves == 4 || t.gemm_waves == 6 || t.gemm_waves == 10 || (t.gemm_waves == 7 && !single_split))
+                 ? t.gemm_waves
+                 : 8;
   const int kc = dtype == kBF16 ? 128 : 64;                       // elements per 256-byte chunk
   const int chunks = (K + kc - 1) / kc;
   const int max_splits = single_split ? 1 : t.gemm_max_splits;
@@ -461,8 +469,9 @@ GemmPlan plan_gemm(const Tunables& t, int dtype, int m, int N, int K, bool singl
   constexpr int kUnits = 256;
   if (pl.nt == 1 && pl.row_chunks == 1) {
     double best = 1e30;
-    for (int w : {8, 6, 10}) {                                    // 8 first: ties keep the 8-wave shape
+    for (int w : {8, 6, 10, 7}) {                                 // 8 first: ties keep the 8-wave shape
       if (t.gemm_waves != 0 && w != pl.waves) continue;
+      if (w == 7 && single_split) continue;
       if (pl.mt > 8 && w != 8) continue;                          // the tall chunk fits the registers of 8 waves only
       for (int s = 1; s <= max_splits; s *= 2) {
         const int cps = (chunks + s - 1) / s;

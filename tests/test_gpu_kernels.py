@@ -56,7 +56,7 @@ def test_linear_parity(B, dtype, m, N, K, tunables=None):
     ctx.close()
 
 
-@pytest.mark.parametrize("waves", [4, 6, 8, 10])
+@pytest.mark.parametrize("waves", [4, 6, 7, 8, 10])
 @pytest.mark.parametrize("dtype,m,N,K", [("f32", 37, 250, 132), ("bf16", 70, 1000, 520), ("bf16", 9, 176, 4096)])
 def test_linear_parity_every_workgroup_width(B, waves, dtype, m, N, K):
     """The planner picks 6, 8 or 10 waves per workgroup by shape; here each width (and the 4-wave one) is
@@ -173,7 +173,7 @@ def test_refresh_layer_parity_row_major_weights(B, name):
     _refresh_layer_parity(B, *case, tunables={"gemm_preshuffle": 0})
 
 
-@pytest.mark.parametrize("waves", [6, 10])
+@pytest.mark.parametrize("waves", [6, 7, 10])
 @pytest.mark.parametrize("name", ["C1-f32", "bf16-small", "tiny-f32-odd-ffn"])
 def test_refresh_layer_parity_forced_workgroup_width(B, name, waves):
     """The gated epilogue pairs neighbouring waves: checked for the 6- and 10-wave workgroups on shapes where

@@ -36,7 +36,7 @@ def test_plan_covers_rows_and_contraction_and_keeps_the_kernel_assumptions(dtype
         assert p["k_per_split"] * p["splits"] >= K and p["k_per_split"] * (p["splits"] - 1) < K, where
         assert p["k_per_split"] % elem_per_chunk == 0, where                        # splits start on chunk boundaries
         assert 1 <= p["splits"] <= 8 and (not single or p["splits"] == 1), where
-        assert p["waves"] in (4, 6, 8, 10) and p["col_tiles_per_wave"] in (1, 2, 4), where
+        assert p["waves"] in (4, 6, 7, 8, 10) and p["col_tiles_per_wave"] in (1, 2, 4), where
         cols = 16 * p["col_tiles_per_wave"] * p["waves"]
         assert p["workgroups"] == -(-N // cols) * p["splits"] * p["row_chunks"], where
         if p["col_tiles_per_wave"] == 4:
@@ -76,6 +76,10 @@ def test_plan_at_the_benchmark_shapes():
     gu = _plan("bf16", 69, 37888, 3584, True)
     assert (gu["workgroups"], gu["waves"], gu["splits"]) == (237, 10, 1)
     assert _plan("bf16", 69, 4608, 3584)["workgroups"] == 252
+    # 3584 output columns: 7-wave workgroups (112 columns) make 32 column blocks x 8 splits = one full round
+    dn = _plan("bf16", 69, 3584, 18944)
+    assert (dn["waves"], dn["splits"], dn["workgroups"]) == (7, 8, 256)
+    assert _plan("bf16", 69, 37888, 3584, True)["waves"] != 7        # the gated epilogue pairs neighbouring waves
     # row-count regimes
     assert _plan("bf16", 150, 12288, 4096)["row_tiles"] == 10 and _plan("bf16", 185, 12288, 4096)["row_tiles"] == 12
     p = _plan("bf16", 200, 12288, 4096)
