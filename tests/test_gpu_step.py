@@ -287,6 +287,19 @@ def test_step_bf16_long_sequence_few_rows(B):
     _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=3)
 
 
+def test_step_at_the_maximum_length(B):
+    """L = 4096, the longest sequence the selection and the rollout chain take: step 0 over all 4096 rows
+    (the dense chain blocks at their largest) and two decode steps, against the oracle's literal L x L
+    rollout.  One more position is refused at d2c_init."""
+    wd = W.ModelDims(2, 256, 4, 2, 64, 512, 512, dtype="bf16")
+    su = W.DecodeSetup(4096 - 64, 64, 32, 1, k=16, p=0.02)
+    mdl = W.model_weights(wd, 13)
+    _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=2)
+    with pytest.raises(B.D2CError) as err:
+        B.Context(wd, mdl, 4097)
+    assert err.value.code == -4                      # D2C_ESHAPE
+
+
 def test_step_batch_of_ragged_sequences(B):
     """Two independent sequences of different length in one d2c_step call equal two separate calls."""
     wd = W.ModelDims(2, 256, 4, 4, 64, 688, 512, dtype="bf16")
