@@ -228,6 +228,7 @@ __global__ void influence_kernel(const float* __restrict__ c_block, const int32_
 // so the sequential part touches m^2 numbers per layer and the m L part is one fully parallel launch.
 constexpr int kChainThreads = 1024;
 constexpr int kChainMaxLen = 4096;           // = the selection kernel's length limit
+constexpr int kChainSpreadMinRows = 512;     // from this many rows on the sequential part runs as a launch per layer
 
 // The sequences one chain covers (independent: own A-bar slots, index set and influence vector); their dense
 // blocks and per-layer vectors sit one after the other in the scratch buffers.
@@ -312,6 +313,49 @@ __global__ __launch_bounds__(kChainThreads) void chain_rows_kernel(const ChainSe
     cur ^= 1;
   }
   for (int k = tid; k < m; k += kChainThreads) influence[s_idx[k]] = u[cur][k];
+}
+
+// The sequential part for long index sets (step 0, select-all): one launch per layer, 64 entries of S per
+// workgroup, so that a layer's m x m product is spread over m / 64 compute units instead of one.  The vector
+// entering layer l is U[l] (ones for the last layer, written here); the result goes to U[l - 1], or, after
+// layer 0, to c at the positions of S.  A lane owns one entry k, the 16 waves split the rows i (wave w: rows
+// w, w + 16, ..), the waves' sums are added in wave order: fixed summation order.
+__global__ __launch_bounds__(kChainThreads) void chain_layer_kernel(const ChainSeqs seqs, int n_layers, int l,
+                                                                    const float* __restrict__ g_scratch,
+                                                                    float* __restrict__ u_scratch) {
+  const ChainSeq& q = seqs.seq[blockIdx.y];
+  const int m = q.m;
+  if ((int)blockIdx.x * 64 >= m) return;                  // the grid follows the longest index set
+  __shared__ float red[kChainThreads / 64][64];
+  const float* __restrict__ G = g_scratch + q.g_off + (size_t)l * m * m;
+  float* __restrict__ U = u_scratch + q.u_off;
+  const float* __restrict__ uin = U + (size_t)l * m;
+  const bool first = l == n_layers - 1;                   // u = ones
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int k = blockIdx.x * 64 + lane;
+  const float* acol = G + min(k, m - 1);
+  constexpr int NW = kChainThreads / 64;
+  float acc = 0.f;
+  int i = wave;
+  for (; i + 7 * NW < m; i += 8 * NW) {
+    float x[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) x[t] = acol[(size_t)(i + t * NW) * m];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc = fmaf(first ? 1.f : uin[i + t * NW], x[t], acc);
+  }
+  for (; i < m; i += NW) acc = fmaf(first ? 1.f : uin[i], acol[(size_t)i * m], acc);
+  red[wave][lane] = acc;
+  __syncthreads();
+  if (wave != 0 || k >= m) return;
+  float sum = 0.f;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) sum += red[w][lane];
+  const float uk = first ? 1.f : uin[k];
+  const float out = 0.5f * (sum + uk);
+  if (first) U[(size_t)l * m + k] = 1.f;
+  if (l > 0) U[(size_t)(l - 1) * m + k] = out;
+  else q.influence[q.idx[k]] = out;
 }
 
 // Parallel part: 64 columns per workgroup, its 16 waves take the layers round-robin (wave w: layers w,
@@ -708,9 +752,19 @@ hipError_t launch_influence_chain(const ChainCall* calls, int n_calls, size_t la
                      layer_stride, g_scratch);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(chain_rows_kernel, dim3(n), dim3(kChainThreads), 0, st, seqs, n_layers, g_scratch, u_scratch);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (max_m >= kChainSpreadMinRows) {
+    // long index sets: a launch per layer over m / 64 workgroups beats one workgroup walking all layers
+    for (int l = n_layers - 1; l >= 0; --l) {
+      hipLaunchKernelGGL(chain_layer_kernel, dim3((max_m + 63) / 64, n), dim3(kChainThreads), 0, st, seqs, n_layers, l,
+                         g_scratch, u_scratch);
+      e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
+  } else {
+    hipLaunchKernelGGL(chain_rows_kernel, dim3(n), dim3(kChainThreads), 0, st, seqs, n_layers, g_scratch, u_scratch);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   hipLaunchKernelGGL(chain_cols_kernel, dim3((max_L + 63) / 64, n), dim3(kChainThreads), 0, st, seqs, layer_stride,
                      n_layers, u_scratch);
   return hipGetLastError();
