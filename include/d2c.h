@@ -228,7 +228,8 @@ int d2c_influence(d2c_ctx* ctx, const float* rollout, const int32_t* idx, int32_
  * of S_t, selection and unmasking; leaves S_{t+1} in the state and refreshes the
  * host mirrors.  A sequence with n_masked == 0 is skipped.  The sequences are independent (own
  * caches, sets, rollout); they are taken in groups of up to max_batch whose rows share the
- * projection launches, every other kernel runs per sequence. */
+ * projection launches; the other kernels work on each sequence's own slice (several sequences
+ * of a group per launch where the kernel allows it). */
 int d2c_step(d2c_ctx* ctx, const d2c_params* params, d2c_seq_state* seqs, int32_t batch,
              void* stream);
 
