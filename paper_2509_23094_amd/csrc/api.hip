@@ -80,11 +80,11 @@ struct d2c_ctx {
   // d2c_step keeps every layer's head average (per batch slot: [n_layers][max_seq * max_seq]) and turns
   // them into the influence scores by a row-vector chain after the last layer
   float* abar_all = nullptr;
-  // per-head attention rows of the few-row attention launches, [max_batch][n_layers][probs_floats]
-  float* probs_all = nullptr;
+  // per-head attention rows (bf16) of the few-row attention launches, [max_batch][n_layers][probs_elems]
+  uint16_t* probs_all = nullptr;
   float* chain_u = nullptr;     // [n_layers, max_seq]: the chain's per-layer vectors (one sequence at a time)
   float* chain_g = nullptr;     // [n_layers, max_seq * max_seq]: the dense m x m blocks of the chain
-  size_t probs_floats = 0;
+  size_t probs_elems = 0;
   int max_batch = 1;            // sequences whose rows d2c_step projects together
   size_t max_rows = 0;          // max_seq * max_batch: rows the row-count-sized buffers hold
   void* head_a = nullptr;       // T [head_rows, d]
@@ -227,7 +227,7 @@ struct Seg {
   void *k_cache, *v_cache;      // this layer's cache of the sequence
   int L;
   float* abar;                  // [m, L] out: head average of this layer (null = not wanted)
-  float* probs;                 // [H, m, L] out: per-head attention rows written by the attention launch
+  void* probs;                  // bf16 [H, m, L] out: per-head attention rows written by the attention launch
                                 // itself (null = not wanted; only where attention_fwd_emits_probs)
   const float* roll_in;         // rollout block before this layer (ignored at layer 0)
   float* roll_out;              // rollout block after it; null = no rollout update
@@ -453,8 +453,8 @@ int d2c_init_tuned(const d2c_dims* dims, const d2c_weights* w, const d2c_tunable
   if ((rc = ws_alloc(c, &c->roll, Lm * Lm * 4)) ||
       (rc = ws_alloc(c, &c->abar_all, (size_t)c->max_batch * D.n_layers * Lm * Lm * 4)))
     return bail(rc);
-  c->probs_floats = attention_probs_floats(D.dtype, D.n_heads, D.max_seq);
-  if ((rc = ws_alloc(c, &c->probs_all, (size_t)c->max_batch * D.n_layers * c->probs_floats * 4)) ||
+  c->probs_elems = attention_probs_elems(D.dtype, D.n_heads, D.max_seq);
+  if ((rc = ws_alloc(c, &c->probs_all, (size_t)c->max_batch * D.n_layers * c->probs_elems * 2)) ||
       (rc = ws_alloc(c, &c->chain_u, (size_t)D.n_layers * Lm * 4)) ||
       (rc = ws_alloc(c, &c->chain_g, (size_t)D.n_layers * Lm * Lm * 4)))
     return bail(rc);
@@ -763,7 +763,7 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
   const size_t abar_stride = (size_t)D.max_seq * D.max_seq;
   auto abar_slot = [&](int slot, int layer) { return c->abar_all + ((size_t)slot * D.n_layers + layer) * abar_stride; };
   auto probs_slot = [&](int slot, int layer) {
-    return c->probs_all + ((size_t)slot * D.n_layers + layer) * c->probs_floats;
+    return c->probs_all + ((size_t)slot * D.n_layers + layer) * c->probs_elems;
   };
   // sequences are taken in groups of up to max_batch; the rows of a group are projected together
   std::vector<int> group;                       // indices into seqs
@@ -827,7 +827,7 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
       d2c_seq_state& s = seqs[group[i]];
       if (attention_fwd_emits_probs(c->tun, dt, segs[i].m, s.L))
         D2C_TIMED(c, side, D2C_PROF_ATTN_AVG, 0.0,
-                  launch_head_mean(probs_slot(i, 0), c->probs_floats, abar_slot(i, 0), abar_stride, roll_layers,
+                  launch_head_mean(probs_slot(i, 0), c->probs_elems, abar_slot(i, 0), abar_stride, roll_layers,
                                    D.n_heads, segs[i].m, s.L, side));
     }
     {

@@ -17,7 +17,7 @@
 //             values per lane and key) and 4x4 in-register transposes turn them
 //             into the A operand (4+4 keys per lane for one head-dim value).
 //             Writes O (bf16), the log-sum-exp per (head, row) and, up to 1024 keys, the
-//             normalised probability rows of its head (the waves keep their scaled scores
+//             normalised probability rows of its head in bf16 (the waves keep their scaled scores
 //             in registers until the row's log-sum-exp is known).
 //   head mean one launch per step: A-bar of every layer = mean over the heads of those rows.
 //   second pass (more than 1024 keys and too few rows for the tiled kernels): one workgroup per
@@ -141,7 +141,7 @@ template <int DH, int KEEP, int DPARTS>
 __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
     const bf16* __restrict__ q, const bf16* __restrict__ k_cache, const bf16* __restrict__ v_cache, int m, int L,
     int n_heads, int n_kv_heads, float scale, bf16* __restrict__ out, float* __restrict__ lse,
-    float* __restrict__ probs) {
+    bf16* __restrict__ probs) {
   constexpr int NS = DH / 32;     // contraction steps of Q K^T
   constexpr int NB = DH / 64 / DPARTS;     // 64-wide head-dim blocks of the output this workgroup owns
   constexpr int DW = NB * 64;              // its output columns
@@ -304,34 +304,47 @@ __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
   if constexpr (KEEP > 0) {
     if (q0 + r >= m || dpart != 0) return;
     const float e = lse_lds[r];
-    float* prow = probs + ((size_t)head * m + q0 + r) * L;
+    bf16* prow = probs + ((size_t)head * m + q0 + r) * L;
 #pragma unroll
     for (int o = 0; o < 4 * KEEP; ++o) {
       const int key0 = (wave + (o >> 1) * kFwdWaves) * 32 + (o & 1) * 16 + 4 * g;
-      if ((L & 3) == 0) {                       // rows start 16-byte aligned: one store per tile
-        if (key0 < L)
-          __builtin_nontemporal_store(f32x4{__expf(kept[o][0] - e), __expf(kept[o][1] - e), __expf(kept[o][2] - e),
-                                            __expf(kept[o][3] - e)},
-                                      reinterpret_cast<f32x4*>(prow + key0));
+      const bf16x4 pv = {(bf16)__expf(kept[o][0] - e), (bf16)__expf(kept[o][1] - e), (bf16)__expf(kept[o][2] - e),
+                         (bf16)__expf(kept[o][3] - e)};
+      if ((L & 3) == 0) {                       // rows start 8-byte aligned: one store per tile
+        if (key0 < L) __builtin_nontemporal_store(__builtin_bit_cast(u32x2, pv), reinterpret_cast<u32x2*>(prow + key0));
       } else {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-          if (key0 + j < L) prow[key0 + j] = __expf(kept[o][j] - e);    // masked scores are -inf: never stored
+          if (key0 + j < L) prow[key0 + j] = pv[j];                     // masked scores are -inf: never stored
       }
     }
   }
 }
 
-// abar[l][i, j] = mean over the heads of probs[l][h][i, j], heads added in order (one thread per element)
-__global__ __launch_bounds__(kThreads) void head_mean_kernel(const float* __restrict__ probs, size_t probs_layer_stride,
+// abar[l][i, j] = mean over the heads of probs[l][h][i, j], heads added in order.  The probability rows are kept
+// in bf16, the precision in which the second contraction consumed them (and in which the tiled kernels keep
+// theirs).  PIECE = 4: four consecutive elements per thread (element counts that are multiples of 4).
+template <int PIECE>
+__global__ __launch_bounds__(kThreads) void head_mean_kernel(const bf16* __restrict__ probs, size_t probs_layer_stride,
                                                              float* __restrict__ abar, size_t abar_layer_stride,
                                                              int n_heads, size_t n_elems) {
-  const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  const size_t i = ((size_t)blockIdx.x * kThreads + threadIdx.x) * PIECE;
   if (i >= n_elems) return;
-  const float* p = probs + (size_t)blockIdx.y * probs_layer_stride + i;
-  float sum = 0.f;
-  for (int h = 0; h < n_heads; ++h) sum += __builtin_nontemporal_load(p + (size_t)h * n_elems);   // read once
-  abar[(size_t)blockIdx.y * abar_layer_stride + i] = sum * (1.0f / (float)n_heads);
+  const bf16* p = probs + (size_t)blockIdx.y * probs_layer_stride + i;
+  const float inv_h = 1.0f / (float)n_heads;
+  if constexpr (PIECE == 4) {
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    for (int h = 0; h < n_heads; ++h) {                                          // read once: past the L2
+      const u32x2 raw = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p + (size_t)h * n_elems));
+      const bf16x4 v = __builtin_bit_cast(bf16x4, raw);
+      sum += f32x4{(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
+    }
+    *reinterpret_cast<f32x4*>(abar + (size_t)blockIdx.y * abar_layer_stride + i) = sum * inv_h;
+  } else {
+    float sum = 0.f;
+    for (int h = 0; h < n_heads; ++h) sum += (float)p[(size_t)h * n_elems];
+    abar[(size_t)blockIdx.y * abar_layer_stride + i] = sum * inv_h;
+  }
 }
 
 // Pass 2: one workgroup per (16-query tile, 16-key tile); its 4 waves split the heads (wave w takes
@@ -475,7 +488,7 @@ __global__ __launch_bounds__(kThreads) void attn_avg_f32_kernel(const float* __r
 
 template <int DH>
 hipError_t launch_fwd_bf16(const void* q, const void* k_cache, const void* v_cache, int m, int L, int n_heads,
-                           int n_kv_heads, void* out, float* lse, float* probs, hipStream_t st) {
+                           int n_kv_heads, void* out, float* lse, bf16* probs, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)DH);
   // split the output columns over two workgroups when that still fits one round of workgroups on the chip
   constexpr int kUnits = 256;
@@ -519,16 +532,23 @@ bool attention_fwd_emits_probs(const Tunables& t, int dtype, int m, int L) {
   return dtype == kBF16 && m > 0 && !attention_is_tiled(t, dtype, m, L) && m <= kProbsMaxM && L <= kProbsMaxL;
 }
 
-size_t attention_probs_floats(int dtype, int n_heads, int max_L) {
+size_t attention_probs_elems(int dtype, int n_heads, int max_L) {
   return dtype == kBF16 ? (size_t)n_heads * kProbsMaxM * std::min(max_L, kProbsMaxL) : 0;
 }
 
-hipError_t launch_head_mean(const float* probs, size_t probs_layer_stride, float* abar, size_t abar_layer_stride,
+hipError_t launch_head_mean(const void* probs, size_t probs_layer_stride, float* abar, size_t abar_layer_stride,
                             int n_layers, int n_heads, int m, int L, hipStream_t st) {
   if (n_layers <= 0 || m <= 0) return hipSuccess;
   const size_t n = (size_t)m * L;
-  hipLaunchKernelGGL(head_mean_kernel, dim3((unsigned)((n + kThreads - 1) / kThreads), n_layers), dim3(kThreads), 0, st,
-                     probs, probs_layer_stride, abar, abar_layer_stride, n_heads, n);
+  // four elements per thread need 8-byte aligned pieces of the rows and 16-byte aligned pieces of A-bar
+  if (n % 4 == 0 && probs_layer_stride % 4 == 0 && abar_layer_stride % 4 == 0 && (uintptr_t)probs % 8 == 0 &&
+      (uintptr_t)abar % 16 == 0) {
+    hipLaunchKernelGGL(head_mean_kernel<4>, dim3((unsigned)((n / 4 + kThreads - 1) / kThreads), n_layers), dim3(kThreads),
+                       0, st, (const bf16*)probs, probs_layer_stride, abar, abar_layer_stride, n_heads, n);
+  } else {
+    hipLaunchKernelGGL(head_mean_kernel<1>, dim3((unsigned)((n + kThreads - 1) / kThreads), n_layers), dim3(kThreads), 0,
+                       st, (const bf16*)probs, probs_layer_stride, abar, abar_layer_stride, n_heads, n);
+  }
   return hipGetLastError();
 }
 
@@ -546,7 +566,7 @@ bool attention_is_tiled(const Tunables& t, int dtype, int m, int L) {
 
 hipError_t launch_attention_fwd(const Tunables& t, int dtype, const void* q, const void* k_cache, const void* v_cache, int m, int L,
                                 int n_heads, int n_kv_heads, int head_dim, void* out, float* lse, float* scratch,
-                                size_t scratch_floats, hipStream_t st, float* probs, float* tiled_avg) {
+                                size_t scratch_floats, hipStream_t st, void* probs, float* tiled_avg) {
   if (m <= 0) return hipSuccess;
   if (L <= 0 || n_heads % n_kv_heads) return hipErrorInvalidValue;
   if (probs && !attention_fwd_emits_probs(t, dtype, m, L)) return hipErrorInvalidValue;
@@ -557,8 +577,9 @@ hipError_t launch_attention_fwd(const Tunables& t, int dtype, const void* q, con
   if (tiled_avg) return hipErrorInvalidValue;
   if (dtype == kBF16) {
     if (head_dim == 128)
-      return launch_fwd_bf16<128>(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, probs, st);
-    if (head_dim == 64) return launch_fwd_bf16<64>(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, probs, st);
+      return launch_fwd_bf16<128>(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, (bf16*)probs, st);
+    if (head_dim == 64)
+      return launch_fwd_bf16<64>(q, k_cache, v_cache, m, L, n_heads, n_kv_heads, out, lse, (bf16*)probs, st);
     return hipErrorInvalidValue;
   }
   const size_t smem = ((size_t)L + 8) * sizeof(float);

@@ -109,17 +109,17 @@ hipError_t launch_rope_table(float* cos_t, float* sin_t, int max_pos, int head_d
 // scratch: attention_scratch_floats(...) floats, may be null for fp32
 bool attention_is_tiled(const Tunables& t, int dtype, int m, int L);
 size_t attention_scratch_floats(const Tunables& t, int dtype, int max_m, int max_L, int n_heads, int head_dim);
-// probs (optional, only where attention_fwd_emits_probs): float [H, m, L], the normalised attention rows of
+// probs (optional, only where attention_fwd_emits_probs): bf16 [H, m, L], the normalised attention rows of
 // every head, written by the same launch; launch_head_mean turns them into the head average.
 bool attention_fwd_emits_probs(const Tunables& t, int dtype, int m, int L);
-size_t attention_probs_floats(int dtype, int n_heads, int max_L);      // capacity one (layer, sequence) needs
+size_t attention_probs_elems(int dtype, int n_heads, int max_L);       // bf16 elements one (layer, sequence) needs
 // tiled_avg: float [m, L] or null; only read where attention_is_tiled (elsewhere it must be null)
 hipError_t launch_attention_fwd(const Tunables& t, int dtype, const void* q, const void* k_cache, const void* v_cache, int m, int L,
                                 int n_heads, int n_kv_heads, int head_dim, void* out, float* lse, float* scratch,
-                                size_t scratch_floats, hipStream_t st, float* probs = nullptr,
+                                size_t scratch_floats, hipStream_t st, void* probs = nullptr,
                                 float* tiled_avg = nullptr);
 // abar[l] (at abar + l * abar_layer_stride, [m, L]) = mean over heads of probs[l] (at probs + l * stride, [H, m, L])
-hipError_t launch_head_mean(const float* probs, size_t probs_layer_stride, float* abar, size_t abar_layer_stride,
+hipError_t launch_head_mean(const void* probs, size_t probs_layer_stride, float* abar, size_t abar_layer_stride,
                             int n_layers, int n_heads, int m, int L, hipStream_t st);
 // the second launch of the few-row kernels: attn_avg float [m, L] = mean over heads of
 // exp(q k / sqrt(dh) - lse); needs fwd's lse.  Not for attention_is_tiled shapes.
