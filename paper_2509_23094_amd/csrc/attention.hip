@@ -136,7 +136,7 @@ __device__ __forceinline__ bool fwd_map_decode(const FwdMap& f, int n_kv_heads, 
 // DPARTS = 1 or DH / 64: with DPARTS > 1 a (query tile, head) is shared by DPARTS workgroups; each computes all
 // scores (and the same softmax) but accumulates only its 64 output columns, so it pulls all of K and only its
 // part of V through its compute unit: less per workgroup, more workgroups, nothing to merge.  Part 0 writes
-// the log-sum-exp and the probability rows.
+// the log-sum-exp; the probability rows (every part holds all scores) are written in equal shares.
 template <int DH, int KEEP, int DPARTS>
 __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
     const bf16* __restrict__ q, const bf16* __restrict__ k_cache, const bf16* __restrict__ v_cache, int m, int L,
@@ -302,11 +302,12 @@ __global__ __launch_bounds__(kFwdThreads) void attn_fwd_bf16_kernel(
     if (q0 + qi < m) out[(size_t)(q0 + qi) * dq + head * DH + dpart * DW + dcol] = (bf16)osum;
   }
   if constexpr (KEEP > 0) {
-    if (q0 + r >= m || dpart != 0) return;
+    if (q0 + r >= m) return;
     const float e = lse_lds[r];
     bf16* prow = probs + ((size_t)head * m + q0 + r) * L;
 #pragma unroll
     for (int o = 0; o < 4 * KEEP; ++o) {
+      if (o % DPARTS != dpart) continue;        // the workgroups that share this (tile, head) share the rows' stores
       const int key0 = (wave + (o >> 1) * kFwdWaves) * 32 + (o & 1) * 16 + 4 * g;
       const bf16x4 pv = {(bf16)__expf(kept[o][0] - e), (bf16)__expf(kept[o][1] - e), (bf16)__expf(kept[o][2] - e),
                          (bf16)__expf(kept[o][3] - e)};
