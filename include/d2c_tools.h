@@ -41,7 +41,7 @@ int d2c_profile_end(d2c_ctx* ctx, double* ms, int64_t* launches, double* bytes);
  * attention: "attn_tiled_min_m" (bf16 attention switches to the LDS-tiled kernels from this many query rows
  * on), "attn_max_splits" (1..8, key-range splits of one attention launch), "attn_qt", "attn_waves" (4, 8),
  * "attn_target_wgs",
- * "side_stream" (0/1: whether d2c_step runs the head average and the rollout on a second
+ * "side_stream" (0/1, default 0: whether d2c_step runs the head average and the rollout on a second
  * stream). */
 typedef struct {
   const char* name;

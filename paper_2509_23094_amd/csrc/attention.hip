@@ -335,11 +335,20 @@ __global__ __launch_bounds__(kThreads) void head_mean_kernel(const bf16* __restr
   const float inv_h = 1.0f / (float)n_heads;
   if constexpr (PIECE == 4) {
     f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-    for (int h = 0; h < n_heads; ++h) {                                          // read once: past the L2
-      const u32x2 raw = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p + (size_t)h * n_elems));
+    auto add = [&](const u32x2 raw) {
       const bf16x4 v = __builtin_bit_cast(bf16x4, raw);
       sum += f32x4{(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
+    };
+    int h = 0;
+    for (; h + 8 <= n_heads; h += 8) {                     // eight heads' loads in flight; read once: past the L2
+      u32x2 raw[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        raw[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p + (size_t)(h + u) * n_elems));
+#pragma unroll
+      for (int u = 0; u < 8; ++u) add(raw[u]);             // heads in order
     }
+    for (; h < n_heads; ++h) add(__builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p + (size_t)h * n_elems)));
     *reinterpret_cast<f32x4*>(abar + (size_t)blockIdx.y * abar_layer_stride + i) = sum * inv_h;
   } else {
     float sum = 0.f;

@@ -29,7 +29,8 @@ struct Tunables {
   int attn_qt = 0;             // 16-row query tiles per wave in the tiled forward kernel: 1, 2; 0 = by m
   int attn_waves = 0;          // waves per workgroup of the tiled forward kernel: 4, 8; 0 = by m
   int attn_target_wgs = 256;   // split the key range until the forward grid has this many workgroups
-  bool side_stream = true;     // d2c_step: head average + rollout on a second stream
+  bool side_stream = false;    // d2c_step: head average + rollout on a second stream (measured slower: with two
+                               // queues in use every launch of the step takes longer than the overlap saves)
 };
 // name -> field; false for an unknown name
 bool set_tunable(Tunables& t, const char* name, int value);

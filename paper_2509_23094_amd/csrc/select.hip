@@ -228,6 +228,8 @@ __global__ void influence_kernel(const float* __restrict__ c_block, const int32_
 // so the sequential part touches m^2 numbers per layer and the m L part is one fully parallel launch.
 constexpr int kChainThreads = 1024;
 constexpr int kChainMaxLen = 4096;           // = the selection kernel's length limit
+constexpr int kChainFewRows = 128;           // up to this many rows a wave's share of a layer's block fits its registers
+constexpr int kChainFewVals = 16;            // = kChainFewRows / (1024 / 128) rows per wave at most
 constexpr int kChainSpreadMinRows = 512;     // from this many rows on the sequential part runs as a launch per layer
 
 // The sequences one chain covers (independent: own A-bar slots, index set and influence vector); their dense
@@ -282,6 +284,49 @@ __global__ __launch_bounds__(kChainThreads) void chain_rows_kernel(const ChainSe
   const int RG = mp < kChainThreads ? kChainThreads / mp : 1;
   const int n_items = n_cb * RG;
   int cur = 0;
+  if (m <= kChainFewRows) {
+    // Few rows (the decode steps): every wave has at most one item of at most kChainFewVals rows, so its
+    // values of the NEXT layer's block are requested before this layer's sums are exchanged: the chain then
+    // runs at one LDS round trip per layer instead of a memory latency.  Same sums in the same order as below.
+    const bool has_item = wave < n_items;
+    const int cb = wave % n_cb, rg = wave / n_cb;
+    const int k = cb * 64 + lane;
+    const float* acol = G + min(k, m - 1);
+    auto load_layer = [&](float (&x)[kChainFewVals], int l) {
+      const float* a = acol + (size_t)l * m * m;
+#pragma unroll
+      for (int t = 0; t < kChainFewVals; ++t) x[t] = a[(size_t)min(rg + t * RG, m - 1) * m];
+    };
+    float xs[kChainFewVals], xn[kChainFewVals];
+    load_layer(xs, n_layers - 1);
+    for (int l = n_layers - 1; l >= 0; --l) {
+      const float* uin = u[cur];
+      float* uout = u[cur ^ 1];
+      load_layer(xn, max(l - 1, 0));                       // unconditional: the last one re-reads layer 0
+      for (int i = tid; i < m; i += kChainThreads) U[(size_t)l * m + i] = uin[i];
+      if (has_item) {
+        float acc = 0.f;
+#pragma unroll
+        for (int t = 0; t < kChainFewVals; ++t) {
+          const int i = rg + t * RG;
+          if (i < m) acc = fmaf(uin[i], xs[t], acc);
+        }
+        part[rg * mp + k] = acc;
+      }
+      __syncthreads();
+      for (int kk = tid; kk < m; kk += kChainThreads) {
+        float sum = 0.f;
+        for (int g2 = 0; g2 < RG; ++g2) sum += part[g2 * mp + kk];
+        uout[kk] = 0.5f * (sum + uin[kk]);
+      }
+      __syncthreads();
+#pragma unroll
+      for (int t = 0; t < kChainFewVals; ++t) xs[t] = xn[t];
+      cur ^= 1;
+    }
+    for (int kk = tid; kk < m; kk += kChainThreads) influence[s_idx[kk]] = u[cur][kk];
+    return;
+  }
   for (int l = n_layers - 1; l >= 0; --l) {
     const float* a = G + (size_t)l * m * m;
     const float* uin = u[cur];

@@ -259,18 +259,27 @@ def test_step_bf16_small_teacher_forced(B):
     _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=24)
 
 
-def test_step_bf16_small_on_one_stream(B):
-    """The same narrow bf16 model with the second stream switched off: head means, chain and selection
-    all queue behind the projections on the caller's stream."""
+def test_step_bf16_small_on_two_streams(B):
+    """The same narrow bf16 model with the second stream switched on: head means and the rollout chain run
+    beside the last layer's projections and the LM head, and the selection waits for them."""
     wd = W.ModelDims(3, 512, 8, 2, 64, 1408, 2048, dtype="bf16")
     su = W.DecodeSetup(40, 24, 12, 1, k=6, p=0.3)
     mdl = W.model_weights(wd, 3)
-    _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=8, tunables={"side_stream": 0})
+    _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=8, tunables={"side_stream": 1})
+
+
+def test_step_long_sequence_few_rows_on_two_streams(B):
+    """The long-generation regime (second Q K^T launch per layer for the head average) with that launch on the
+    second stream."""
+    wd = W.ModelDims(2, 512, 8, 2, 64, 1024, 1024, dtype="bf16")
+    su = W.DecodeSetup(1040, 64, 32, 1, k=16, p=0.02)
+    mdl = W.model_weights(wd, 9)
+    _teacher_forced(B, wd, mdl, su, oracle_params(su), n_steps=2, tunables={"side_stream": 1})
 
 
 def test_step_bf16_many_rows_per_step(B):
     """A bf16 model whose steps select more than 96 rows (k = 64 masked + half the known tokens): the
-    LDS-tiled attention kernels and the per-layer head average on the second stream inside d2c_step."""
+    LDS-tiled attention kernels, whose finishing launch also writes the head average, inside d2c_step."""
     wd = W.ModelDims(2, 512, 4, 4, 128, 1408, 2048, dtype="bf16")
     su = W.DecodeSetup(160, 96, 96, 2, k=64, p=0.6)
     mdl = W.model_weights(wd, 5)
@@ -280,7 +289,7 @@ def test_step_bf16_many_rows_per_step(B):
 def test_step_bf16_long_sequence_few_rows(B):
     """More than 1024 positions with a few dozen selected rows per step (the long-generation regime): the
     few-row attention kernel cannot keep its scores, so every layer runs the second Q K^T pass for the head
-    average on the second stream; grouped-query geometry (8 query heads on 2 kv heads)."""
+    average; grouped-query geometry (8 query heads on 2 kv heads)."""
     wd = W.ModelDims(2, 512, 8, 2, 64, 1024, 1024, dtype="bf16")
     su = W.DecodeSetup(1040, 64, 32, 1, k=16, p=0.02)
     mdl = W.model_weights(wd, 9)
