@@ -230,7 +230,7 @@ constexpr int kChainThreads = 1024;
 constexpr int kChainMaxLen = 4096;           // = the selection kernel's length limit
 constexpr int kChainFewRows = 128;           // up to this many rows a wave's share of a layer's block fits its registers
 constexpr int kChainFewVals = 16;            // = kChainFewRows / (1024 / 128) rows per wave at most
-constexpr int kChainSpreadMinRows = 512;     // from this many rows on the sequential part runs as a launch per layer
+constexpr int kChainSpreadMinRows = 129;     // from this many rows on the sequential part runs as a launch per layer
 
 // The sequences one chain covers (independent: own A-bar slots, index set and influence vector); their dense
 // blocks and per-layer vectors sit one after the other in the scratch buffers.
@@ -425,12 +425,12 @@ __global__ __launch_bounds__(kChainThreads) void chain_cols_kernel(const ChainSe
     const float* a = acol + (size_t)l * layer_stride;
     const float* ul = U + (size_t)l * m;
     int i = 0;
-    for (; i + 8 <= m; i += 8) {
-      float x[8];
+    for (; i + 16 <= m; i += 16) {                          // sixteen rows' loads in flight
+      float x[16];
 #pragma unroll
-      for (int t = 0; t < 8; ++t) x[t] = a[(size_t)(i + t) * L];
+      for (int t = 0; t < 16; ++t) x[t] = a[(size_t)(i + t) * L];
 #pragma unroll
-      for (int t = 0; t < 8; ++t) acc = fmaf(ul[i + t], x[t], acc);
+      for (int t = 0; t < 16; ++t) acc = fmaf(ul[i + t], x[t], acc);
     }
     for (; i < m; ++i) acc = fmaf(ul[i], a[(size_t)i * L], acc);
   }
