@@ -68,7 +68,7 @@ struct d2c_ctx {
   int64_t ws_bytes = 0;
   float* hidden = nullptr;      // [max_rows, d]
   void* a_norm = nullptr;       // T [max_seq, d]
-  void* q = nullptr;            // T [n_layers, max_seq, d_q]: one slot per layer (read later by the side stream)
+  void* q = nullptr;            // T [n_layers, max_seq, d_q]: one slot per layer (a second stream may read it later)
   void* attn_o = nullptr;       // T [max_seq, d_q]
   void* act = nullptr;          // T [max_seq, F]
   float* lse = nullptr;         // [n_layers, H, max_seq]
@@ -93,9 +93,10 @@ struct d2c_ctx {
   int head_rows = 0;
   float* rope_cos = nullptr;    // [max_seq, head_dim/2]
   float* rope_sin = nullptr;
-  // The head-averaged attention rows and the rollout only feed the selection at the end of a step, so
-  // d2c_step runs them on a second stream beside the projections: fwd_done[l] is recorded on the caller's
-  // stream after layer l's attention, side_done on the side stream after the last rollout update.
+  // The head-averaged attention rows and the rollout only feed the selection at the end of a step.  With
+  // the side_stream tunable on, d2c_step runs them on a second stream beside the projections: fwd_done[l] is
+  // recorded on the caller's stream after layer l's attention, side_done on the side stream after the last
+  // rollout update.  Off (the default: two busy queues slow every launch down) they queue on the caller's.
   hipStream_t side = nullptr;
   std::vector<hipEvent_t> fwd_done;
   hipEvent_t side_done = nullptr;
@@ -821,8 +822,8 @@ int d2c_step(d2c_ctx* c, const d2c_params* p, d2c_seq_state* seqs, int32_t batch
       }
       if (side != st) D2C_HIP(c, hipStreamWaitEvent(side, c->fwd_done[roll_layers - 1], 0));
     }
-    // Eq. 9 on the side stream, behind the last head average: v = ones, then the layers in reverse order.
-    // It runs beside the last layer's FFN, the LM head and Eq. 1.
+    // Eq. 9 behind the last head average: v = ones, then the layers in reverse order.  On the second stream
+    // (if that is on) it runs beside the last layer's FFN, the LM head and Eq. 1.
     for (int i = 0; i < n_seg; ++i) {
       d2c_seq_state& s = seqs[group[i]];
       if (attention_fwd_emits_probs(c->tun, dt, segs[i].m, s.L))
